@@ -1,0 +1,121 @@
+/*
+ * ppo — exact joint partition-and-placement search on one AMD MI355X (gfx950).
+ *
+ * Problem (paper Sec. I, Eq. 2; Sec. III-B, Eq. 3 and the memory rule around Eq. 6):
+ * a model is a chain of L layers; layer i has weight size m[i] and emits a tensor of size t[i].
+ * The chain is cut into k non-empty contiguous segments, segment s = layers [c_s, c_{s+1}) with
+ * 0 = c_0 < c_1 < ... < c_{k-1} < c_k = L, and segment s runs on node order[s]; the k nodes are
+ * all distinct.  Node j holds at most M[j]; nodes a and b are joined by a link of bandwidth B[a][b].
+ *     gamma_s = t[c_s - 1] / B[order[s-1]][order[s]]      s = 1..k-1          (Eq. 3)
+ *     beta    = max_s gamma_s                              (0 when k = 1)      (Eq. 2)
+ * The library returns, per instance, the minimum of beta over every feasible (order, cuts) pair —
+ * the true optimum that the paper's Theorem 1 bounds from below — by evaluating every one of the
+ * k! node orderings with a memory-windowed min-max chain-partition DP.
+ *
+ * Arithmetic (identical in the CPU oracle used by the tests):
+ *     P[0] = 0, P[i+1] = P[i] + (double)m[i], accumulated in index order in binary64;
+ *     segment [i,e) fits node j  iff  P[e] - P[i] <= (double)M[j]     ("within the capacity");
+ *     gamma is ONE IEEE binary32 division, round to nearest even;  min and max are exact.
+ * Uniqueness of the answer:
+ *     order = the optimal ordering of lowest lexicographic rank (identity permutation = rank 0);
+ *     cuts  = among that ordering's feasible cut vectors with bottleneck beta, the one minimising
+ *             c_{k-1}, then c_{k-2}, ..., then c_1.
+ *
+ * Conventions for every entry point
+ *   - All array arguments are DEVICE pointers owned by the caller.  The library reads inputs,
+ *     writes outputs, and keeps no pointer after the work enqueued by the call has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued;
+ *     calls do not wait for it.  Outputs are valid once the stream has been synchronised.
+ *   - Batches: arrays carry n_inst independent instances, row-major, contiguous:
+ *         t, m [n_inst][L]   M [n_inst][k]   B [n_inst][k][k]
+ *   - Return value: 0 on success, a negative PPO_E* code otherwise; on error nothing was enqueued
+ *     by that call (PPO_EHIP excepted: a launch may have failed half-way).  n_inst = 0 succeeds
+ *     and does nothing.
+ *   - Data preconditions, not checked on the device: every value finite; t >= +0 (no negative
+ *     zero), m >= 0, M >= 0; B[a][b] > 0 and bit-identical to B[b][a] for a != b (the element with
+ *     the smaller row index is the one read); the diagonal of B and t[.][L-1] are ignored.
+ *   - Limits: 1 <= k <= L, k <= PPO_MAX_K (so that k! fits 32 bits), L <= PPO_MAX_L.
+ *   - Concurrent calls are allowed when their outputs and workspaces are distinct.
+ */
+#ifndef PPO_H
+#define PPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PPO_OK 0
+#define PPO_EINVAL (-1)   /* null pointer, L < 1, k < 1, k > L, n_inst < 0, bad rank range */
+#define PPO_ETOOBIG (-2)  /* k > PPO_MAX_K or L > PPO_MAX_L */
+#define PPO_EHIP (-3)     /* a HIP call failed; ppo_strerror gives the runtime's text */
+#define PPO_ENOSPC (-4)   /* workspace smaller than ppo_workspace_bytes() */
+
+#define PPO_MAX_K 12
+#define PPO_MAX_L 128
+
+/* Key of an ordering: (IEEE bits of its beta) << 32 | lexicographic rank.  For beta >= +0 the bit
+ * pattern orders like the value, so the unsigned minimum of keys is the lowest beta and, among
+ * equals, the lowest rank.  An all-ones key means "nothing evaluated yet". */
+#define PPO_KEY_NONE 0xFFFFFFFFFFFFFFFFull
+
+int ppo_version(void);
+
+/* Text for a return code (static storage; for PPO_EHIP, the last HIP error seen by this thread). */
+const char *ppo_strerror(int code);
+
+/* Bytes of device scratch that ppo_solve_ws / ppo_prepare need for this shape (0 on bad shape). */
+size_t ppo_workspace_bytes(int L, int k, int n_inst);
+
+/* Whole search: minimum bottleneck latency (Eq. 2 minimised over all orderings and cuts).
+ *   beta_out  [n_inst]        seconds if t is in Mbit and B in Mbps; +inf if no feasible solution
+ *   cuts_out  [n_inst][k-1]   c_1..c_{k-1} (index of the first layer of segments 1..k-1); -1 if infeasible
+ *   order_out [n_inst][k]     node hosting segment s; -1 if infeasible
+ * Allocates its scratch with the stream-ordered allocator and releases it on the same stream.
+ * Equivalent to ppo_prepare, ppo_init_keys, ppo_solve_range over [0, k!), ppo_finalize. */
+int ppo_solve(const float *t, const float *m, int L, const float *M, const float *B, int k, int n_inst,
+              float *beta_out, int32_t *cuts_out, int32_t *order_out, void *stream);
+
+/* Same, with caller-supplied device scratch of at least ppo_workspace_bytes(L,k,n_inst) bytes,
+ * 256-byte aligned.  The scratch may be reused once the stream has passed this call's work. */
+int ppo_solve_ws(const float *t, const float *m, int L, const float *M, const float *B, int k, int n_inst,
+                 float *beta_out, int32_t *cuts_out, int32_t *order_out, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+/* The same search in separate stages, for callers that split the rank range (over time, streams or
+ * devices) or want to time the stages.  All stages of one search share one workspace.
+ *
+ * Stage 1 — per-instance tables (prefix sums of m and the window of legal segment starts per node
+ * and segment end: the memory rule; the quotient t[i]/B[a][b] of Eq. 3 for every link and cut,
+ * reduced to order-preserving 16-bit codes).  Must precede stages 2 and 3 on the stream. */
+int ppo_prepare(const float *t, const float *m, int L, const float *M, const float *B, int k, int n_inst,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Set best_key[0..n_inst) to PPO_KEY_NONE. */
+int ppo_init_keys(uint64_t *best_key, int n_inst, void *stream);
+
+/* Stage 2 — evaluate the orderings with rank in [rank_begin, rank_end) (0 <= begin <= end <= k!) of
+ * every instance, each with its own full DP, and fold them into best_key [n_inst] by unsigned
+ * minimum.  Ranges may be issued in any order, from any number of calls; the result is that of
+ * their union.  L, k, n_inst and workspace must be those given to ppo_prepare. */
+int ppo_solve_range(int L, int k, int n_inst, const void *workspace, size_t workspace_bytes, uint64_t rank_begin,
+                    uint64_t rank_end, uint64_t *best_key, void *stream);
+
+/* Stage 3 — turn best_key into (beta, cuts, order): decodes the winning rank, reruns its DP keeping
+ * every row, and walks back with the cut rule stated at the top.  A key whose beta is +inf (or
+ * PPO_KEY_NONE) gives beta = +inf, cuts = order = -1. */
+int ppo_finalize(int L, int k, int n_inst, const void *workspace, size_t workspace_bytes, const uint64_t *best_key,
+                 float *beta_out, int32_t *cuts_out, int32_t *order_out, void *stream);
+
+/* Diagnostic export: beta of each ordering of ONE instance (t,m [L]; M [k]; B [k][k]) with rank in
+ * [rank_begin, rank_end), written to beta_per_ordering [rank_end - rank_begin].  Same kernels and
+ * arithmetic as the search; allocates and releases its scratch on the stream. */
+int ppo_eval_orderings(const float *t, const float *m, int L, const float *M, const float *B, int k,
+                       uint64_t rank_begin, uint64_t rank_end, float *beta_per_ordering, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPO_H */

@@ -1,0 +1,181 @@
+"""Thin ctypes binding over the C ABI of libppo.so (include/ppo.h), same names as the C entry points.
+
+Argument marshalling only: every step of the search runs in the HIP kernels.  PyTorch supplies
+device memory and the current stream.  There is no CPU fallback: if the library is missing or
+no GPU is present, calls fail loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libppo.so")
+
+PPO_OK, PPO_EINVAL, PPO_ETOOBIG, PPO_EHIP, PPO_ENOSPC = 0, -1, -2, -3, -4
+PPO_MAX_K, PPO_MAX_L = 12, 128
+PPO_KEY_NONE = 0xFFFFFFFFFFFFFFFF
+
+
+class PpoError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"ppo error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libppo.so (built by paper_2210_12219_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2210_12219_amd.build` first")
+        lib = C.CDLL(LIB_PATH)
+        vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
+        inst = [vp, vp, i, vp, vp, i]
+        lib.ppo_version.argtypes = []
+        lib.ppo_strerror.argtypes = [i]
+        lib.ppo_strerror.restype = C.c_char_p
+        lib.ppo_workspace_bytes.argtypes = [i, i, i]
+        lib.ppo_workspace_bytes.restype = sz
+        lib.ppo_solve.argtypes = inst + [i, vp, vp, vp, vp]
+        lib.ppo_solve_ws.argtypes = inst + [i, vp, vp, vp, vp, sz, vp]
+        lib.ppo_prepare.argtypes = inst + [i, vp, sz, vp]
+        lib.ppo_init_keys.argtypes = [vp, i, vp]
+        lib.ppo_solve_range.argtypes = [i, i, i, vp, sz, u64, u64, vp, vp]
+        lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
+        lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("ppo needs a GPU: torch.cuda.is_available() is False")
+    return torch
+
+
+def _check(rc: int):
+    if rc != PPO_OK:
+        raise PpoError(rc, load().ppo_strerror(rc).decode())
+
+
+def _stream(stream):
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(x, dtype):
+    torch = _torch()
+    assert x.is_cuda and x.dtype == dtype and x.is_contiguous(), "expected a contiguous device tensor"
+    return C.c_void_p(x.data_ptr())
+
+
+def _shape(t, m, M, B):
+    n, L = t.shape
+    k = M.shape[1]
+    assert tuple(m.shape) == (n, L) and tuple(M.shape) == (n, k) and tuple(B.shape) == (n, k, k)
+    return n, L, k
+
+
+def ppo_version() -> int:
+    return load().ppo_version()
+
+
+def ppo_strerror(code: int) -> str:
+    return load().ppo_strerror(code).decode()
+
+
+def ppo_workspace_bytes(L: int, k: int, n_inst: int) -> int:
+    return int(load().ppo_workspace_bytes(L, k, n_inst))
+
+
+def to_device(w, device="cuda:0"):
+    """Copy a workloads.Workload's arrays to the GPU; returns (t, m, M, B) float32 tensors."""
+    torch = _torch()
+    return tuple(torch.from_numpy(a).to(device) for a in (w.t, w.m, w.M, w.B))
+
+
+def alloc_outputs(n_inst: int, k: int, device="cuda:0"):
+    torch = _torch()
+    return (torch.empty(n_inst, dtype=torch.float32, device=device),
+            torch.empty((n_inst, max(k - 1, 0)), dtype=torch.int32, device=device),
+            torch.empty((n_inst, k), dtype=torch.int32, device=device))
+
+
+def ppo_solve(t, m, M, B, out=None, workspace=None, stream=None):
+    """beta [n], cuts [n,k-1], order [n,k] for device tensors t,m [n,L], M [n,k], B [n,k,k].
+    Enqueues on the stream and returns without synchronising."""
+    torch = _torch()
+    n, L, k = _shape(t, m, M, B)
+    beta, cuts, order = out if out is not None else alloc_outputs(n, k, t.device)
+    f32, i32 = torch.float32, torch.int32
+    args = [_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, n, _dev(beta, f32),
+            C.c_void_p(cuts.data_ptr()), _dev(order, i32)]
+    if workspace is None:
+        _check(load().ppo_solve(*args, _stream(stream)))
+    else:
+        assert workspace.is_cuda and workspace.dtype == torch.uint8
+        _check(load().ppo_solve_ws(*args, C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    return beta, cuts, order
+
+
+def alloc_workspace(L: int, k: int, n_inst: int, device="cuda:0"):
+    torch = _torch()
+    return torch.empty(max(ppo_workspace_bytes(L, k, n_inst), 1), dtype=torch.uint8, device=device)
+
+
+def ppo_prepare(t, m, M, B, workspace, stream=None):
+    """Stage 1: per-instance tables into workspace (uint8 device tensor)."""
+    torch = _torch()
+    n, L, k = _shape(t, m, M, B)
+    f32 = torch.float32
+    assert workspace.is_cuda and workspace.dtype == torch.uint8
+    _check(load().ppo_prepare(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, n,
+                              C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+
+
+def ppo_init_keys(best_key, stream=None):
+    torch = _torch()
+    assert best_key.dtype == torch.int64 and best_key.is_cuda
+    _check(load().ppo_init_keys(C.c_void_p(best_key.data_ptr()), best_key.numel(), _stream(stream)))
+
+
+def ppo_solve_range(L, k, n_inst, workspace, rank_begin, rank_end, best_key, stream=None):
+    """Stage 2: fold the orderings with rank in [rank_begin, rank_end) into best_key (int64 tensor
+    holding the unsigned 64-bit keys)."""
+    torch = _torch()
+    assert best_key.dtype == torch.int64 and best_key.numel() == n_inst and workspace.dtype == torch.uint8
+    _check(load().ppo_solve_range(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(), int(rank_begin),
+                                  int(rank_end), C.c_void_p(best_key.data_ptr()), _stream(stream)))
+
+
+def ppo_finalize(L, k, n_inst, workspace, best_key, out=None, stream=None):
+    """Stage 3: (beta, cuts, order) from best_key."""
+    torch = _torch()
+    beta, cuts, order = out if out is not None else alloc_outputs(n_inst, k, workspace.device)
+    f32, i32 = torch.float32, torch.int32
+    _check(load().ppo_finalize(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                               C.c_void_p(best_key.data_ptr()), _dev(beta, f32), C.c_void_p(cuts.data_ptr()),
+                               _dev(order, i32), _stream(stream)))
+    return beta, cuts, order
+
+
+def ppo_eval_orderings(t, m, M, B, rank_begin, rank_end, stream=None):
+    """beta of every ordering of ONE instance (t,m [L]; M [k]; B [k,k]) with rank in the range."""
+    torch = _torch()
+    L, k = t.shape[0], M.shape[0]
+    f32 = torch.float32
+    out = torch.empty(int(rank_end - rank_begin), dtype=f32, device=t.device)
+    _check(load().ppo_eval_orderings(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, int(rank_begin),
+                                     int(rank_end), C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def orderings_per_instance(k: int) -> int:
+    return math.factorial(k)

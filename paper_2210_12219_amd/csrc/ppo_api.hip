@@ -1,0 +1,199 @@
+// C ABI of the ppo library (declared in include/ppo.h): argument checks, workspace carving, launches.
+#include <string>
+
+#include "ppo_common.h"
+
+namespace ppo {
+hipError_t launch_precompute(const float*, const float*, const float*, const float*, const Layout&, int, void*,
+                             hipStream_t);
+hipError_t launch_init_keys(uint64_t*, int, hipStream_t);
+hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t, uint64_t*, float*, hipStream_t);
+hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, float*, int32_t*, int32_t*,
+                            hipStream_t);
+}  // namespace ppo
+
+namespace {
+
+thread_local std::string g_hip_error = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char* where) {
+    g_hip_error = std::string("HIP error in ") + where + ": " + hipGetErrorString(e);
+    return PPO_EHIP;
+}
+
+#define PPO_HIP(call, where)                            \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) return hip_fail(e_, where); \
+    } while (0)
+
+int check_shape(int L, int k, int n_inst) {
+    if (L < 1 || k < 1 || k > L || n_inst < 0) return PPO_EINVAL;
+    if (k > PPO_MAX_K || L > PPO_MAX_L) return PPO_ETOOBIG;
+    return PPO_OK;
+}
+
+// One launch covers at most this many instances (grid y dimension).
+constexpr int kInstPerLaunch = 32768;
+
+size_t tables_bytes(const ppo::Layout& y, int n_inst) { return (size_t)y.stride * (size_t)n_inst; }
+
+int run_prepare(const float* t, const float* m, int L, const float* M, const float* B, int k, int n_inst, void* ws,
+                hipStream_t stream) {
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int n = (n_inst - first < kInstPerLaunch) ? n_inst - first : kInstPerLaunch;
+        unsigned char* wsi = static_cast<unsigned char*>(ws) + (size_t)first * y.stride;
+        PPO_HIP(ppo::launch_precompute(t + (size_t)first * L, m + (size_t)first * L, M + (size_t)first * k,
+                                       B + (size_t)first * k * k, y, n, wsi, stream),
+                "precompute launch");
+    }
+    return PPO_OK;
+}
+
+int run_range(int L, int k, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end, uint64_t* best_key,
+              hipStream_t stream) {
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int n = (n_inst - first < kInstPerLaunch) ? n_inst - first : kInstPerLaunch;
+        const unsigned char* wsi = static_cast<const unsigned char*>(ws) + (size_t)first * y.stride;
+        PPO_HIP(ppo::launch_enumerate(y, n, wsi, rank_begin, rank_end, best_key + first, nullptr, stream),
+                "enumerate launch");
+    }
+    return PPO_OK;
+}
+
+int run_finalize(int L, int k, int n_inst, const void* ws, const uint64_t* best_key, float* beta_out,
+                 int32_t* cuts_out, int32_t* order_out, hipStream_t stream) {
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int n = (n_inst - first < kInstPerLaunch) ? n_inst - first : kInstPerLaunch;
+        const unsigned char* wsi = static_cast<const unsigned char*>(ws) + (size_t)first * y.stride;
+        PPO_HIP(ppo::launch_traceback(y, n, wsi, best_key + first, beta_out + first,
+                                      cuts_out + (size_t)first * (k - 1), order_out + (size_t)first * k, stream),
+                "traceback launch");
+    }
+    return PPO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ppo_version(void) { return 100; }
+
+const char* ppo_strerror(int code) {
+    switch (code) {
+        case PPO_OK: return "ok";
+        case PPO_EINVAL: return "invalid argument";
+        case PPO_ETOOBIG: return "k or L beyond the compiled limits";
+        case PPO_EHIP: return g_hip_error.c_str();
+        case PPO_ENOSPC: return "workspace too small";
+        default: return "unknown ppo error code";
+    }
+}
+
+size_t ppo_workspace_bytes(int L, int k, int n_inst) {
+    if (check_shape(L, k, n_inst) != PPO_OK) return 0;
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    // tables of every instance, then one key per instance (used by ppo_solve_ws)
+    return tables_bytes(y, n_inst) + ppo::align_up((size_t)n_inst * sizeof(uint64_t), 256);
+}
+
+int ppo_prepare(const float* t, const float* m, int L, const float* M, const float* B, int k, int n_inst,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !workspace) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    return run_prepare(t, m, L, M, B, k, n_inst, workspace, static_cast<hipStream_t>(stream));
+}
+
+int ppo_init_keys(uint64_t* best_key, int n_inst, void* stream) {
+    if (n_inst < 0) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!best_key) return PPO_EINVAL;
+    PPO_HIP(ppo::launch_init_keys(best_key, n_inst, static_cast<hipStream_t>(stream)), "init_keys launch");
+    return PPO_OK;
+}
+
+int ppo_solve_range(int L, int k, int n_inst, const void* workspace, size_t workspace_bytes, uint64_t rank_begin,
+                    uint64_t rank_end, uint64_t* best_key, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!best_key || !workspace) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key,
+                     static_cast<hipStream_t>(stream));
+}
+
+int ppo_finalize(int L, int k, int n_inst, const void* workspace, size_t workspace_bytes, const uint64_t* best_key,
+                 float* beta_out, int32_t* cuts_out, int32_t* order_out, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!workspace || !best_key || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    return run_finalize(L, k, n_inst, workspace, best_key, beta_out, cuts_out, order_out,
+                        static_cast<hipStream_t>(stream));
+}
+
+int ppo_solve_ws(const float* t, const float* m, int L, const float* M, const float* B, int k, int n_inst,
+                 float* beta_out, int32_t* cuts_out, int32_t* order_out, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_out || !order_out || (k > 1 && !cuts_out) || !workspace) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + tables_bytes(y, n_inst));
+    rc = run_prepare(t, m, L, M, B, k, n_inst, workspace, s);
+    if (rc) return rc;
+    PPO_HIP(ppo::launch_init_keys(keys, n_inst, s), "init_keys launch");
+    rc = run_range(L, k, n_inst, workspace, 0u, ppo::factorial_u32(k), keys, s);
+    if (rc) return rc;
+    return run_finalize(L, k, n_inst, workspace, keys, beta_out, cuts_out, order_out, s);
+}
+
+int ppo_solve(const float* t, const float* m, int L, const float* M, const float* B, int k, int n_inst,
+              float* beta_out, int32_t* cuts_out, int32_t* order_out, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t bytes = ppo_workspace_bytes(L, k, n_inst);
+    void* ws = nullptr;
+    PPO_HIP(hipMallocAsync(&ws, bytes, s), "hipMallocAsync");
+    rc = ppo_solve_ws(t, m, L, M, B, k, n_inst, beta_out, cuts_out, order_out, ws, bytes, stream);
+    hipError_t e = hipFreeAsync(ws, s);
+    if (rc == PPO_OK && e != hipSuccess) rc = hip_fail(e, "hipFreeAsync");
+    return rc;
+}
+
+int ppo_eval_orderings(const float* t, const float* m, int L, const float* M, const float* B, int k,
+                       uint64_t rank_begin, uint64_t rank_end, float* beta_per_ordering, void* stream) {
+    int rc = check_shape(L, k, 1);
+    if (rc) return rc;
+    if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
+    if (rank_begin == rank_end) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_per_ordering) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    void* ws = nullptr;
+    PPO_HIP(hipMallocAsync(&ws, tables_bytes(y, 1), s), "hipMallocAsync");
+    hipError_t e = ppo::launch_precompute(t, m, M, B, y, 1, ws, s);
+    if (e == hipSuccess)
+        e = ppo::launch_enumerate(y, 1, ws, (uint32_t)rank_begin, (uint32_t)rank_end, nullptr, beta_per_ordering, s);
+    if (e != hipSuccess) rc = hip_fail(e, "eval_orderings launch");
+    hipError_t e2 = hipFreeAsync(ws, s);
+    if (rc == PPO_OK && e2 != hipSuccess) rc = hip_fail(e2, "hipFreeAsync");
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Shared declarations of the ppo HIP library: workspace layout, value codes, small device helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ppo.h"
+
+namespace ppo {
+
+// Every latency that can occur in an instance is one of the npairs*(L-1) quotients t[i]/B[a][b]
+// (Eq. 3), or 0 (no link crossed yet), or +inf (infeasible).  The precompute kernel replaces each
+// by a 16-bit code that orders exactly like the value (equal values, equal codes), so the DP can
+// run on 16-bit integers; the winner's code is mapped back to the binary32 quotient afterwards.
+// Codes are also valid positive normal binary16 patterns, which order like unsigned integers.
+constexpr uint32_t kCodeZero = 0x0400u;  // value +0
+constexpr uint32_t kCodeInf = 0x7C00u;   // value +inf
+constexpr uint32_t kInfBits = 0x7F800000u;
+
+__host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Per-instance tables written by the precompute kernel and read by the enumeration and traceback.
+//   lo  [k][L+1] u8   lo[j][e] = first layer i such that layers [i,e) fit on node j (== e: none)
+//   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
+//   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
+struct Layout {
+    int L, k, npairs;
+    uint32_t lo_off, qc_off, dec_off, stride;  // bytes within one instance's slice
+
+    __host__ __device__ static Layout make(int L, int k) {
+        Layout y;
+        y.L = L;
+        y.k = k;
+        y.npairs = k * (k - 1) / 2;
+        size_t off = 0;
+        y.lo_off = (uint32_t)off;
+        off = align_up(off + (size_t)k * (L + 1), 16);
+        y.qc_off = (uint32_t)off;
+        off = align_up(off + (size_t)y.npairs * L * 2, 16);
+        y.dec_off = (uint32_t)off;
+        off = align_up(off + ((size_t)y.npairs * (L - 1) + 2) * 4, 256);
+        y.stride = (uint32_t)off;
+        return y;
+    }
+};
+
+// index of the unordered pair {a,b}, a != b, among the k(k-1)/2 pairs in row-major upper-triangle order
+__host__ __device__ inline int pair_index(int a, int b, int k) {
+    int lo = a < b ? a : b, hi = a < b ? b : a;
+    return lo * k - lo * (lo + 1) / 2 + (hi - lo - 1);
+}
+
+__host__ __device__ inline uint32_t factorial_u32(int n) {
+    uint32_t f = 1;
+    for (int i = 2; i <= n; ++i) f *= (uint32_t)i;
+    return f;
+}
+
+// The permutation of 0..k-1 with lexicographic rank r, packed four bits per position
+// (position p in bits [4p, 4p+4)).  Digit p of r in the factorial number system selects the
+// digit-th smallest node not used by positions 0..p-1.
+__device__ inline uint64_t unrank_packed(uint32_t r, int k) {
+    uint64_t avail = 0xBA9876543210ull;  // nibble j = j-th smallest unused node
+    uint64_t perm = 0;
+    for (int p = 0; p < k; ++p) {
+        uint32_t f = factorial_u32(k - 1 - p);
+        uint32_t d = r / f;
+        r -= d * f;
+        uint32_t sh = 4u * d;
+        uint64_t node = (avail >> sh) & 0xFull;
+        uint64_t low = avail & ((1ull << sh) - 1ull);
+        avail = low | ((avail >> 4) & ~((1ull << sh) - 1ull));
+        perm |= node << (4 * p);
+    }
+    return perm;
+}
+
+__device__ inline int perm_at(uint64_t perm, int p) { return (int)((perm >> (4 * p)) & 0xFull); }
+
+}  // namespace ppo

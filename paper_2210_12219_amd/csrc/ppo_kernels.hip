@@ -1,0 +1,285 @@
+// HIP kernels of the exact partition-and-placement search for gfx950:
+//   precompute  per instance: prefix sums, memory windows, latency quotients and their order codes
+//   enumerate   per ordering: unrank, memory-windowed min-max chain DP, packed-key argmin
+//   traceback   per instance: rerun the winner's DP keeping all rows, recover the cuts
+#include "ppo_common.h"
+
+namespace ppo {
+
+// ---------------------------------------------------------------------------------------------
+// precompute: one block per instance.
+//   P[i+1] = P[i] + (double)m[i] in index order (binary64);
+//   lo[j][e] = smallest i with P[e] - P[i] <= (double)M[j]   (memory rule of Sec. III-B, "within
+//              the capacity"); legal segment starts for a segment ending before layer e on node j
+//              are i in [lo, e-1], one contiguous run because P is non-decreasing;
+//   q[p][i]  = t[i] / B[a][b], one binary32 division rounded to nearest (Eq. 3);
+//   code     = kCodeZero + 1 + #{quotients of the instance strictly below q}.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPreThreads = 1024;
+constexpr int kMaxQuot = (PPO_MAX_K * (PPO_MAX_K - 1) / 2) * (PPO_MAX_L - 1);
+
+__global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __restrict__ t,
+                                                                 const float* __restrict__ m,
+                                                                 const float* __restrict__ M,
+                                                                 const float* __restrict__ B, Layout y,
+                                                                 unsigned char* __restrict__ ws) {
+    __shared__ double P[PPO_MAX_L + 1];
+    __shared__ float qv[kMaxQuot];
+    const int L = y.L, k = y.k, inst = blockIdx.x, tid = threadIdx.x;
+    const float* ti = t + (size_t)inst * L;
+    const float* mi = m + (size_t)inst * L;
+    const float* Mi = M + (size_t)inst * k;
+    const float* Bi = B + (size_t)inst * k * k;
+    unsigned char* base = ws + (size_t)inst * y.stride;
+    unsigned char* lo = base + y.lo_off;
+    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
+    float* dec = reinterpret_cast<float*>(base + y.dec_off);
+
+    if (tid == 0) {
+        double acc = 0.0;
+        P[0] = 0.0;
+        for (int i = 0; i < L; ++i) {
+            acc = acc + (double)mi[i];
+            P[i + 1] = acc;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < k * (L + 1); idx += kPreThreads) {
+        int j = idx / (L + 1), e = idx - j * (L + 1);
+        double cap = (double)Mi[j];
+        int i = 0;
+        while (i < e && (P[e] - P[i]) > cap) ++i;
+        lo[idx] = (unsigned char)i;
+    }
+    const int nq = y.npairs * (L - 1);
+    for (int idx = tid; idx < nq; idx += kPreThreads) {
+        int p = idx / (L - 1), i = idx - p * (L - 1);
+        int a = 0, rem = p;
+        while (rem >= k - 1 - a) { rem -= k - 1 - a; ++a; }
+        int b = a + 1 + rem;
+        qv[idx] = __fdiv_rn(ti[i], Bi[a * k + b]);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nq; idx += kPreThreads) {
+        int p = idx / (L - 1), i = idx - p * (L - 1);
+        float x = qv[idx];
+        int below = 0;
+        for (int j = 0; j < nq; ++j) below += (qv[j] < x) ? 1 : 0;
+        qc[p * L + i] = (uint16_t)(kCodeZero + 1 + below);
+        dec[1 + below] = x;
+    }
+    if (tid == 0) dec[0] = 0.0f;
+}
+
+__global__ void init_keys_kernel(unsigned long long* keys, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) keys[i] = PPO_KEY_NONE;
+}
+
+// ---------------------------------------------------------------------------------------------
+// enumerate (generic variant): one ordering per lane, rank = lexicographic index.
+// The lane's DP row lives in LDS as 16-bit codes, laid out [position][thread] so that a wave
+// reading one position touches consecutive addresses.  Row s is computed in place:
+//   g[i]   = max(D_{s-1}[i], q[{pi_{s-1},pi_s}][i-1])                       i = s .. L-k+s
+//   D_s[e] = min_{i in [max(s, lo[pi_s][e]), e-1]} g[i]                      e = L-k+1+s .. s+1 (downwards)
+// so that position e is overwritten only after every e' > e has read the g values below it.
+// beta(pi) = D_{k-1}[L];  key = bits(beta) << 32 | rank;  wave minimum, then one atomicMin per wave.
+// ---------------------------------------------------------------------------------------------
+constexpr int kEnumThreads = 256;
+
+__device__ inline uint32_t dp_one_ordering(uint64_t perm, int L, int k, const unsigned char* lo_s,
+                                           const uint16_t* qc_s, uint16_t* row /* [L+1][kEnumThreads], + tid */) {
+    const int n0 = perm_at(perm, 0);
+    const unsigned char* lo0 = lo_s + n0 * (L + 1);
+    for (int e = 1; e <= L - (k - 1); ++e) row[e * kEnumThreads] = (lo0[e] == 0) ? (uint16_t)kCodeZero : (uint16_t)kCodeInf;
+    int prev = n0;
+    for (int s = 1; s < k; ++s) {
+        const int node = perm_at(perm, s);
+        const uint16_t* q = qc_s + pair_index(prev, node, k) * L;
+        const unsigned char* lo = lo_s + node * (L + 1);
+        for (int i = s; i <= L - k + s; ++i) {
+            uint16_t d = row[i * kEnumThreads], g = q[i - 1];
+            row[i * kEnumThreads] = d > g ? d : g;
+        }
+        for (int e = L - k + 1 + s; e >= s + 1; --e) {
+            int first = lo[e];
+            first = first > s ? first : s;
+            uint32_t acc = kCodeInf;
+            for (int i = first; i < e; ++i) {
+                uint32_t g = row[i * kEnumThreads];
+                acc = g < acc ? g : acc;
+            }
+            row[e * kEnumThreads] = (uint16_t)acc;
+        }
+        prev = node;
+    }
+    return row[L * kEnumThreads];
+}
+
+__device__ inline unsigned long long wave_min_u64(unsigned long long v) {
+    for (int off = 32; off >= 1; off >>= 1) {
+        unsigned long long o = __shfl_xor(v, off, 64);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+template <bool EXPORT>
+__global__ __launch_bounds__(kEnumThreads) void enumerate_kernel(Layout y, const unsigned char* __restrict__ ws,
+                                                                 uint32_t rank_begin, uint32_t rank_end,
+                                                                 unsigned long long* __restrict__ best_key,
+                                                                 float* __restrict__ beta_export) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x;
+    const unsigned char* base = ws + (size_t)inst * y.stride;
+    const float* dec = reinterpret_cast<const float*>(base + y.dec_off);
+    // stage the instance's tables (lo, then qc) into LDS; they are contiguous in the workspace
+    const uint32_t table_bytes = y.dec_off;
+    for (uint32_t i = tid * 16u; i < table_bytes; i += kEnumThreads * 16u)
+        *reinterpret_cast<uint4*>(smem + i) = *reinterpret_cast<const uint4*>(base + i);
+    __syncthreads();
+    const unsigned char* lo_s = smem + y.lo_off;
+    const uint16_t* qc_s = reinterpret_cast<const uint16_t*>(smem + y.qc_off);
+    uint16_t* row = reinterpret_cast<uint16_t*>(smem + table_bytes) + tid;
+
+    unsigned long long best = PPO_KEY_NONE;
+    const uint32_t span = rank_end - rank_begin;
+    for (uint32_t off = blockIdx.x * kEnumThreads + tid; off < span; off += gridDim.x * kEnumThreads) {
+        const uint32_t r = rank_begin + off;
+        const uint64_t perm = unrank_packed(r, k);
+        const uint32_t code = dp_one_ordering(perm, L, k, lo_s, qc_s, row);
+        const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+        if (EXPORT) beta_export[off] = __uint_as_float(bits);
+        const unsigned long long key = ((unsigned long long)bits << 32) | r;
+        best = key < best ? key : best;
+    }
+    if (!EXPORT) {
+        best = wave_min_u64(best);
+        if ((tid & 63) == 0 && best != PPO_KEY_NONE) atomicMin(best_key + inst, best);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// traceback: one block per instance, lane 0 works.  Decodes the winning rank, reruns its DP with all
+// k rows kept, then walks back from e = L: for s = k-1 .. 1 the cut c_s is the smallest legal start
+// i whose candidate max(D_{s-1}[i], q[i-1]) does not exceed beta, and e <- c_s.  Because
+// D_{s-1}[i] <= beta exactly when some feasible prefix ends at i within the bottleneck, this yields
+// the cut vector that minimises c_{k-1}, then c_{k-2}, ..., then c_1.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned char* __restrict__ ws,
+                                                       const unsigned long long* __restrict__ best_key,
+                                                       float* __restrict__ beta_out, int32_t* __restrict__ cuts_out,
+                                                       int32_t* __restrict__ order_out) {
+    __shared__ uint16_t rows[PPO_MAX_K][PPO_MAX_L + 1];
+    const int L = y.L, k = y.k, inst = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    const unsigned char* base = ws + (size_t)inst * y.stride;
+    const unsigned char* lo_t = base + y.lo_off;
+    const uint16_t* qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
+    const float* dec = reinterpret_cast<const float*>(base + y.dec_off);
+    int32_t* cuts = cuts_out + (size_t)inst * (k - 1);
+    int32_t* order = order_out + (size_t)inst * k;
+    const unsigned long long key = best_key[inst];
+    const uint32_t bits = (uint32_t)(key >> 32), r = (uint32_t)(key & 0xFFFFFFFFull);
+    if (key == PPO_KEY_NONE || bits >= kInfBits || r >= factorial_u32(k)) {
+        beta_out[inst] = __uint_as_float(kInfBits);
+        for (int s = 0; s < k; ++s) order[s] = -1;
+        for (int s = 0; s + 1 < k; ++s) cuts[s] = -1;
+        return;
+    }
+    const uint64_t perm = unrank_packed(r, k);
+    for (int s = 0; s < k; ++s)
+        for (int e = 0; e <= L; ++e) rows[s][e] = (uint16_t)kCodeInf;
+    {
+        const unsigned char* lo0 = lo_t + perm_at(perm, 0) * (L + 1);
+        for (int e = 1; e <= L - (k - 1); ++e)
+            if (lo0[e] == 0) rows[0][e] = (uint16_t)kCodeZero;
+    }
+    for (int s = 1; s < k; ++s) {
+        const int node = perm_at(perm, s);
+        const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), node, k) * L;
+        const unsigned char* lo = lo_t + node * (L + 1);
+        for (int e = s + 1; e <= L - (k - 1 - s); ++e) {
+            int first = lo[e] > s ? lo[e] : s;
+            uint32_t acc = kCodeInf;
+            for (int i = first; i < e; ++i) {
+                uint32_t d = rows[s - 1][i], g = q[i - 1];
+                uint32_t c = d > g ? d : g;
+                acc = c < acc ? c : acc;
+            }
+            rows[s][e] = (uint16_t)acc;
+        }
+    }
+    const uint32_t beta_code = rows[k - 1][L];
+    beta_out[inst] = (beta_code >= kCodeInf) ? __uint_as_float(kInfBits) : dec[beta_code - kCodeZero];
+    for (int s = 0; s < k; ++s) order[s] = perm_at(perm, s);
+    int e = L;
+    for (int s = k - 1; s >= 1; --s) {
+        const int node = perm_at(perm, s);
+        const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), node, k) * L;
+        const unsigned char* lo = lo_t + node * (L + 1);
+        int first = lo[e] > s ? lo[e] : s;
+        int chosen = -1;
+        for (int i = first; i < e; ++i) {
+            uint32_t d = rows[s - 1][i], g = q[i - 1];
+            uint32_t c = d > g ? d : g;
+            if (c <= beta_code) { chosen = i; break; }
+        }
+        cuts[s - 1] = chosen;
+        if (chosen < 0) break;  // cannot happen for a key produced by the enumeration
+        e = chosen;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers (called from the C ABI)
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_precompute(const float* t, const float* m, const float* M, const float* B, const Layout& y,
+                             int n_inst, void* ws, hipStream_t stream) {
+    hipLaunchKernelGGL(precompute_kernel, dim3(n_inst), dim3(kPreThreads), 0, stream, t, m, M, B, y,
+                       static_cast<unsigned char*>(ws));
+    return hipGetLastError();
+}
+
+hipError_t launch_init_keys(uint64_t* keys, int n_inst, hipStream_t stream) {
+    hipLaunchKernelGGL(init_keys_kernel, dim3((n_inst + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<unsigned long long*>(keys), n_inst);
+    return hipGetLastError();
+}
+
+size_t enumerate_lds_bytes(const Layout& y) { return (size_t)y.dec_off + (size_t)(y.L + 1) * kEnumThreads * 2; }
+
+hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
+                            uint64_t* best_key, float* beta_export, hipStream_t stream) {
+    const uint32_t span = rank_end - rank_begin;
+    if (span == 0 || n_inst == 0) return hipSuccess;
+    const size_t lds = enumerate_lds_bytes(y);
+    uint32_t gx = (span + kEnumThreads - 1) / kEnumThreads;
+    if (gx > 4096u) gx = 4096u;
+    hipError_t e;
+    if (beta_export) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(enumerate_kernel<true>, dim3(gx, n_inst), dim3(kEnumThreads), lds, stream, y,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end,
+                           reinterpret_cast<unsigned long long*>(best_key), beta_export);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(enumerate_kernel<false>, dim3(gx, n_inst), dim3(kEnumThreads), lds, stream, y,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end,
+                           reinterpret_cast<unsigned long long*>(best_key), beta_export);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_traceback(const Layout& y, int n_inst, const void* ws, const uint64_t* best_key, float* beta_out,
+                            int32_t* cuts_out, int32_t* order_out, hipStream_t stream) {
+    hipLaunchKernelGGL(traceback_kernel, dim3(n_inst), dim3(64), 0, stream, y, static_cast<const unsigned char*>(ws),
+                       reinterpret_cast<const unsigned long long*>(best_key), beta_out, cuts_out, order_out);
+    return hipGetLastError();
+}
+
+}  // namespace ppo

@@ -1,0 +1,84 @@
+"""The C-ABI library: it loads, exports every entry point the header declares, and rejects bad
+arguments before touching the GPU (so these run without one)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2210_12219_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2210_12219_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ppo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ppo_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"ppo_solve", "ppo_solve_ws", "ppo_prepare", "ppo_solve_range", "ppo_finalize", "ppo_eval_orderings", "ppo_init_keys",
+            "ppo_workspace_bytes", "ppo_strerror", "ppo_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_messages(lib):
+    assert lib.ppo_version() >= 100
+    assert binding.ppo_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert binding.ppo_strerror(code)
+
+
+def test_workspace_bytes(lib):
+    assert binding.ppo_workspace_bytes(0, 1, 1) == 0
+    assert binding.ppo_workspace_bytes(4, 5, 1) == 0          # k > L
+    assert binding.ppo_workspace_bytes(129, 4, 1) == 0        # L too large
+    assert binding.ppo_workspace_bytes(100, 13, 1) == 0       # k too large
+    one = binding.ppo_workspace_bytes(100, 10, 1)
+    many = binding.ppo_workspace_bytes(100, 10, 64)
+    assert one >= 10 * 101 + 45 * 100 * 2 + (45 * 99 + 2) * 4
+    assert many >= 64 * (one - 256) and many % 256 == 0
+
+
+def test_bad_arguments_are_refused_without_a_gpu(lib):
+    p = C.c_void_p(0x1000)     # never dereferenced: every call below must fail on its scalars first
+    null = C.c_void_p(0)
+    s = C.c_void_p(0)
+    # shape errors
+    assert lib.ppo_solve(p, p, 0, p, p, 1, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 4, p, p, 5, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 4, p, p, 0, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 4, p, p, 2, -1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 129, p, p, 2, 1, p, p, p, s) == binding.PPO_ETOOBIG
+    assert lib.ppo_solve(p, p, 100, p, p, 13, 1, p, p, p, s) == binding.PPO_ETOOBIG
+    # null pointers
+    assert lib.ppo_solve(null, p, 4, p, p, 2, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 4, p, p, 2, 1, null, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve(p, p, 4, p, p, 2, 1, p, null, p, s) == binding.PPO_EINVAL
+    # empty batch is a successful no-op, even with null pointers
+    assert lib.ppo_solve(null, null, 4, null, null, 2, 0, null, null, null, s) == binding.PPO_OK
+    assert lib.ppo_init_keys(null, 0, s) == binding.PPO_OK
+    assert lib.ppo_init_keys(null, 3, s) == binding.PPO_EINVAL
+    # workspace too small / missing
+    assert lib.ppo_solve_ws(p, p, 4, p, p, 2, 1, p, p, p, p, 16, s) == binding.PPO_ENOSPC
+    assert lib.ppo_solve_ws(p, p, 4, p, p, 2, 1, p, p, p, null, 1 << 20, s) == binding.PPO_EINVAL
+    # rank ranges
+    assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 5, 4, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 0, 7, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range(4, 3, 1, p, 16, 0, 6, p, s) == binding.PPO_ENOSPC
+    assert lib.ppo_prepare(p, p, 4, p, p, 3, 1, p, 16, s) == binding.PPO_ENOSPC
+    assert lib.ppo_prepare(p, null, 4, p, p, 3, 1, p, 1 << 20, s) == binding.PPO_EINVAL
+    assert lib.ppo_eval_orderings(p, p, 4, p, p, 3, 0, 7, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_eval_orderings(p, p, 4, p, p, 3, 2, 2, p, s) == binding.PPO_OK   # empty range
+    assert lib.ppo_finalize(4, 2, 1, p, 1 << 20, null, p, p, p, s) == binding.PPO_EINVAL

@@ -1,0 +1,214 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, bit for bit: beta, cuts, ordering."""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import ppo_oracle as O
+from paper_2210_12219_amd import workloads as W
+
+
+@pytest.fixture(scope="module")
+def ppo():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2210_12219_amd import binding
+    binding.load()
+    return binding
+
+
+def bits(x):
+    return np.asarray(x, dtype=np.float32).view(np.uint32)
+
+
+def gpu_solve(ppo, w, **kw):
+    import torch
+    dev = ppo.to_device(w)
+    beta, cuts, order = ppo.ppo_solve(*dev, **kw)
+    torch.cuda.synchronize()
+    return beta.cpu().numpy(), cuts.cpu().numpy(), order.cpu().numpy()
+
+
+def assert_same(got, ref, what=""):
+    bad = np.nonzero(bits(got[0]) != bits(ref[0]))[0]
+    assert bad.size == 0, f"{what}: beta differs at instances {bad[:8]}: {got[0][bad[:4]]} vs {ref[0][bad[:4]]}"
+    assert np.array_equal(got[2], ref[2]), f"{what}: ordering differs"
+    assert np.array_equal(got[1], ref[1]), f"{what}: cuts differ"
+
+
+def test_worked_example(ppo):
+    """Sec. I: 10.2 Mbit over 6 Mbps, about 1.7 s; binary32 quotient 0x3FD99999."""
+    w = W.Workload("ex", 2, 2, 1, 0, np.array([[10.2, 3.0]], np.float32), np.ones((1, 2), np.float32),
+                   np.full((1, 2), 5.0, np.float32), np.array([[[0, 6], [6, 0]]], np.float32))
+    beta, cuts, order = gpu_solve(ppo, w)
+    assert int(bits(beta)[0]) == 0x3FD99999 and cuts.tolist() == [[1]] and order.tolist() == [[0, 1]]
+
+
+def test_tiny_workload_against_brute_force_and_exhaustive(ppo):
+    w = W.tiny()
+    got = gpu_solve(ppo, w)
+    assert_same(got, O.bruteforce(w.t, w.m, w.M, w.B), "tiny vs brute force")
+    assert_same(got, O.exhaustive(w.t, w.m, w.M, w.B)[:3], "tiny vs exhaustive")
+    assert np.isinf(got[0]).sum() > 10          # the workload does contain infeasible instances
+
+
+def test_per_ordering_beta_tiny_and_resnet(ppo):
+    import torch
+    for w, n in ((W.tiny(), 24), (W.resnet50_shaped(), 6)):
+        dev = ppo.to_device(w.take(n))
+        kf = math.factorial(w.k)
+        for j in range(n):
+            got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], 0, kf)
+            torch.cuda.synchronize()
+            ref, _ = O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], 0, kf)
+            assert np.array_equal(bits(got.cpu().numpy()), bits(ref)), (w.name, j)
+
+
+def test_resnet_workload_full(ppo):
+    w = W.resnet50_shaped()
+    assert_same(gpu_solve(ppo, w), O.exhaustive(w.t, w.m, w.M, w.B)[:3], "resnet50_shaped")
+
+
+def test_transformer_workload_full(ppo):
+    """Almost every ordering ties on beta here: this is the test of the lowest-rank rule."""
+    w = W.transformer_encoder()
+    got = gpu_solve(ppo, w)
+    assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), "transformer vs subset DP")
+    head = w.take(8)
+    assert_same(tuple(x[:8] for x in got), O.exhaustive(head.t, head.m, head.M, head.B)[:3],
+                "transformer vs exhaustive")
+
+
+def sampled_orderings_match(ppo, w, inst, n_ranges, width, seed):
+    import torch
+    rng = np.random.default_rng(seed)
+    kf = math.factorial(w.k)
+    dev = ppo.to_device(w)
+    for j in inst:
+        for _ in range(n_ranges):
+            r0 = int(rng.integers(0, kf - width))
+            got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], r0, r0 + width)
+            torch.cuda.synchronize()
+            ref, _ = O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], r0, r0 + width)
+            assert np.array_equal(bits(got.cpu().numpy()), bits(ref)), (w.name, j, r0)
+
+
+def test_headline_workload_full(ppo):
+    """Full size, in the launch configuration the benchmark times: the optimum against the independent
+    subset DP, plus beta of sampled orderings one by one against the per-ordering oracle."""
+    w = W.headline()
+    got = gpu_solve(ppo, w)
+    assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), "headline vs subset DP")
+    sampled_orderings_match(ppo, w, [0, 17, 63], 3, 3000, seed=1)
+
+
+def test_large_workload_full(ppo):
+    w = W.large()
+    got = gpu_solve(ppo, w)
+    assert np.isfinite(got[0][0])
+    assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), "large vs subset DP")
+    sampled_orderings_match(ppo, w, [0], 4, 5000, seed=2)
+
+
+def test_small_instances_with_ties_and_exact_capacity_hits(ppo):
+    for seed in range(24):
+        rng = np.random.default_rng(5000 + seed)
+        L = int(rng.integers(1, 11))
+        k = int(rng.integers(1, min(L, 5) + 1))
+        w = W.random_instances(seed, 50, L, k, capacity_factor=float(rng.uniform(1.0, 1.8)), quantised=bool(seed % 2))
+        ref = O.exhaustive(w.t, w.m, w.M, w.B)[:3] if k == 5 else O.bruteforce(w.t, w.m, w.M, w.B)
+        assert_same(gpu_solve(ppo, w), ref, f"random L={L} k={k} seed={seed}")
+
+
+def test_degenerate_shapes(ppo):
+    # k = 1
+    w = W.random_instances(1, 9, 7, 1, capacity_factor=1.2)
+    w.M[::2] *= np.float32(0.5)                     # every other instance cannot hold the model
+    got = gpu_solve(ppo, w)
+    assert_same(got, O.bruteforce(w.t, w.m, w.M, w.B), "k=1")
+    assert np.isinf(got[0][::2]).all() and (got[0][1::2] == 0).all()
+    # L = k: every segment is a single layer
+    w = W.random_instances(2, 40, 5, 5, capacity_factor=3.0)
+    assert_same(gpu_solve(ppo, w), O.bruteforce(w.t, w.m, w.M, w.B), "L=k")
+    # L = k = 1
+    w = W.random_instances(3, 4, 1, 1, capacity_factor=1.5)
+    assert_same(gpu_solve(ppo, w), O.bruteforce(w.t, w.m, w.M, w.B), "L=k=1")
+    # nothing fits anywhere
+    w = W.random_instances(4, 5, 9, 3, capacity_factor=0.5)
+    got = gpu_solve(ppo, w)
+    assert np.isinf(got[0]).all() and (got[1] == -1).all() and (got[2] == -1).all()
+    # zero transfer sizes are legal and give beta = +0
+    w = W.random_instances(5, 3, 6, 3, capacity_factor=3.0)
+    w.t[:] = 0
+    got = gpu_solve(ppo, w)
+    assert (bits(got[0]) == 0).all()
+    assert_same(got, O.bruteforce(w.t, w.m, w.M, w.B), "t=0")
+
+
+def test_empty_batch(ppo):
+    import torch
+    z = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda:0")
+    beta, cuts, order = ppo.ppo_solve(z(0, 5), z(0, 5), z(0, 3), z(0, 3, 3))
+    torch.cuda.synchronize()
+    assert beta.numel() == 0 and cuts.shape == (0, 2) and order.shape == (0, 3)
+
+
+def test_maximum_sizes_on_a_rank_range(ppo):
+    """L = 128, k = 12 (the compiled limits): 12! orderings is too many to enumerate in a test, so a rank
+    range goes through solve_range + finalize and is compared with the oracle on the same range."""
+    import torch
+    w = W.random_instances(77, 2, 128, 12, capacity_factor=1.3)
+    dev = ppo.to_device(w)
+    kf = math.factorial(12)
+    r0, r1 = kf - 70001, kf
+    ws = ppo.alloc_workspace(128, 12, 2)
+    keys = torch.empty(2, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_prepare(*dev, ws)
+    ppo.ppo_init_keys(keys)
+    ppo.ppo_solve_range(128, 12, 2, ws, r0, r1, keys)
+    beta, cuts, order = ppo.ppo_finalize(128, 12, 2, ws, keys)
+    torch.cuda.synchronize()
+    ref = O.exhaustive(w.t, w.m, w.M, w.B, rank_range=(r0, r1))[:3]
+    assert_same((beta.cpu().numpy(), cuts.cpu().numpy(), order.cpu().numpy()), ref, "L=128 k=12 range")
+    j = 1
+    got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], r1 - 3000, r1)
+    torch.cuda.synchronize()
+    per, _ = O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], r1 - 3000, r1)
+    assert np.array_equal(bits(got.cpu().numpy()), bits(per))
+
+
+def test_rank_ranges_compose_and_workspace_variant(ppo):
+    """Ragged pieces of the rank range, issued out of order, give the key of the whole search; and the
+    caller-workspace entry point equals the allocating one."""
+    import torch
+    w = W.resnet50_shaped().take(37)
+    dev = ppo.to_device(w)
+    whole = gpu_solve(ppo, w)
+    ws = ppo.alloc_workspace(w.L, w.k, w.n_inst)
+    assert_same(gpu_solve(ppo, w, workspace=ws), whole, "workspace variant")
+    keys = torch.empty(w.n_inst, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_prepare(*dev, ws)
+    ppo.ppo_init_keys(keys)
+    for a, b in ((301, 720), (0, 1), (64, 301), (1, 64), (5, 5)):
+        ppo.ppo_solve_range(w.L, w.k, w.n_inst, ws, a, b, keys)
+    out = ppo.ppo_finalize(w.L, w.k, w.n_inst, ws, keys)
+    torch.cuda.synchronize()
+    assert_same(tuple(x.cpu().numpy() for x in out), whole, "composed ranges")
+
+
+def test_division_is_correctly_rounded_on_a_million_pairs(ppo):
+    """k = 2, L = 2 with ample memory reduces the search to one quotient t[0]/B[0][1] (Eq. 3)."""
+    n = 1_000_000
+    rng = np.random.default_rng(123)
+    t0 = np.exp(rng.uniform(np.log(1e-6), np.log(1e6), n)).astype(np.float32)
+    b = np.exp(rng.uniform(np.log(1e-3), np.log(1e5), n)).astype(np.float32)
+    t = np.stack([t0, np.ones(n, np.float32)], 1)
+    B = np.zeros((n, 2, 2), np.float32)
+    B[:, 0, 1] = B[:, 1, 0] = b
+    w = W.Workload("div", 2, 2, n, 0, np.ascontiguousarray(t), np.ones((n, 2), np.float32),
+                   np.full((n, 2), 8.0, np.float32), B)
+    beta, cuts, order = gpu_solve(ppo, w)
+    assert np.array_equal(bits(beta), bits(t0 / b))
+    assert (cuts == 1).all() and (order == np.array([0, 1])).all()
