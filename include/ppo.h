@@ -66,6 +66,16 @@ int ppo_version(void);
 /* Text for a return code (static storage; for PPO_EHIP, the last HIP error seen by this thread). */
 const char *ppo_strerror(int code);
 
+/* Which enumeration kernel ppo_solve_range (and everything built on it) launches.  Process-wide,
+ * not synchronised with calls in flight on other threads; meant for tests and tuning.
+ *   PPO_ENUM_AUTO     grouped kernel (wave-uniform memory windows) when k >= 6 and L-k+2 <= 96,
+ *                     otherwise the generic kernel
+ *   PPO_ENUM_GENERIC  always the generic kernel (one ordering per lane, any shape within the limits)
+ * Both produce identical results. */
+#define PPO_ENUM_AUTO 0
+#define PPO_ENUM_GENERIC 1
+int ppo_set_enumeration(int variant);
+
 /* Bytes of device scratch that ppo_solve_ws / ppo_prepare need for this shape (0 on bad shape). */
 size_t ppo_workspace_bytes(int L, int k, int n_inst);
 

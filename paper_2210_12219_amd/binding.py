@@ -39,6 +39,7 @@ def load() -> C.CDLL:
         lib.ppo_version.argtypes = []
         lib.ppo_strerror.argtypes = [i]
         lib.ppo_strerror.restype = C.c_char_p
+        lib.ppo_set_enumeration.argtypes = [i]
         lib.ppo_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_workspace_bytes.restype = sz
         lib.ppo_solve.argtypes = inst + [i, vp, vp, vp, vp]
@@ -89,6 +90,13 @@ def ppo_version() -> int:
 
 def ppo_strerror(code: int) -> str:
     return load().ppo_strerror(code).decode()
+
+
+PPO_ENUM_AUTO, PPO_ENUM_GENERIC = 0, 1
+
+
+def ppo_set_enumeration(variant: int):
+    _check(load().ppo_set_enumeration(variant))
 
 
 def ppo_workspace_bytes(L: int, k: int, n_inst: int) -> int:

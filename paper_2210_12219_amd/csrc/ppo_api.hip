@@ -10,6 +10,7 @@ hipError_t launch_init_keys(uint64_t*, int, hipStream_t);
 hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t, uint64_t*, float*, hipStream_t);
 hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, float*, int32_t*, int32_t*,
                             hipStream_t);
+void set_enumeration_variant(int);
 }  // namespace ppo
 
 namespace {
@@ -80,7 +81,13 @@ int run_finalize(int L, int k, int n_inst, const void* ws, const uint64_t* best_
 
 extern "C" {
 
-int ppo_version(void) { return 100; }
+int ppo_version(void) { return 101; }
+
+int ppo_set_enumeration(int variant) {
+    if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC) return PPO_EINVAL;
+    ppo::set_enumeration_variant(variant);
+    return PPO_OK;
+}
 
 const char* ppo_strerror(int code) {
     switch (code) {

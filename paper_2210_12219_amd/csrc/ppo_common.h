@@ -23,9 +23,10 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   lo  [k][L+1] u8   lo[j][e] = first layer i such that layers [i,e) fit on node j (== e: none)
 //   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
 //   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
+//   low [k][L+1] u32  the lo table again, one dword per entry (for scalar loads)
 struct Layout {
     int L, k, npairs;
-    uint32_t lo_off, qc_off, dec_off, stride;  // bytes within one instance's slice
+    uint32_t lo_off, qc_off, dec_off, low_off, stride;  // bytes within one instance's slice
 
     __host__ __device__ static Layout make(int L, int k) {
         Layout y;
@@ -38,7 +39,9 @@ struct Layout {
         y.qc_off = (uint32_t)off;
         off = align_up(off + (size_t)y.npairs * L * 2, 16);
         y.dec_off = (uint32_t)off;
-        off = align_up(off + ((size_t)y.npairs * (L - 1) + 2) * 4, 256);
+        off = align_up(off + ((size_t)y.npairs * (L - 1) + 2) * 4, 16);
+        y.low_off = (uint32_t)off;
+        off = align_up(off + (size_t)k * (L + 1) * 4, 256);
         y.stride = (uint32_t)off;
         return y;
     }

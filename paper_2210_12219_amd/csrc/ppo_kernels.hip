@@ -34,6 +34,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
     unsigned char* lo = base + y.lo_off;
     uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
     float* dec = reinterpret_cast<float*>(base + y.dec_off);
+    uint32_t* low = reinterpret_cast<uint32_t*>(base + y.low_off);
 
     if (tid == 0) {
         double acc = 0.0;
@@ -50,6 +51,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
         int i = 0;
         while (i < e && (P[e] - P[i]) > cap) ++i;
         lo[idx] = (unsigned char)i;
+        low[idx] = (uint32_t)i;
     }
     const int nq = y.npairs * (L - 1);
     for (int idx = tid; idx < nq; idx += kPreThreads) {
@@ -247,12 +249,22 @@ hipError_t launch_init_keys(uint64_t* keys, int n_inst, hipStream_t stream) {
     return hipGetLastError();
 }
 
+bool grouped_supported(int L, int k);
+hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin,
+                                    uint32_t rank_end, uint64_t* best_key, float* beta_export, hipStream_t stream);
+
+// 0: pick per shape (grouped kernel when k >= 6 and the rows fit LDS), 1: always the generic kernel
+static int g_enumeration_variant = 0;
+void set_enumeration_variant(int v) { g_enumeration_variant = v; }
+
 size_t enumerate_lds_bytes(const Layout& y) { return (size_t)y.dec_off + (size_t)(y.L + 1) * kEnumThreads * 2; }
 
 hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
                             uint64_t* best_key, float* beta_export, hipStream_t stream) {
     const uint32_t span = rank_end - rank_begin;
     if (span == 0 || n_inst == 0) return hipSuccess;
+    if (g_enumeration_variant == 0 && grouped_supported(y.L, y.k))
+        return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, stream);
     const size_t lds = enumerate_lds_bytes(y);
     uint32_t gx = (span + kEnumThreads - 1) / kEnumThreads;
     if (gx > 4096u) gx = 4096u;
