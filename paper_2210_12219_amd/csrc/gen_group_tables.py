@@ -16,11 +16,14 @@ rows are interleaved so that the bank of a slot is its class.  For any position 
 lane `32 + class`, and every half-wave touches 30 distinct banks.
 
 Tables (same for every instance):
-  kLaneSlot[2][42][64]  slot id (index*32 + class) handled by each lane, 0xFFFF = idle lane;
+  kLaneSlot[2][42][64]  slot id (index*32 + class) handled by each lane; lanes 30, 31, 62, 63 are
+                        idle and point at the two unused bank columns (slot ids 30 and 31), so that
+                        they never collide with a working lane and need no predicate;
                         sets 0..35 = (position r, value c) -> r*6 + c; sets 36..41 = all slots in
                         natural order (index 2n and 2n+1), used while the node is the same for all
   kSlotPerm[2][384]     per slot: sigma packed 3 bits per position, lexicographic rank of sigma
                         among the 720 permutations of six in bits 18..27, bit 31 = slot in use
+                        (idle slots carry the identity permutation with bit 31 clear)
 Index 0 of the first dimension holds the even permutations, index 1 the odd ones.
 """
 import itertools
@@ -49,8 +52,10 @@ def build():
     H = a4_on_pairs()
     all6 = list(itertools.permutations(range(6)))
     lex = {p: i for i, p in enumerate(all6)}
-    lane_slot = [[[0xFFFF] * 64 for _ in range(42)] for _ in range(2)]
-    slot_perm = [[0] * 384 for _ in range(2)]
+    idle = [(30 + (lane & 1)) if (lane & 31) >= 30 else 0xFFFF for lane in range(64)]
+    lane_slot = [[list(idle) for _ in range(42)] for _ in range(2)]
+    identity = sum(v << (3 * pos) for pos, v in enumerate(range(6)))
+    slot_perm = [[identity] * 384 for _ in range(2)]
     for par in range(2):
         perms = [p for p in all6 if parity(p) == par]
         assert len(perms) == 360
@@ -87,9 +92,9 @@ def build():
         # every lane set is bank-conflict free per half-wave, and the natural sets cover every slot once
         for s in range(42):
             for half in range(2):
-                banks = [v & 31 for v in lane_slot[par][s][32 * half:32 * half + 32] if v != 0xFFFF]
-                assert len(banks) == 30 == len(set(banks))
-        covered = sorted(v for n in range(6) for v in lane_slot[par][36 + n] if v != 0xFFFF)
+                banks = [v & 31 for v in lane_slot[par][s][32 * half:32 * half + 32]]
+                assert 0xFFFF not in lane_slot[par][s] and len(set(banks)) == 32
+        covered = sorted(v for n in range(6) for l, v in enumerate(lane_slot[par][36 + n]) if (l & 31) < 30)
         assert covered == sorted(slot.values())
     return lane_slot, slot_perm
 

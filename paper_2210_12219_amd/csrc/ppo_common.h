@@ -24,9 +24,12 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
 //   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
 //   low [k][L+1] u32  the lo table again, one dword per entry (for scalar loads)
+//   wt  [k][k-2][wt_cols] u16   window lengths for the grouped kernel: for node j, DP row s = 1..k-2
+//       and output dword jj (positions e = 2jj+s and e+1 of row s): wx | wy << 8 with
+//       w = e - max(lo[j][e], s) if s+1 <= e <= L-k+1+s, else 0
 struct Layout {
-    int L, k, npairs;
-    uint32_t lo_off, qc_off, dec_off, low_off, stride;  // bytes within one instance's slice
+    int L, k, npairs, wt_cols;
+    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, stride;  // bytes within one instance's slice
 
     __host__ __device__ static Layout make(int L, int k) {
         Layout y;
@@ -41,7 +44,10 @@ struct Layout {
         y.dec_off = (uint32_t)off;
         off = align_up(off + ((size_t)y.npairs * (L - 1) + 2) * 4, 16);
         y.low_off = (uint32_t)off;
-        off = align_up(off + (size_t)k * (L + 1) * 4, 256);
+        off = align_up(off + (size_t)k * (L + 1) * 4, 16);
+        y.wt_off = (uint32_t)off;
+        y.wt_cols = (int)align_up((size_t)((L - k + 2 + 1) / 2), 4);
+        off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * 2, 256);
         y.stride = (uint32_t)off;
         return y;
     }

@@ -42,6 +42,13 @@ __device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
     ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(x, y));
 }
+// Codes are positive normal binary16 patterns (or +inf), which order like the unsigned integers they
+// are, so the three-input packed binary16 minimum of gfx950 can do two comparisons per position.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pk_min3(uint32_t a, uint32_t b, uint32_t c) {
+    half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b), z = __builtin_bit_cast(half2_t, c);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_minimum(__builtin_elementwise_minimum(x, y), z));
+}
 // (hi:lo) >> 16: the dword made of the upper code of lo and the lower code of hi
 __device__ inline uint32_t align16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
@@ -161,9 +168,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const int c = wave % 6, half = wave / 6;
         const int node = p0 > 0 ? prefix_node(0) : rest_node(c);
         const int set = p0 > 0 ? 36 + c : c;
-        const uint32_t slot = slotTab[set * 64 + lane];
-        const bool active = slot != 0xFFFFu;
-        const uint32_t sl = active ? slot : 0u;
+        const uint32_t sl = slotTab[set * 64 + lane];
         const uint32_t perm = permTab[sl];
         uint32_t* out = buf0 + (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
         const uint32_t* qrow = qtab + link_row(0, perm) * QROW + link_col(0);
@@ -173,13 +178,13 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             const int ix = 2 * jj, iy = 2 * jj + 1;
             const uint32_t dx = (ix >= 1 && ix <= L - k + 1 && lowrow[ix] == 0u) ? kCodeZero : kCodeInf;
             const uint32_t dy = (iy <= L - k + 1 && lowrow[iy] == 0u) ? kCodeZero : kCodeInf;
-            const uint32_t v = pk_max(dx | (dy << 16), qrow[jj]);
-            if (active) out[jj * 32] = v;
+            out[jj * 32] = pk_max(dx | (dy << 16), qrow[jj]);
         }
     }
     __syncthreads();
 
     // ---- rows 1 .. k-2
+    const uint16_t* __restrict__ wt = reinterpret_cast<const uint16_t*>(base + y.wt_off);
     for (int s = 1; s <= k - 2; ++s) {
         const uint32_t* in = (s & 1) ? buf0 : buf1;
         uint32_t* outb = (s & 1) ? buf1 : buf0;
@@ -193,41 +198,65 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             if (jbeg >= NP) continue;
             const int node = s < p0 ? prefix_node(s) : rest_node(c);
             const int set = s < p0 ? 36 + c : (s - p0) * 6 + c;
-            const uint32_t slot = slotTab[set * 64 + lane];
-            const bool active = slot != 0xFFFFu;
-            const uint32_t sl = active ? slot : 0u;
+            // window lengths of the task's four output dwords: one 8-byte scalar load
+            const uint2 wpack = *reinterpret_cast<const uint2*>(wt + ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
+            const uint32_t sl = slotTab[set * 64 + lane];
             const uint32_t perm = permTab[sl];
             const uint32_t slot_dw = (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
             const uint32_t* qrow = qtab + link_row(s, perm) * QROW + col;
-            const uint32_t* lowrow = low + node * (L + 1);
             const int jend = jbeg + kChunkPairs < NP ? jbeg + kChunkPairs : NP;
-            for (int jj = jbeg; jj < jend; ++jj) {
-                const int ex = 2 * jj + s, ey = ex + 1, emax = L - k + 1 + s;
-                int wx = 0, wy = 0;
-                if (ex <= emax) { const int l = (int)lowrow[ex]; wx = ex - (l > s ? l : s); }
-                if (ey <= emax) { const int l = (int)lowrow[ey]; wy = ey - (l > s ? l : s); }
-                const int nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx, nfull = nmin >> 1;
-                const uint32_t* src = in + slot_dw + jj * 32;
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) {
+                const int jj = jbeg + t;
+                if (jj >= jend) break;
+                const uint32_t wboth = ((t < 2 ? wpack.x : wpack.y) >> (16 * (t & 1))) & 0xFFFFu;
+                const int wx = (int)(wboth & 0xFFu), wy = (int)(wboth >> 8);
+                const int nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx;
+                // p walks down the input row; p[0] is the dword holding input indices (2a, 2a+1)
+                const uint32_t* p = in + slot_dw + jj * 32;
                 uint32_t acc = kInf2;
-                uint32_t cur = src[0];
-                for (int mth = 0; mth < nfull; ++mth) {
-                    const uint32_t nxt = src[-(mth + 1) * 32];
-                    acc = pk_min(pk_min(acc, cur), align16(cur, nxt));
-                    cur = nxt;
+                uint32_t cur = p[0];
+                int n = nmin >> 1;   // steps in which both positions take both offsets 2m and 2m+1
+                while (n >= 4) {
+                    p -= 128;
+                    const uint32_t l1 = p[96], l2 = p[64], l3 = p[32], l4 = p[0];
+                    acc = pk_min3(acc, cur, align16(cur, l1));
+                    acc = pk_min3(acc, l1, align16(l1, l2));
+                    acc = pk_min3(acc, l2, align16(l2, l3));
+                    acc = pk_min3(acc, l3, align16(l3, l4));
+                    cur = l4;
+                    n -= 4;
                 }
-                for (int d = 2 * nfull; d < nmax; ++d) {
-                    uint32_t v;
-                    if (d & 1) {
-                        const int a = (d + 1) >> 1;
-                        v = align16(src[-(a - 1) * 32], src[-a * 32]);
-                    } else {
-                        v = src[-(d >> 1) * 32];
+                if (n & 2) {
+                    p -= 64;
+                    const uint32_t l1 = p[32], l2 = p[0];
+                    acc = pk_min3(acc, cur, align16(cur, l1));
+                    acc = pk_min3(acc, l1, align16(l1, l2));
+                    cur = l2;
+                }
+                if (n & 1) {
+                    p -= 32;
+                    const uint32_t l1 = p[0];
+                    acc = pk_min3(acc, cur, align16(cur, l1));
+                    cur = l1;
+                }
+                if (nmin & 1) acc = pk_min(acc, cur);   // offset nmin-1 is even and valid for both
+                if (nmax > nmin) {
+                    // offsets nmin .. nmax-1 exist only for the position with the longer window
+                    const uint32_t mask = wx > wy ? (kCodeInf << 16) : kCodeInf;
+                    const uint32_t* p0w = in + slot_dw + jj * 32;
+                    for (int d = nmin; d < nmax; ++d) {
+                        uint32_t v;
+                        if (d & 1) {
+                            const int a = (d + 1) >> 1;
+                            v = align16(p0w[-(a - 1) * 32], p0w[-a * 32]);
+                        } else {
+                            v = p0w[-(d >> 1) * 32];
+                        }
+                        acc = pk_min(acc, pk_max(v, mask));
                     }
-                    const uint32_t mask = (d < wx ? 0u : kCodeInf) | (d < wy ? 0u : (kCodeInf << 16));
-                    acc = pk_min(acc, pk_max(v, mask));
                 }
-                const uint32_t v = pk_max(acc, qrow[jj]);
-                if (active) outb[slot_dw + jj * 32] = v;
+                outb[slot_dw + jj * 32] = pk_max(acc, qrow[jj]);
             }
         }
         __syncthreads();
@@ -240,10 +269,9 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t* in = (s & 1) ? buf0 : buf1;
         const int node = rest_node(c);
         const int set = 5 * 6 + c;
-        const uint32_t slot = slotTab[set * 64 + lane];
-        const bool active = slot != 0xFFFFu;
-        const uint32_t sl = active ? slot : 0u;
+        const uint32_t sl = slotTab[set * 64 + lane];
         const uint32_t perm = permTab[sl];
+        const bool active = (perm >> 31) != 0u;   // idle lanes sit on the two unused bank columns
         const uint32_t slot_dw = (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
         const int l = (int)low[node * (L + 1) + L];
         const int w = L - (l > s ? l : s);

@@ -53,6 +53,26 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
         lo[idx] = (unsigned char)i;
         low[idx] = (uint32_t)i;
     }
+    __syncthreads();
+    {
+        uint16_t* wt = reinterpret_cast<uint16_t*>(base + y.wt_off);
+        const int rows = k > 2 ? k - 2 : 0, cols = y.wt_cols;
+        for (int idx = tid; idx < k * rows * cols; idx += kPreThreads) {
+            const int jj = idx % cols, s = (idx / cols) % rows + 1, j = idx / (cols * rows);
+            const int emax = L - k + 1 + s;
+            uint32_t w[2];
+            for (int h = 0; h < 2; ++h) {
+                const int e = 2 * jj + s + h;
+                int v = 0;
+                if (e >= s + 1 && e <= emax) {
+                    const int l = lo[j * (L + 1) + e];
+                    v = e - (l > s ? l : s);
+                }
+                w[h] = (uint32_t)v;
+            }
+            wt[idx] = (uint16_t)(w[0] | (w[1] << 8));
+        }
+    }
     const int nq = y.npairs * (L - 1);
     for (int idx = tid; idx < nq; idx += kPreThreads) {
         int p = idx / (L - 1), i = idx - p * (L - 1);
