@@ -16,10 +16,13 @@ rows are interleaved so that the bank of a slot is its class.  For any position 
 lane `32 + class`, and every half-wave touches 30 distinct banks.
 
 Tables (same for every instance):
-  kLaneSlot[2][42][64]  slot id (index*32 + class) handled by each lane; lanes 30, 31, 62, 63 are
-                        idle and point at the two unused bank columns (slot ids 30 and 31), so that
-                        they never collide with a working lane and need no predicate;
-                        sets 0..35 = (position r, value c) -> r*6 + c; sets 36..41 = all slots in
+  kLaneSlot[2][42][64]  per lane: bits 0..8 the slot id (index*32 + class) it handles; bits 16..19
+                        the index of the unordered pair {sigma(r), sigma(r+1)} among the 15 pairs of
+                        six (row-major upper triangle) for the set's position r (0 for r = 5 and for
+                        the natural sets); bits 20..22 sigma(0).  Lanes 30, 31, 62, 63 are idle and
+                        point at the two unused bank columns (slot ids 30 and 31), so that they never
+                        collide with a working lane and need no predicate.
+                        Sets 0..35 = (position r, value c) -> r*6 + c; sets 36..41 = all slots in
                         natural order (index 2n and 2n+1), used while the node is the same for all
   kSlotPerm[2][384]     per slot: sigma packed 3 bits per position, lexicographic rank of sigma
                         among the 720 permutations of six in bits 18..27, bit 31 = slot in use
@@ -56,6 +59,12 @@ def build():
     lane_slot = [[list(idle) for _ in range(42)] for _ in range(2)]
     identity = sum(v << (3 * pos) for pos, v in enumerate(range(6)))
     slot_perm = [[identity] * 384 for _ in range(2)]
+
+    def pair6(a, b):
+        lo, hi = min(a, b), max(a, b)
+        return lo * 6 - lo * (lo + 1) // 2 + (hi - lo - 1)
+
+
     for par in range(2):
         perms = [p for p in all6 if parity(p) == par]
         assert len(perms) == 360
@@ -96,6 +105,14 @@ def build():
                 assert 0xFFFF not in lane_slot[par][s] and len(set(banks)) == 32
         covered = sorted(v for n in range(6) for l, v in enumerate(lane_slot[par][36 + n]) if (l & 31) < 30)
         assert covered == sorted(slot.values())
+        perm_of = {slot[p]: p for p in perms}
+        for st in range(42):
+            r = st // 6 if st < 36 else None
+            for lane in range(64):
+                v = lane_slot[par][st][lane]
+                p = perm_of.get(v, tuple(range(6)))
+                link = pair6(p[r], p[r + 1]) if (r is not None and r < 5) else 0
+                lane_slot[par][st][lane] = v | (link << 16) | (p[0] << 20)
     return lane_slot, slot_perm
 
 
@@ -104,11 +121,11 @@ def main():
     out = ["// Generated by gen_group_tables.py; do not edit.  Lane/slot schedule of the grouped enumeration",
            "// kernel (360 orderings per workgroup, one LDS bank per coset class).",
            "#pragma once", "#include <stdint.h>", "", "namespace ppo {", ""]
-    out.append("__device__ const uint16_t kLaneSlot[2][42][64] = {")
+    out.append("__device__ const uint32_t kLaneSlot[2][42][64] = {")
     for par in range(2):
         out.append(" {")
         for s in range(42):
-            out.append("  {" + ",".join(str(v) for v in lane_slot[par][s]) + "},")
+            out.append("  {" + ",".join(f"0x{v:x}" for v in lane_slot[par][s]) + "},")
         out.append(" },")
     out.append("};")
     out.append("")

@@ -2,8 +2,8 @@
 //
 // One workgroup evaluates the 360 orderings that share a prefix of k-6 nodes and whose arrangement
 // sigma of the six remaining nodes has one parity.  Every ordering still runs its own k DP rows; what
-// the grouping buys is that the rows are *scheduled* so that all 60 lanes of a wave, at any moment,
-// work on orderings that put the same node at the current DP row.  The memory window
+// the grouping buys is that the rows are *scheduled* so that all 60 working lanes of a wave, at any
+// moment, handle orderings that put the same node at the current DP row.  The memory window
 // [lo[node][e], e-1] is then the same for the whole wave: loop bounds are scalar, nothing is
 // predicated per lane, and the only vector work left is the min/max arithmetic itself, done two
 // positions at a time on packed 16-bit order codes.
@@ -12,7 +12,7 @@
 // ceil(NE/2) dwords (two codes per dword).  There are two row buffers (read one, write the other).
 // Dword a of slot (index, class) sits at ((index*NP + a)*32 + class): the LDS bank of every access
 // is the slot's class, and the lane/slot schedule (ppo_group_tables.h) gives the lanes of each
-// half-wave 30 distinct classes.
+// half-wave 32 distinct banks.
 //
 // Row convention.  While row s is being computed, the input buffer holds
 //     g_s[i] = max(D_{s-1}[i], q_{pi_{s-1},pi_s}[i-1])        at index u = i - s + 1
@@ -21,6 +21,10 @@
 // input indices (u' - w, u'] with w = e - max(lo[pi_s][e], s).  Index 0 is always +inf.  The max
 // with the next link's quotients is folded into the write, so each row is one pass.  The last row
 // needs only D_{k-1}[L].
+//
+// Work split.  A row is 6 lane sets (one per node that can sit at that row) times 12 chunks of four
+// output dwords.  Wave w takes, in round q = 0..5, the set (w+q) mod 6 and chunk 2q + (w >= 6): every
+// wave meets every node once per row, which evens out the very different window lengths of the nodes.
 #include "ppo_common.h"
 #include "ppo_group_tables.h"
 
@@ -28,33 +32,38 @@ namespace ppo {
 
 constexpr int kGrpWaves = 12;
 constexpr int kGrpThreads = kGrpWaves * 64;
-constexpr int kChunkPairs = 4;                      // target dwords (pairs of positions) per task
+constexpr int kChunkPairs = 4;                      // output dwords (pairs of positions) per task
 constexpr int kGrpMaxPairs = 6 * 2 * kChunkPairs;   // six rounds of two chunks cover at most 48 dwords
+constexpr int kDeep = 8;                            // input dwords fetched below each output dword
 constexpr uint32_t kInf2 = kCodeInf | (kCodeInf << 16);
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-__device__ inline uint32_t pk_min(uint32_t a, uint32_t b) {
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
     ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(x, y));
 }
-__device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
     ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(x, y));
 }
 // Codes are positive normal binary16 patterns (or +inf), which order like the unsigned integers they
-// are, so the three-input packed binary16 minimum of gfx950 can do two comparisons per position.
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-__device__ inline uint32_t pk_min3(uint32_t a, uint32_t b, uint32_t c) {
+// are, so the three-input packed binary16 minimum of gfx950 does two comparisons per position.
+__device__ __forceinline__ uint32_t pk_min3(uint32_t a, uint32_t b, uint32_t c) {
     half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b), z = __builtin_bit_cast(half2_t, c);
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_minimum(__builtin_elementwise_minimum(x, y), z));
 }
+// LDS accesses by 32-bit LDS byte address
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+__device__ __forceinline__ uint32_t lds_addr(const uint32_t* p) { return (uint32_t)(uintptr_t)(const lds_u32_t*)p; }
+__device__ __forceinline__ uint32_t lds_load(uint32_t byte_addr) { return *(const lds_u32_t*)(uintptr_t)byte_addr; }
 // (hi:lo) >> 16: the dword made of the upper code of lo and the lower code of hi
-__device__ inline uint32_t align16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
+__device__ __forceinline__ uint32_t align16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
 struct GroupedShape {
     int NE, NP, QD, QROW, nA, nB, nQ;
-    uint32_t buf_dwords, q_off, slot_off, perm_off, total_bytes;  // offsets in dwords
+    uint32_t buf_off, buf_dwords, q_off, slot_off, total_bytes;  // offsets in dwords
     __host__ __device__ static GroupedShape make(int L, int k) {
         GroupedShape g;
         g.NE = L - k + 2;
@@ -65,11 +74,11 @@ struct GroupedShape {
         g.nA = p0 > 1 ? p0 - 1 : 0;   // links inside the prefix
         g.nB = p0 > 0 ? 6 : 0;        // links from the last prefix node to each remaining node
         g.nQ = g.nA + g.nB + 15;      // plus the links among the six remaining nodes
+        g.buf_off = (uint32_t)(kDeep + 1) * 32u;   // room for the fixed-depth fetches below dword 0
         g.buf_dwords = 12u * g.NP * 32u;
-        g.q_off = 2u * g.buf_dwords;
+        g.q_off = g.buf_off + 2u * g.buf_dwords;
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
-        g.perm_off = g.slot_off + 42u * 64u / 2u;
-        g.total_bytes = (g.perm_off + 384u) * 4u;
+        g.total_bytes = (g.slot_off + 42u * 64u) * 4u;
         return g;
     }
 };
@@ -79,6 +88,10 @@ bool grouped_supported(int L, int k) {
     GroupedShape g = GroupedShape::make(L, k);
     return g.NP <= kGrpMaxPairs && g.total_bytes <= 160u * 1024u;
 }
+
+// One step of a chain folds two offsets of both positions: the dword `hi` itself and the dword
+// straddling `lo_` and `hi`.
+#define PPO_STEP(hi, lo_) acc = pk_min3(acc, hi, align16(hi, lo_))
 
 template <bool EXPORT>
 __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
@@ -94,19 +107,19 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     const uint32_t par = group & 1u, pr = group >> 1;
 
     const unsigned char* base = ws + (size_t)inst * y.stride;
-    const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
     const uint32_t* __restrict__ low = reinterpret_cast<const uint32_t*>(base + y.low_off);
+    const uint32_t* __restrict__ wt = reinterpret_cast<const uint32_t*>(base + y.wt_off);
+    const uint32_t* __restrict__ qa = reinterpret_cast<const uint32_t*>(base + y.qa_off);
 
-    uint32_t* const buf0 = lds;
-    uint32_t* const buf1 = lds + gs.buf_dwords;
+    uint32_t* const buf0 = lds + gs.buf_off;
+    uint32_t* const buf1 = buf0 + gs.buf_dwords;
     uint32_t* const qtab = lds + gs.q_off;
-    uint16_t* const slotTab = reinterpret_cast<uint16_t*>(lds + gs.slot_off);
-    uint32_t* const permTab = lds + gs.perm_off;
+    uint32_t* const slotTab = lds + gs.slot_off;
 
     // ---- prefix: positions 0..p0-1 from the Lehmer digits of pr (weights (k-1-p)!/6!); `avail` ends up
     //      holding the six remaining nodes in ascending order, four bits each
-    uint64_t avail = 0xBA9876543210ull, prefix = 0;
+    uint64_t avail_ = 0xBA9876543210ull, prefix_ = 0;
     {
         uint32_t rem = pr;
         for (int p = 0; p < p0; ++p) {
@@ -114,24 +127,28 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             const uint32_t d = rem / f;
             rem -= d * f;
             const uint32_t sh = 4u * d;
-            const uint64_t node = (avail >> sh) & 0xFull;
-            const uint64_t lowbits = avail & ((1ull << sh) - 1ull);
-            avail = lowbits | ((avail >> 4) & ~((1ull << sh) - 1ull));
-            prefix |= node << (4 * p);
+            const uint64_t node = (avail_ >> sh) & 0xFull;
+            const uint64_t lowbits = avail_ & ((1ull << sh) - 1ull);
+            avail_ = lowbits | ((avail_ >> 4) & ~((1ull << sh) - 1ull));
+            prefix_ |= node << (4 * p);
         }
     }
-    auto prefix_node = [&](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
-    auto rest_node = [&](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
+    const uint64_t avail = avail_, prefix = prefix_;
+    auto prefix_node = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
+    auto rest_node = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
+    // node at DP row s for the lane set of remaining-node index c
+    auto row_node = [=](int s, int c) {
+        const uint64_t packed = s < p0 ? prefix : avail;
+        const int idx = s < p0 ? s : c;
+        return (int)((packed >> (4 * idx)) & 0xFull);
+    };
 
-    // ---- stage the schedule tables and the quotient rows of the links this group can cross
+    // ---- stage the schedule and the quotient rows of the links this group can cross
     {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(&kLaneSlot[par][0][0]);
-        uint32_t* dst = lds + gs.slot_off;
-        for (int i = tid; i < 42 * 64 / 2; i += kGrpThreads) dst[i] = src[i];
-        for (int i = tid; i < 384; i += kGrpThreads) permTab[i] = kSlotPerm[par][i];
-        const int total = gs.nQ * QROW;
-        for (int idx = tid; idx < total; idx += kGrpThreads) {
-            const int row = idx / QROW, col = idx - row * QROW;
+        const uint32_t* src = &kLaneSlot[par][0][0];
+        for (int i = tid; i < 42 * 64; i += kGrpThreads) slotTab[i] = src[i];
+        for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
+        for (int row = wave; row < gs.nQ; row += kGrpWaves) {
             int a, b;
             if (row < nA) {
                 a = prefix_node(row); b = prefix_node(row + 1);
@@ -142,36 +159,33 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 while (pi >= 5 - ca) { pi -= 5 - ca; ++ca; }
                 a = rest_node(ca); b = rest_node(ca + 1 + pi);
             }
-            const uint16_t* qrow = qc + pair_index(a, b, k) * L;
-            // columns [0,QD): (q[2a], q[2a+1]);  columns [QD, 2QD+2): (q[2a+1], q[2a+2]) for a = col-QD-1
-            const int i0 = col < QD ? 2 * col : 2 * (col - QD - 1) + 1;
-            const uint32_t v0 = (i0 >= 0 && i0 <= L - 2) ? qrow[i0] : kCodeInf;
-            const uint32_t v1 = (i0 + 1 >= 0 && i0 + 1 <= L - 2) ? qrow[i0 + 1] : kCodeInf;
-            qtab[idx] = v0 | (v1 << 16);
+            const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
+            for (int col = lane; col < QROW; col += 64) qtab[row * QROW + col] = qsrc[col];
         }
     }
     __syncthreads();
 
-    // quotient row used when row s is written: the link between the nodes of rows s and s+1
-    auto link_row = [&](int s, uint32_t perm) -> int {
+    // quotient row used when row s is written (the link between the nodes of rows s and s+1), from the
+    // lane's schedule entry
+    auto link_row = [&](int s, uint32_t ent) -> int {
         if (s + 1 < p0) return s;
-        if (s + 1 == p0) return nA + (int)(perm & 7u);
-        const int r = s - p0;
-        const int a = (int)((perm >> (3 * r)) & 7u), b = (int)((perm >> (3 * r + 3)) & 7u);
-        return nA + nB + pair_index(a, b, 6);
+        if (s + 1 == p0) return nA + (int)((ent >> 20) & 7u);
+        return nA + nB + (int)((ent >> 16) & 15u);
     };
     // column of the quotient row holding (q[e-1], q[e]) for the output dword jj of row s (e = 2jj + s)
     auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
+    auto slot_dword = [&](uint32_t ent) -> uint32_t {
+        return __umul24((ent >> 5) & 15u, (uint32_t)(NP * 32)) + (ent & 31u);
+    };
 
     // ---- row 0: g_1[i] = max(D_0[i], q_{pi_0,pi_1}[i-1]) at index i, D_0[i] = 0 if layers [0,i) fit node pi_0
     {
         const int c = wave % 6, half = wave / 6;
-        const int node = p0 > 0 ? prefix_node(0) : rest_node(c);
+        const int node = row_node(0, c);
         const int set = p0 > 0 ? 36 + c : c;
-        const uint32_t sl = slotTab[set * 64 + lane];
-        const uint32_t perm = permTab[sl];
-        uint32_t* out = buf0 + (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
-        const uint32_t* qrow = qtab + link_row(0, perm) * QROW + link_col(0);
+        const uint32_t ent = slotTab[set * 64 + lane];
+        uint32_t* out = buf0 + slot_dword(ent);
+        const uint32_t* qrow = qtab + link_row(0, ent) * QROW + link_col(0);
         const uint32_t* lowrow = low + node * (L + 1);
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
         for (int jj = j0; jj < j1; ++jj) {
@@ -181,100 +195,162 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             out[jj * 32] = pk_max(dx | (dy << 16), qrow[jj]);
         }
     }
+
+    // ---- rows 1 .. k-2 as one sequence of tasks T = (s-1)*6 + q; the schedule entry and the chain
+    //      descriptors of task T+1 are requested while task T runs
+    const int n_tasks = 6 * (k - 2);
+    auto task_set = [&](int s, int c) -> int { return s < p0 ? 36 + c : (s - p0) * 6 + c; };
+    auto task_c = [&](int q) -> int {
+        int c = wave + q;
+        c = c >= 12 ? c - 12 : c;
+        return c >= 6 ? c - 6 : c;
+    };
+    auto task_jbeg = [&](int q) -> int { return (2 * q + (wave >= 6 ? 1 : 0)) * kChunkPairs; };
+    auto load_desc = [&](int s, int q) -> uint4 {
+        const int c = task_c(q), jbeg = task_jbeg(q);
+        const int node = row_node(s, c);
+        if (jbeg >= NP) return make_uint4(0u, 0u, 0u, 0u);
+        return *reinterpret_cast<const uint4*>(wt + ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
+    };
+    uint32_t ent_next = slotTab[task_set(1, task_c(0)) * 64 + lane];
+    uint4 desc_next = load_desc(1, 0);
     __syncthreads();
 
-    // ---- rows 1 .. k-2
-    const uint16_t* __restrict__ wt = reinterpret_cast<const uint16_t*>(base + y.wt_off);
-    for (int s = 1; s <= k - 2; ++s) {
+    int s = 1, q = 0;
+    for (int T = 0; T < n_tasks; ++T) {
+        const uint32_t ent = ent_next;
+        const uint4 dpack = desc_next;
+        const int jbeg = task_jbeg(q);
         const uint32_t* in = (s & 1) ? buf0 : buf1;
         uint32_t* outb = (s & 1) ? buf1 : buf0;
-        const int col = link_col(s);
-        for (int q = 0; q < 6; ++q) {
-            int c = wave + q;
-            c = c >= 12 ? c - 12 : c;
-            c = c >= 6 ? c - 6 : c;
-            const int chunk = 2 * q + (wave >= 6 ? 1 : 0);
-            const int jbeg = chunk * kChunkPairs;
-            if (jbeg >= NP) continue;
-            const int node = s < p0 ? prefix_node(s) : rest_node(c);
-            const int set = s < p0 ? 36 + c : (s - p0) * 6 + c;
-            // window lengths of the task's four output dwords: one 8-byte scalar load
-            const uint2 wpack = *reinterpret_cast<const uint2*>(wt + ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
-            const uint32_t sl = slotTab[set * 64 + lane];
-            const uint32_t perm = permTab[sl];
-            const uint32_t slot_dw = (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
-            const uint32_t* qrow = qtab + link_row(s, perm) * QROW + col;
-            const int jend = jbeg + kChunkPairs < NP ? jbeg + kChunkPairs : NP;
+        // next task's coordinates; its schedule entry is requested right away
+        const int qn = q == 5 ? 0 : q + 1, sn = q == 5 ? s + 1 : s;
+        if (T + 1 < n_tasks) ent_next = slotTab[task_set(sn, task_c(qn)) * 64 + lane];
+
+        if (jbeg < NP) {
+            const uint32_t slot_dw = slot_dword(ent);
+            const uint32_t* qrow = qtab + link_row(s, ent) * QROW + link_col(s) + jbeg;
+            uint32_t* outrow = outb + slot_dw + jbeg * 32;
+            const int np = NP - jbeg < kChunkPairs ? NP - jbeg : kChunkPairs;
+            // LDS byte address of the dword kDeep below dword jbeg of the lane's input row.  It is made
+            // opaque to the compiler so that every fetch below is this register plus a small constant.
+            uint32_t fetch_base = lds_addr(in + slot_dw + (jbeg - kDeep) * 32);
+            asm volatile("" : "+v"(fetch_base));
+            auto lds_at = [&](uint32_t byte_off) -> uint32_t { return lds_load(fetch_base + byte_off); };
+
+            // Fetch for output dword t: the next link's quotients, then the kDeep input dwords below the
+            // output's index (reads below the window are harmless and stay inside LDS), deepest first,
+            // and the dword at the output's own index last: the chain starts with the last ones issued,
+            // so one wait covers the whole fetch.
+            uint32_t lw[kChunkPairs][kDeep + 1], qv[kChunkPairs];
+            auto fetch = [&](int t) {
+                qv[t] = qrow[t];
 #pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) {
-                const int jj = jbeg + t;
-                if (jj >= jend) break;
-                const uint32_t wboth = ((t < 2 ? wpack.x : wpack.y) >> (16 * (t & 1))) & 0xFFFFu;
-                const int wx = (int)(wboth & 0xFFu), wy = (int)(wboth >> 8);
-                const int nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx;
-                // p walks down the input row; p[0] is the dword holding input indices (2a, 2a+1)
-                const uint32_t* p = in + slot_dw + jj * 32;
+                for (int i = kDeep; i >= 0; --i) lw[t][i] = lds_at((uint32_t)(t + kDeep - i) * 128u);
+            };
+            // Evaluate output dword t.  The number of steps is consumed bit by bit (4, 2, 1); after each
+            // taken block the fetched dwords are renamed downwards, so that every branch is a plain `if`
+            // and a0, a1 end up as the two dwords at the bottom of the window.
+            auto finish = [&](int t) {
+                const uint32_t d = t == 0 ? dpack.x : t == 1 ? dpack.y : t == 2 ? dpack.z : dpack.w;
+                uint32_t a0 = lw[t][0], a1 = lw[t][1], a2 = lw[t][2], a3 = lw[t][3], a4 = lw[t][4];
                 uint32_t acc = kInf2;
-                uint32_t cur = p[0];
-                int n = nmin >> 1;   // steps in which both positions take both offsets 2m and 2m+1
-                while (n >= 4) {
-                    p -= 128;
-                    const uint32_t l1 = p[96], l2 = p[64], l3 = p[32], l4 = p[0];
-                    acc = pk_min3(acc, cur, align16(cur, l1));
-                    acc = pk_min3(acc, l1, align16(l1, l2));
-                    acc = pk_min3(acc, l2, align16(l2, l3));
-                    acc = pk_min3(acc, l3, align16(l3, l4));
-                    cur = l4;
-                    n -= 4;
+                if ((d & WinDesc::kStepsMask) >= 8u) {
+                    PPO_STEP(a0, a1); PPO_STEP(a1, a2); PPO_STEP(a2, a3); PPO_STEP(a3, a4);
+                    PPO_STEP(a4, lw[t][5]); PPO_STEP(lw[t][5], lw[t][6]); PPO_STEP(lw[t][6], lw[t][7]);
+                    PPO_STEP(lw[t][7], lw[t][8]);
+                    // the rest of a long chain walks further down the row
+                    uint32_t pa = fetch_base + (uint32_t)t * 128u;   // address of the deepest fetched dword
+                    uint32_t cur = lw[t][8];
+                    int m = (int)(d & WinDesc::kStepsMask) - 8;
+                    while (m >= 4) {
+                        pa -= 512u;
+                        const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u), b3 = lds_load(pa + 128u),
+                                       b4 = lds_load(pa);
+                        PPO_STEP(cur, b1); PPO_STEP(b1, b2); PPO_STEP(b2, b3); PPO_STEP(b3, b4);
+                        cur = b4;
+                        m -= 4;
+                    }
+                    while (m >= 1) {
+                        pa -= 128u;
+                        const uint32_t b1 = lds_load(pa);
+                        PPO_STEP(cur, b1);
+                        cur = b1;
+                        m -= 1;
+                    }
+                    a0 = cur;
+                    a1 = lds_load(pa - 128u);
+                } else {
+                    if (d & 4u) {
+                        PPO_STEP(a0, a1); PPO_STEP(a1, a2); PPO_STEP(a2, a3); PPO_STEP(a3, a4);
+                        a0 = a4; a1 = lw[t][5]; a2 = lw[t][6]; a3 = lw[t][7]; a4 = lw[t][8];
+                    }
+                    if (d & 2u) {
+                        PPO_STEP(a0, a1); PPO_STEP(a1, a2);
+                        a0 = a2; a1 = a3; a2 = a4;
+                    }
+                    if (d & 1u) {
+                        PPO_STEP(a0, a1);
+                        a0 = a1; a1 = a2;
+                    }
                 }
-                if (n & 2) {
-                    p -= 64;
-                    const uint32_t l1 = p[32], l2 = p[0];
-                    acc = pk_min3(acc, cur, align16(cur, l1));
-                    acc = pk_min3(acc, l1, align16(l1, l2));
-                    cur = l2;
+                // bottom of the window: if the shorter window is odd, one more offset for both positions
+                // (the dword a0); then the offsets that only the longer window has, masked to it
+                const uint32_t mask = (d & (1u << WinDesc::kXLongerBit)) ? (kCodeInf << 16) : kCodeInf;
+                if (d & (1u << WinDesc::kOddBit)) acc = pk_min(acc, a0);
+                if (d & (1u << WinDesc::kTailBit)) {
+                    uint32_t v = a0;
+                    if (d & (1u << WinDesc::kOddBit)) v = align16(a0, a1);
+                    acc = pk_min(acc, pk_max(v, mask));
                 }
-                if (n & 1) {
-                    p -= 32;
-                    const uint32_t l1 = p[0];
-                    acc = pk_min3(acc, cur, align16(cur, l1));
-                    cur = l1;
-                }
-                if (nmin & 1) acc = pk_min(acc, cur);   // offset nmin-1 is even and valid for both
-                if (nmax > nmin) {
-                    // offsets nmin .. nmax-1 exist only for the position with the longer window
-                    const uint32_t mask = wx > wy ? (kCodeInf << 16) : kCodeInf;
-                    const uint32_t* p0w = in + slot_dw + jj * 32;
-                    for (int d = nmin; d < nmax; ++d) {
+                if (d & (1u << WinDesc::kLongTailBit)) {
+                    const int nmin = 2 * (int)(d & WinDesc::kStepsMask) + (int)((d >> WinDesc::kOddBit) & 1u);
+                    const int nmax = nmin + (int)((d >> WinDesc::kTailShift) & 0xFFu);
+                    // pw[0] is the input dword at the output's own index
+                    const uint32_t pw = fetch_base + (uint32_t)(t + kDeep) * 128u;
+                    for (int off = nmin + 1; off < nmax; ++off) {
                         uint32_t v;
-                        if (d & 1) {
-                            const int a = (d + 1) >> 1;
-                            v = align16(p0w[-(a - 1) * 32], p0w[-a * 32]);
+                        if (off & 1) {
+                            const uint32_t a = (uint32_t)(off + 1) >> 1;
+                            v = align16(lds_load(pw - (a - 1u) * 128u), lds_load(pw - a * 128u));
                         } else {
-                            v = p0w[-(d >> 1) * 32];
+                            v = lds_load(pw - ((uint32_t)off >> 1) * 128u);
                         }
                         acc = pk_min(acc, pk_max(v, mask));
                     }
                 }
-                outb[slot_dw + jj * 32] = pk_max(acc, qrow[jj]);
+                outrow[t * 32] = pk_max(acc, qv[t]);
+            };
+            // software pipeline over the task's output dwords: fetch t+1 while t is evaluated
+            fetch(0);
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) {
+                if (t + 1 < np) fetch(t + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < np) finish(t);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        __syncthreads();
+        // chain descriptors of the next task (a scalar load; issued here, after the last LDS fetch of this
+        // task, because scalar loads and LDS reads complete under one counter)
+        if (T + 1 < n_tasks) desc_next = load_desc(sn, qn);
+        if (q == 5) __syncthreads();
+        s = sn;
+        q = qn;
     }
 
     // ---- row k-1: only D_{k-1}[L] is needed; then the key of each ordering and the block minimum
     unsigned long long best = PPO_KEY_NONE;
     if (wave < 6) {
-        const int s = k - 1, c = wave;
-        const uint32_t* in = (s & 1) ? buf0 : buf1;
+        const int sl_ = k - 1, c = wave;
+        const uint32_t* in = (sl_ & 1) ? buf0 : buf1;
         const int node = rest_node(c);
-        const int set = 5 * 6 + c;
-        const uint32_t sl = slotTab[set * 64 + lane];
-        const uint32_t perm = permTab[sl];
+        const uint32_t ent = slotTab[(5 * 6 + c) * 64 + lane];
+        const uint32_t slot_dw = slot_dword(ent);
+        const uint32_t perm = kSlotPerm[par][ent & 511u];
         const bool active = (perm >> 31) != 0u;   // idle lanes sit on the two unused bank columns
-        const uint32_t slot_dw = (sl >> 5) * (uint32_t)(NP * 32) + (sl & 31u);
         const int l = (int)low[node * (L + 1) + L];
-        const int w = L - (l > s ? l : s);
+        const int w = L - (l > sl_ ? l : sl_);
         // input indices (NE-1-w, NE-1]
         const int ulo = gs.NE - w, uhi = gs.NE - 1;
         uint32_t acc = kInf2;
@@ -301,6 +377,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         }
     }
 }
+#undef PPO_STEP
 
 hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin,
                                     uint32_t rank_end, uint64_t* best_key, float* beta_export, hipStream_t stream) {

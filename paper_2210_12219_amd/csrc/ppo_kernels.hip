@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
     }
     __syncthreads();
     {
-        uint16_t* wt = reinterpret_cast<uint16_t*>(base + y.wt_off);
+        uint32_t* wt = reinterpret_cast<uint32_t*>(base + y.wt_off);
         const int rows = k > 2 ? k - 2 : 0, cols = y.wt_cols;
         for (int idx = tid; idx < k * rows * cols; idx += kPreThreads) {
             const int jj = idx % cols, s = (idx / cols) % rows + 1, j = idx / (cols * rows);
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                 }
                 w[h] = (uint32_t)v;
             }
-            wt[idx] = (uint16_t)(w[0] | (w[1] << 8));
+            wt[idx] = WinDesc::pack(w[0], w[1]);
         }
     }
     const int nq = y.npairs * (L - 1);
@@ -91,6 +91,18 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
         dec[1 + below] = x;
     }
     if (tid == 0) dec[0] = 0.0f;
+    __syncthreads();
+    {
+        uint32_t* qa = reinterpret_cast<uint32_t*>(base + y.qa_off);
+        const int cols = y.qa_cols, QD = L / 2 + 1;
+        for (int idx = tid; idx < y.npairs * cols; idx += kPreThreads) {
+            const int p = idx / cols, col = idx - p * cols;
+            const int i0 = col < QD ? 2 * col : 2 * (col - QD - 1) + 1;
+            const uint32_t v0 = (i0 >= 0 && i0 <= L - 2) ? qc[p * L + i0] : kCodeInf;
+            const uint32_t v1 = (i0 + 1 >= 0 && i0 + 1 <= L - 2) ? qc[p * L + i0 + 1] : kCodeInf;
+            qa[idx] = v0 | (v1 << 16);
+        }
+    }
 }
 
 __global__ void init_keys_kernel(unsigned long long* keys, int n) {
