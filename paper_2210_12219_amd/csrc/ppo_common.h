@@ -24,26 +24,30 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
 //   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
 //   low [k][L+1] u32  the lo table again, one dword per entry (for scalar loads)
-//   wt  [k][k-2][wt_cols] u32   chain descriptors for the grouped kernel: for node j, DP row s = 1..k-2
-//       and output dword jj (positions e = 2jj+s and e+1 of row s), from the window lengths
+//   wt  [k][k-2][wt_cols][4] u32   chain descriptors for the grouped kernel: for node j, DP row
+//       s = 1..k-2 and output dword jj (positions e = 2jj+s and e+1 of row s), from the window lengths
 //       w = e - max(lo[j][e], s) if s+1 <= e <= L-k+1+s, else 0 (wx for e, wy for e+1), see WinDesc
 //   qa  [npairs][qa_cols] u32   the codes of qc again, two per dword, in both alignments, for the
 //       grouped kernel: column a < QD holds (q[2a], q[2a+1]); column QD+1+a holds (q[2a+1], q[2a+2])
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
-// nmin = min(wx,wy), nmax = max(wx,wy):  steps = nmin/2 (both positions take two offsets per step),
-// odd = nmin&1, ntail = nmax-nmin offsets that only the longer window has.
+// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, four dwords.
+// With nmin = min(wx,wy), nmax = max(wx,wy), ntail = nmax - nmin:
+//   ctrl      bits 0..6  steps = nmin/2 (both positions take two offsets per step)
+//             bit  7     ntail >= 2 (only the first position's window can be that much longer)
+//             bits 8..15 nmin, bits 16..23 nmax
+//   oddmask   0 if nmin is odd, else +inf in both halves: max(v, oddmask) keeps or drops offset nmin-1
+//   tailmask  if ntail == 1: +inf in the half of the shorter window, else +inf in both halves
+//   selmask   all ones if nmin is odd, else 0: picks the dword that holds offset nmin
 struct WinDesc {
-    static constexpr uint32_t kStepsMask = 0x7Fu;   // bits 0..6: steps
-    static constexpr int kOddBit = 7;               // nmin is odd
-    static constexpr int kXLongerBit = 8;           // wx > wy
-    static constexpr int kTailBit = 9;              // ntail >= 1
-    static constexpr int kLongTailBit = 10;         // ntail >= 2
-    static constexpr int kTailShift = 16;           // bits 16..23: ntail
-    __host__ __device__ static uint32_t pack(uint32_t wx, uint32_t wy) {
+    static constexpr uint32_t kStepsMask = 0x7Fu;
+    static constexpr uint32_t kLongTail = 0x80u;
+    __host__ __device__ static void pack(uint32_t wx, uint32_t wy, uint32_t out[4]) {
+        const uint32_t inf = kCodeInf, inf2 = kCodeInf | (kCodeInf << 16);
         const uint32_t nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx, ntail = nmax - nmin;
-        return (nmin >> 1) | ((nmin & 1u) << kOddBit) | ((wx > wy ? 1u : 0u) << kXLongerBit) |
-               ((ntail >= 1u ? 1u : 0u) << kTailBit) | ((ntail >= 2u ? 1u : 0u) << kLongTailBit) |
-               (ntail << kTailShift);
+        out[0] = (nmin >> 1) | (ntail >= 2u ? kLongTail : 0u) | (nmin << 8) | (nmax << 16);
+        out[1] = (nmin & 1u) ? 0u : inf2;
+        out[2] = ntail == 1u ? (wx > wy ? (inf << 16) : inf) : inf2;
+        out[3] = (nmin & 1u) ? 0xFFFFFFFFu : 0u;
     }
 };
 
@@ -65,9 +69,10 @@ struct Layout {
         off = align_up(off + ((size_t)y.npairs * (L - 1) + 2) * 4, 16);
         y.low_off = (uint32_t)off;
         off = align_up(off + (size_t)k * (L + 1) * 4, 16);
+        off = align_up(off, 64);
         y.wt_off = (uint32_t)off;
         y.wt_cols = (int)align_up((size_t)((L - k + 2 + 1) / 2), 4);
-        off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * 4, 16);
+        off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * 16, 16);
         y.qa_off = (uint32_t)off;
         y.qa_cols = 2 * (L / 2 + 1) + 2;
         off = align_up(off + (size_t)y.npairs * y.qa_cols * 4, 256);

@@ -196,147 +196,149 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         }
     }
 
-    // ---- rows 1 .. k-2 as one sequence of tasks T = (s-1)*6 + q; the schedule entry and the chain
-    //      descriptors of task T+1 are requested while task T runs
-    const int n_tasks = 6 * (k - 2);
-    auto task_set = [&](int s, int c) -> int { return s < p0 ? 36 + c : (s - p0) * 6 + c; };
-    auto task_c = [&](int q) -> int {
-        int c = wave + q;
-        c = c >= 12 ? c - 12 : c;
-        return c >= 6 ? c - 6 : c;
+    // ---- rows 1 .. k-2.  A task = (lane set, chunk of four output dwords).  Its inputs are the 13 input
+    //      dwords B[j] = dword (jbeg - 9 + j) of the lane's row (the four at the outputs' own indices and
+    //      the nine below them), the next link's quotients for the four outputs and the four chain
+    //      descriptors.  All of it is requested one task ahead, into a second set of registers, so that a
+    //      task never waits for its own loads.
+    const uint32_t* __restrict__ wt4 = wt;
+    constexpr int kNB = kChunkPairs + kDeep + 1;
+    struct TaskAux {
+        uint4 D[kChunkPairs];
+        uint32_t qv[kChunkPairs];
+        uint32_t fbase;      // LDS byte address of B[0]
+        uint32_t out_dw;     // dword offset of the first output in the output buffer
     };
-    auto task_jbeg = [&](int q) -> int { return (2 * q + (wave >= 6 ? 1 : 0)) * kChunkPairs; };
-    auto load_desc = [&](int s, int q) -> uint4 {
-        const int c = task_c(q), jbeg = task_jbeg(q);
-        const int node = row_node(s, c);
-        if (jbeg >= NP) return make_uint4(0u, 0u, 0u, 0u);
-        return *reinterpret_cast<const uint4*>(wt + ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
-    };
-    uint32_t ent_next = slotTab[task_set(1, task_c(0)) * 64 + lane];
-    uint4 desc_next = load_desc(1, 0);
     __syncthreads();
 
-    int s = 1, q = 0;
-    for (int T = 0; T < n_tasks; ++T) {
-        const uint32_t ent = ent_next;
-        const uint4 dpack = desc_next;
-        const int jbeg = task_jbeg(q);
+    for (int s = 1; s <= k - 2; ++s) {
         const uint32_t* in = (s & 1) ? buf0 : buf1;
         uint32_t* outb = (s & 1) ? buf1 : buf0;
-        // next task's coordinates; its schedule entry is requested right away
-        const int qn = q == 5 ? 0 : q + 1, sn = q == 5 ? s + 1 : s;
-        if (T + 1 < n_tasks) ent_next = slotTab[task_set(sn, task_c(qn)) * 64 + lane];
+        const int col = link_col(s);
+        const int set0 = s < p0 ? 36 : (s - p0) * 6;
+        const int wsel = wave >= 6 ? 1 : 0;
 
-        if (jbeg < NP) {
-            const uint32_t slot_dw = slot_dword(ent);
-            const uint32_t* qrow = qtab + link_row(s, ent) * QROW + link_col(s) + jbeg;
-            uint32_t* outrow = outb + slot_dw + jbeg * 32;
-            const int np = NP - jbeg < kChunkPairs ? NP - jbeg : kChunkPairs;
-            // LDS byte address of the dword kDeep below dword jbeg of the lane's input row.  It is made
-            // opaque to the compiler so that every fetch below is this register plus a small constant.
-            uint32_t fetch_base = lds_addr(in + slot_dw + (jbeg - kDeep) * 32);
-            asm volatile("" : "+v"(fetch_base));
-            auto lds_at = [&](uint32_t byte_off) -> uint32_t { return lds_load(fetch_base + byte_off); };
-
-            // Fetch for output dword t: the next link's quotients, then the kDeep input dwords below the
-            // output's index (reads below the window are harmless and stay inside LDS), deepest first,
-            // and the dword at the output's own index last: the chain starts with the last ones issued,
-            // so one wait covers the whole fetch.
-            uint32_t lw[kChunkPairs][kDeep + 1], qv[kChunkPairs];
-            auto fetch = [&](int t) {
-                qv[t] = qrow[t];
+        // the lane's schedule entries for the six rounds of this row
+        uint32_t ents[6];
 #pragma unroll
-                for (int i = kDeep; i >= 0; --i) lw[t][i] = lds_at((uint32_t)(t + kDeep - i) * 128u);
-            };
-            // Evaluate output dword t.  The number of steps is consumed bit by bit (4, 2, 1); after each
-            // taken block the fetched dwords are renamed downwards, so that every branch is a plain `if`
-            // and a0, a1 end up as the two dwords at the bottom of the window.
-            auto finish = [&](int t) {
-                const uint32_t d = t == 0 ? dpack.x : t == 1 ? dpack.y : t == 2 ? dpack.z : dpack.w;
-                uint32_t a0 = lw[t][0], a1 = lw[t][1], a2 = lw[t][2], a3 = lw[t][3], a4 = lw[t][4];
-                uint32_t acc = kInf2;
-                if ((d & WinDesc::kStepsMask) >= 8u) {
-                    PPO_STEP(a0, a1); PPO_STEP(a1, a2); PPO_STEP(a2, a3); PPO_STEP(a3, a4);
-                    PPO_STEP(a4, lw[t][5]); PPO_STEP(lw[t][5], lw[t][6]); PPO_STEP(lw[t][6], lw[t][7]);
-                    PPO_STEP(lw[t][7], lw[t][8]);
+        for (int q = 0; q < 6; ++q) {
+            int c = wave + q;
+            c = c >= 12 ? c - 12 : c;
+            c = c >= 6 ? c - 6 : c;
+            ents[q] = slotTab[(set0 + c) * 64 + lane];
+        }
+
+        auto request = [&](int q, uint32_t (&B)[kNB], TaskAux& X) {
+            int c = wave + q;
+            c = c >= 12 ? c - 12 : c;
+            c = c >= 6 ? c - 6 : c;
+            const int jbeg = (2 * q + wsel) * kChunkPairs;
+            const int node = row_node(s, c);
+            const uint32_t ent = ents[q];
+            const uint32_t slot_dw = slot_dword(ent);
+            const uint32_t* qrow = qtab + __umul24((uint32_t)link_row(s, ent), (uint32_t)QROW) + col + jbeg;
+            X.out_dw = slot_dw + jbeg * 32;
+            X.fbase = lds_addr(in + slot_dw + (jbeg - kDeep - 1) * 32);
+            asm volatile("" : "+v"(X.fbase));
+#pragma unroll
+            for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = qrow[t];
+            const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) X.D[t] = dp[t];
+        };
+
+        auto run = [&](int q, const uint32_t (&B)[kNB], const TaskAux& X) {
+            const int jbeg = (2 * q + wsel) * kChunkPairs;
+            const int np = NP - jbeg;   // outputs beyond the row end are computed from null descriptors, not stored
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) {
+                const uint32_t ctrl = X.D[t].x, oddmask = X.D[t].y, tailmask = X.D[t].z, selmask = X.D[t].w;
+                // prefix minima of the chain: M[i] folds steps 1..i, step i = offsets 2i-2 and 2i-1 of both
+                // positions = the dword i-1 below the output's index and the dword straddling it and the next
+                uint32_t M[kDeep + 1];
+                M[0] = kInf2;
+#pragma unroll
+                for (int i = 1; i <= kDeep; ++i) {
+                    const uint32_t hi = B[t + kDeep + 2 - i], lo_ = B[t + kDeep + 1 - i];
+                    M[i] = pk_min3(M[i - 1], hi, align16(hi, lo_));
+                }
+                const uint32_t n = ctrl & WinDesc::kStepsMask;
+                const uint32_t idx = n < (uint32_t)kDeep ? n : (uint32_t)kDeep;
+                uint32_t acc = M[idx];
+                uint32_t a0 = B[t + kDeep + 1 - idx], a1 = B[t + kDeep - idx];   // dwords idx and idx+1 below
+                if (n > (uint32_t)kDeep) {
                     // the rest of a long chain walks further down the row
-                    uint32_t pa = fetch_base + (uint32_t)t * 128u;   // address of the deepest fetched dword
-                    uint32_t cur = lw[t][8];
-                    int m = (int)(d & WinDesc::kStepsMask) - 8;
-                    while (m >= 4) {
+                    uint32_t pa = X.fbase + (uint32_t)(t + 1) * 128u;   // dword kDeep below the output's index
+                    uint32_t cur = a0;
+                    uint32_t m = n - (uint32_t)kDeep;
+                    while (m >= 4u) {
                         pa -= 512u;
                         const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u), b3 = lds_load(pa + 128u),
                                        b4 = lds_load(pa);
                         PPO_STEP(cur, b1); PPO_STEP(b1, b2); PPO_STEP(b2, b3); PPO_STEP(b3, b4);
                         cur = b4;
-                        m -= 4;
+                        m -= 4u;
                     }
-                    while (m >= 1) {
+                    while (m >= 1u) {
                         pa -= 128u;
                         const uint32_t b1 = lds_load(pa);
                         PPO_STEP(cur, b1);
                         cur = b1;
-                        m -= 1;
+                        m -= 1u;
                     }
                     a0 = cur;
                     a1 = lds_load(pa - 128u);
-                } else {
-                    if (d & 4u) {
-                        PPO_STEP(a0, a1); PPO_STEP(a1, a2); PPO_STEP(a2, a3); PPO_STEP(a3, a4);
-                        a0 = a4; a1 = lw[t][5]; a2 = lw[t][6]; a3 = lw[t][7]; a4 = lw[t][8];
-                    }
-                    if (d & 2u) {
-                        PPO_STEP(a0, a1); PPO_STEP(a1, a2);
-                        a0 = a2; a1 = a3; a2 = a4;
-                    }
-                    if (d & 1u) {
-                        PPO_STEP(a0, a1);
-                        a0 = a1; a1 = a2;
-                    }
                 }
-                // bottom of the window: if the shorter window is odd, one more offset for both positions
-                // (the dword a0); then the offsets that only the longer window has, masked to it
-                const uint32_t mask = (d & (1u << WinDesc::kXLongerBit)) ? (kCodeInf << 16) : kCodeInf;
-                if (d & (1u << WinDesc::kOddBit)) acc = pk_min(acc, a0);
-                if (d & (1u << WinDesc::kTailBit)) {
-                    uint32_t v = a0;
-                    if (d & (1u << WinDesc::kOddBit)) v = align16(a0, a1);
-                    acc = pk_min(acc, pk_max(v, mask));
-                }
-                if (d & (1u << WinDesc::kLongTailBit)) {
-                    const int nmin = 2 * (int)(d & WinDesc::kStepsMask) + (int)((d >> WinDesc::kOddBit) & 1u);
-                    const int nmax = nmin + (int)((d >> WinDesc::kTailShift) & 0xFFu);
-                    // pw[0] is the input dword at the output's own index
-                    const uint32_t pw = fetch_base + (uint32_t)(t + kDeep) * 128u;
-                    for (int off = nmin + 1; off < nmax; ++off) {
-                        uint32_t v;
-                        if (off & 1) {
-                            const uint32_t a = (uint32_t)(off + 1) >> 1;
-                            v = align16(lds_load(pw - (a - 1u) * 128u), lds_load(pw - a * 128u));
-                        } else {
-                            v = lds_load(pw - ((uint32_t)off >> 1) * 128u);
-                        }
-                        acc = pk_min(acc, pk_max(v, mask));
+                // bottom of the shorter window: offset nmin-1 if nmin is odd (dword a0, both positions),
+                // then the single offset nmin that only the longer window may have (masked to its half)
+                acc = pk_min(acc, pk_max(a0, oddmask));
+                const uint32_t al = align16(a0, a1);
+                const uint32_t v = (al & selmask) | (a0 & ~selmask);
+                acc = pk_min(acc, pk_max(v, tailmask));
+                if (ctrl & WinDesc::kLongTail) {
+                    // the first position's window is longer by two or more: fold the input indices
+                    // [2jj - nmax + 1, 2jj - nmin] dword by dword, then across the two halves
+                    const uint32_t nmin = (ctrl >> 8) & 0xFFu, nmax = (ctrl >> 16) & 0xFFu;
+                    const uint32_t own = X.fbase + (uint32_t)(t + kDeep + 1) * 128u;   // dword at the output's index
+                    // offsets from the output's index: hi_off = nmin (top), lo_off = nmax-1 (bottom)
+                    uint32_t a_hi = nmin >> 1, a_lo = nmax >> 1;   // dwords below `own` holding top and bottom... see below
+                    uint32_t tacc = kInf2;
+                    // top index 2jj - nmin: even nmin -> low half of dword nmin/2 below (its high half is above the range)
+                    if ((nmin & 1u) == 0u) {
+                        tacc = pk_max(lds_load(own - a_hi * 128u), kCodeInf << 16);
+                        a_hi += 1u;
+                    } else {
+                        a_hi = (nmin + 1u) >> 1;
                     }
+                    // bottom index 2jj - nmax + 1: even nmax -> high half of dword nmax/2 below
+                    if ((nmax & 1u) == 0u) {
+                        tacc = pk_min(tacc, pk_max(lds_load(own - a_lo * 128u), kCodeInf));
+                        a_lo -= 1u;
+                    } else {
+                        a_lo = (nmax - 1u) >> 1;
+                    }
+                    for (uint32_t a = a_hi; a <= a_lo; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
+                    tacc = pk_min(tacc, align16(tacc, tacc));
+                    acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                 }
-                outrow[t * 32] = pk_max(acc, qv[t]);
-            };
-            // software pipeline over the task's output dwords: fetch t+1 while t is evaluated
-            fetch(0);
-#pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) {
-                if (t + 1 < np) fetch(t + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (t < np) finish(t);
-                __builtin_amdgcn_sched_barrier(0);
+                if (t < np) outb[X.out_dw + t * 32] = pk_max(acc, X.qv[t]);
             }
+        };
+
+        uint32_t B0[kNB], B1[kNB];
+        TaskAux X0, X1;
+        request(0, B0, X0);
+        for (int q = 0; q < 6; q += 2) {
+            const bool live1 = (2 * (q + 1) + wsel) * kChunkPairs < NP;
+            const bool live0 = (2 * q + wsel) * kChunkPairs < NP;
+            if (live1) request(q + 1, B1, X1);
+            if (live0) run(q, B0, X0);
+            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, B0, X0);
+            if (live1) run(q + 1, B1, X1);
         }
-        // chain descriptors of the next task (a scalar load; issued here, after the last LDS fetch of this
-        // task, because scalar loads and LDS reads complete under one counter)
-        if (T + 1 < n_tasks) desc_next = load_desc(sn, qn);
-        if (q == 5) __syncthreads();
-        s = sn;
-        q = qn;
+        __syncthreads();
     }
 
     // ---- row k-1: only D_{k-1}[L] is needed; then the key of each ordering and the block minimum

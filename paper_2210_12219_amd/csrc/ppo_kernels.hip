@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                 }
                 w[h] = (uint32_t)v;
             }
-            wt[idx] = WinDesc::pack(w[0], w[1]);
+            WinDesc::pack(w[0], w[1], wt + 4 * idx);
         }
     }
     const int nq = y.npairs * (L - 1);
