@@ -13,6 +13,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-fno-fast-math", "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
+    # small dynamically indexed register arrays (DP chain prefixes) must stay in VGPRs, not scratch
+    "-mllvm", "-amdgpu-promote-alloca-to-vector-vgpr-ratio=2",
     # packed-FP32 forms are never wanted here (the path is integer/min/max work)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",

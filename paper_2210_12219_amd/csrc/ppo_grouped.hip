@@ -202,6 +202,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //      descriptors.  All of it is requested one task ahead, into a second set of registers, so that a
     //      task never waits for its own loads.
     const uint32_t* __restrict__ wt4 = wt;
+    uint32_t vzero;   // a zero the compiler cannot see through, kept in a vector register
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
     constexpr int kNB = kChunkPairs + kDeep + 1;
     struct TaskAux {
         uint4 D[kChunkPairs];
@@ -244,7 +246,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = qrow[t];
-            const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg));
+            // The descriptors are the same for every lane, but they are fetched with vector loads on purpose:
+            // scalar loads complete under the same counter as LDS reads, out of order, so one in flight
+            // would make every wait for an LDS result a wait for everything.
+            const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg)) + vzero;
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) X.D[t] = dp[t];
         };
@@ -252,21 +257,31 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         auto run = [&](int q, const uint32_t (&B)[kNB], const TaskAux& X) {
             const int jbeg = (2 * q + wsel) * kChunkPairs;
             const int np = NP - jbeg;   // outputs beyond the row end are computed from null descriptors, not stored
+            // G[j]: the dword straddling input dwords j and j+1 (upper code of j, lower code of j+1)
+            uint32_t G[kNB - 1];
+#pragma unroll
+            for (int j = 0; j < kNB - 1; ++j) G[j] = align16(B[j + 1], B[j]);
+            // prefix minima of the four chains: M[t][i] folds steps 1..i of output t, step i = offsets 2i-2
+            // and 2i-1 of both positions = the dword i-1 below the output's index and the one straddling it
+            // and the next.  Four independent chains in one basic block.
+            uint32_t M0[kDeep + 1], M1[kDeep + 1], M2[kDeep + 1], M3[kDeep + 1];   // one register block each
+            uint32_t ctrl[kChunkPairs];
+            M0[0] = M1[0] = M2[0] = M3[0] = kInf2;
+#pragma unroll
+            for (int t = 0; t < kChunkPairs; ++t) ctrl[t] = __builtin_amdgcn_readfirstlane(X.D[t].x);
+#pragma unroll
+            for (int i = 1; i <= kDeep; ++i) {
+                M0[i] = pk_min3(M0[i - 1], B[0 + kDeep + 2 - i], G[0 + kDeep + 1 - i]);
+                M1[i] = pk_min3(M1[i - 1], B[1 + kDeep + 2 - i], G[1 + kDeep + 1 - i]);
+                M2[i] = pk_min3(M2[i - 1], B[2 + kDeep + 2 - i], G[2 + kDeep + 1 - i]);
+                M3[i] = pk_min3(M3[i - 1], B[3 + kDeep + 2 - i], G[3 + kDeep + 1 - i]);
+            }
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                const uint32_t ctrl = X.D[t].x, oddmask = X.D[t].y, tailmask = X.D[t].z, selmask = X.D[t].w;
-                // prefix minima of the chain: M[i] folds steps 1..i, step i = offsets 2i-2 and 2i-1 of both
-                // positions = the dword i-1 below the output's index and the dword straddling it and the next
-                uint32_t M[kDeep + 1];
-                M[0] = kInf2;
-#pragma unroll
-                for (int i = 1; i <= kDeep; ++i) {
-                    const uint32_t hi = B[t + kDeep + 2 - i], lo_ = B[t + kDeep + 1 - i];
-                    M[i] = pk_min3(M[i - 1], hi, align16(hi, lo_));
-                }
-                const uint32_t n = ctrl & WinDesc::kStepsMask;
+                const uint32_t oddmask = X.D[t].y, tailmask = X.D[t].z, selmask = X.D[t].w;
+                const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
                 const uint32_t idx = n < (uint32_t)kDeep ? n : (uint32_t)kDeep;
-                uint32_t acc = M[idx];
+                uint32_t acc = t == 0 ? M0[idx] : t == 1 ? M1[idx] : t == 2 ? M2[idx] : M3[idx];
                 uint32_t a0 = B[t + kDeep + 1 - idx], a1 = B[t + kDeep - idx];   // dwords idx and idx+1 below
                 if (n > (uint32_t)kDeep) {
                     // the rest of a long chain walks further down the row
@@ -297,29 +312,27 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 const uint32_t al = align16(a0, a1);
                 const uint32_t v = (al & selmask) | (a0 & ~selmask);
                 acc = pk_min(acc, pk_max(v, tailmask));
-                if (ctrl & WinDesc::kLongTail) {
-                    // the first position's window is longer by two or more: fold the input indices
-                    // [2jj - nmax + 1, 2jj - nmin] dword by dword, then across the two halves
-                    const uint32_t nmin = (ctrl >> 8) & 0xFFu, nmax = (ctrl >> 16) & 0xFFu;
+                if (ctrl[t] & WinDesc::kLongTail) {
+                    // the first position's window is longer by two or more: fold its extra offsets
+                    // nmin .. nmax-1 dword by dword, then across the two halves.  The dword `a` below the
+                    // output's index holds offset 2a in its lower half and offset 2a-1 in its upper half.
+                    const uint32_t nmin = (ctrl[t] >> 8) & 0xFFu, nmax = (ctrl[t] >> 16) & 0xFFu;
                     const uint32_t own = X.fbase + (uint32_t)(t + kDeep + 1) * 128u;   // dword at the output's index
-                    // offsets from the output's index: hi_off = nmin (top), lo_off = nmax-1 (bottom)
-                    uint32_t a_hi = nmin >> 1, a_lo = nmax >> 1;   // dwords below `own` holding top and bottom... see below
+                    uint32_t a_first, a_last;
                     uint32_t tacc = kInf2;
-                    // top index 2jj - nmin: even nmin -> low half of dword nmin/2 below (its high half is above the range)
-                    if ((nmin & 1u) == 0u) {
-                        tacc = pk_max(lds_load(own - a_hi * 128u), kCodeInf << 16);
-                        a_hi += 1u;
+                    if ((nmin & 1u) == 0u) {   // top offset nmin is a lower half: the upper half is out of range
+                        tacc = pk_max(lds_load(own - (nmin >> 1) * 128u), kCodeInf << 16);
+                        a_first = (nmin >> 1) + 1u;
                     } else {
-                        a_hi = (nmin + 1u) >> 1;
+                        a_first = (nmin + 1u) >> 1;
                     }
-                    // bottom index 2jj - nmax + 1: even nmax -> high half of dword nmax/2 below
-                    if ((nmax & 1u) == 0u) {
-                        tacc = pk_min(tacc, pk_max(lds_load(own - a_lo * 128u), kCodeInf));
-                        a_lo -= 1u;
+                    if ((nmax & 1u) == 0u) {   // bottom offset nmax-1 is an upper half: the lower half is out of range
+                        tacc = pk_min(tacc, pk_max(lds_load(own - (nmax >> 1) * 128u), kCodeInf));
+                        a_last = (nmax >> 1) - 1u;
                     } else {
-                        a_lo = (nmax - 1u) >> 1;
+                        a_last = (nmax - 1u) >> 1;
                     }
-                    for (uint32_t a = a_hi; a <= a_lo; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
+                    for (uint32_t a = a_first; a <= a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
                     tacc = pk_min(tacc, align16(tacc, tacc));
                     acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                 }
