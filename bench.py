@@ -32,8 +32,10 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 def algorithmic_ops_per_ordering(w):
     """Mean over all k! orderings and all instances of the work the DP recurrence itself asks for:
     one min per (segment start i -> segment end e) candidate inside the memory window, and one max per
-    row entry to form max(D[i], q[i-1]).  Row s uses node pi_s only through its window table, and every
-    node sits at every position in (k-1)! orderings, so the mean is a sum over (row, node) pairs."""
+    row entry to form max(D[i], q[i-1]).  Rows 1..k-2 are counted over their whole range of segment
+    ends; of the last row only D[L] is counted, because that is all the result depends on and all the
+    kernel evaluates.  Row s uses node pi_s only through its window table, and every node sits at every
+    position in (k-1)! orderings, so the mean is a sum over (row, node) pairs."""
     L, k = w.L, w.k
     cand = 0.0
     for n in range(w.n_inst):
@@ -43,7 +45,7 @@ def algorithmic_ops_per_ordering(w):
             # lo[e] = first i with P[e] - P[i] <= cap
             lo = np.array([int(np.argmax(P[e] - P[: e + 1] <= cap)) for e in range(L + 1)])
             for s in range(1, k):
-                e = np.arange(s + 1, L - (k - 1 - s) + 1)
+                e = np.arange(s + 1, L - (k - 1 - s) + 1) if s < k - 1 else np.array([L])
                 cand += np.maximum(e - np.maximum(lo[e], s), 0).sum() / k
     cand /= w.n_inst
     maxops = (k - 1) * (L - k + 1)

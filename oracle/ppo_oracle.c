@@ -64,7 +64,8 @@ static int check_scalars(int L, int k) {
     return ORC_OK;
 }
 
-/* Data preconditions: finite, t,m,M >= 0, off-diagonal B > 0 and bit-symmetric. */
+/* Data preconditions: finite, t >= +0 (negative zero would give gamma = -0, whose bit pattern does not
+ * order like its value), m,M >= 0, off-diagonal B > 0 and bit-symmetric. */
 int ppo_oracle_check_inputs(const float *t, const float *m, int L, const float *M, const float *B, int k,
                             int n_inst) {
     int rc = check_scalars(L, k);
@@ -73,7 +74,7 @@ int ppo_oracle_check_inputs(const float *t, const float *m, int L, const float *
     for (int n = 0; n < n_inst; ++n) {
         for (int i = 0; i < L; ++i) {
             float a = t[(size_t)n * L + i], b = m[(size_t)n * L + i];
-            if (!isfinite(a) || !isfinite(b) || a < 0.0f || b < 0.0f) return ORC_EDATA;
+            if (!isfinite(a) || !isfinite(b) || a < 0.0f || signbit(a) || b < 0.0f) return ORC_EDATA;
         }
         for (int j = 0; j < k; ++j) {
             float c = M[(size_t)n * k + j];

@@ -285,6 +285,8 @@ def test_precondition_violations_are_rejected():
     assert O.check_inputs(t, m, M, B3) == -3          # zero bandwidth
     t2 = t.copy(); t2[0, 2] = -1.0
     assert O.check_inputs(t2, m, M, B) == -3
+    t3 = t.copy(); t3[0, 1] = -0.0
+    assert O.check_inputs(t3, m, M, B) == -3          # negative zero transfer size
     m2 = m.copy(); m2[0, 0] = np.nan
     assert O.check_inputs(t, m2, M, B) == -3
     with pytest.raises(O.OracleError):
