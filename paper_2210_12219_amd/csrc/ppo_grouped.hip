@@ -230,6 +230,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             ents[q] = slotTab[(set0 + c) * 64 + lane];
         }
 
+        // The register array holds the 13 dwords in descending address order (B[kNB-1-j] = input dword j of
+        // the fetch), so that the three register-indexed reads of an output use one and the same index.
         auto request = [&](int q, uint32_t (&B)[kNB], TaskAux& X) {
             int c = wave + q;
             c = c >= 12 ? c - 12 : c;
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             X.fbase = lds_addr(in + slot_dw + (jbeg - kDeep - 1) * 32);
             asm volatile("" : "+v"(X.fbase));
 #pragma unroll
-            for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
+            for (int j = 0; j < kNB; ++j) B[kNB - 1 - j] = lds_load(X.fbase + (uint32_t)j * 128u);
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = qrow[t];
             // The descriptors are the same for every lane, but they are fetched with vector loads on purpose:
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             // G[j]: the dword straddling input dwords j and j+1 (upper code of j, lower code of j+1)
             uint32_t G[kNB - 1];
 #pragma unroll
-            for (int j = 0; j < kNB - 1; ++j) G[j] = align16(B[j + 1], B[j]);
+            for (int j = 0; j < kNB - 1; ++j) G[j] = align16(B[kNB - 2 - j], B[kNB - 1 - j]);
             // prefix minima of the four chains: M[t][i] folds steps 1..i of output t, step i = offsets 2i-2
             // and 2i-1 of both positions = the dword i-1 below the output's index and the one straddling it
             // and the next.  Four independent chains in one basic block.
@@ -271,10 +273,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             for (int t = 0; t < kChunkPairs; ++t) ctrl[t] = __builtin_amdgcn_readfirstlane(X.D[t].x);
 #pragma unroll
             for (int i = 1; i <= kDeep; ++i) {
-                M0[i] = pk_min3(M0[i - 1], B[0 + kDeep + 2 - i], G[0 + kDeep + 1 - i]);
-                M1[i] = pk_min3(M1[i - 1], B[1 + kDeep + 2 - i], G[1 + kDeep + 1 - i]);
-                M2[i] = pk_min3(M2[i - 1], B[2 + kDeep + 2 - i], G[2 + kDeep + 1 - i]);
-                M3[i] = pk_min3(M3[i - 1], B[3 + kDeep + 2 - i], G[3 + kDeep + 1 - i]);
+                M0[i] = pk_min3(M0[i - 1], B[kNB - 1 - (0 + kDeep + 2 - i)], G[0 + kDeep + 1 - i]);
+                M1[i] = pk_min3(M1[i - 1], B[kNB - 1 - (1 + kDeep + 2 - i)], G[1 + kDeep + 1 - i]);
+                M2[i] = pk_min3(M2[i - 1], B[kNB - 1 - (2 + kDeep + 2 - i)], G[2 + kDeep + 1 - i]);
+                M3[i] = pk_min3(M3[i - 1], B[kNB - 1 - (3 + kDeep + 2 - i)], G[3 + kDeep + 1 - i]);
             }
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
                 const uint32_t idx = n < (uint32_t)kDeep ? n : (uint32_t)kDeep;
                 uint32_t acc = t == 0 ? M0[idx] : t == 1 ? M1[idx] : t == 2 ? M2[idx] : M3[idx];
-                uint32_t a0 = B[t + kDeep + 1 - idx], a1 = B[t + kDeep - idx];   // dwords idx and idx+1 below
+                uint32_t a0 = B[kNB - 2 - kDeep - t + idx], a1 = B[kNB - 1 - kDeep - t + idx];   // dwords idx, idx+1 below
                 if (n > (uint32_t)kDeep) {
                     // the rest of a long chain walks further down the row
                     uint32_t pa = X.fbase + (uint32_t)(t + 1) * 128u;   // dword kDeep below the output's index
