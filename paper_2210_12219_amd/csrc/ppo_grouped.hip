@@ -96,15 +96,18 @@ bool grouped_supported(int L, int k) {
 template <bool EXPORT>
 __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     Layout y, const unsigned char* __restrict__ ws, uint32_t rank_begin, uint32_t rank_end, uint32_t group_begin,
-    unsigned long long* __restrict__ best_key, float* __restrict__ beta_export) {
+    uint32_t group_end, uint32_t groups_per_block, unsigned long long* __restrict__ best_key,
+    float* __restrict__ beta_export) {
     extern __shared__ __align__(16) uint32_t lds[];
     const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = k - 6;
     const GroupedShape gs = GroupedShape::make(L, k);
     const int NP = gs.NP, QD = gs.QD, QROW = gs.QROW, nA = gs.nA, nB = gs.nB;
-    const uint32_t group = group_begin + blockIdx.x;
-    const uint32_t par = group & 1u, pr = group >> 1;
+    // A workgroup handles groups_per_block groups of one parity, one after the other (group_begin is even,
+    // so the parity of a group is the parity of its index); the schedule table is staged once.
+    const uint32_t par = blockIdx.x & 1u;
+    const uint32_t group_first = group_begin + par + 2u * (blockIdx.x >> 1) * groups_per_block;
 
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
@@ -116,6 +119,18 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     uint32_t* const buf1 = buf0 + gs.buf_dwords;
     uint32_t* const qtab = lds + gs.q_off;
     uint32_t* const slotTab = lds + gs.slot_off;
+
+    {
+        const uint32_t* src = &kLaneSlot[par][0][0];
+        for (int i = tid; i < 42 * 64; i += kGrpThreads) slotTab[i] = src[i];
+        for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
+    }
+    unsigned long long best = PPO_KEY_NONE;
+
+    for (uint32_t gi = 0; gi < groups_per_block; ++gi) {
+    const uint32_t group = group_first + 2u * gi;
+    if (group >= group_end) break;
+    const uint32_t pr = group >> 1;
 
     // ---- prefix: positions 0..p0-1 from the Lehmer digits of pr (weights (k-1-p)!/6!); `avail` ends up
     //      holding the six remaining nodes in ascending order, four bits each
@@ -143,11 +158,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         return (int)((packed >> (4 * idx)) & 0xFull);
     };
 
-    // ---- stage the schedule and the quotient rows of the links this group can cross
+    // ---- stage the quotient rows of the links this group can cross
     {
-        const uint32_t* src = &kLaneSlot[par][0][0];
-        for (int i = tid; i < 42 * 64; i += kGrpThreads) slotTab[i] = src[i];
-        for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
         for (int row = wave; row < gs.nQ; row += kGrpWaves) {
             int a, b;
             if (row < nA) {
@@ -356,8 +368,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         __syncthreads();
     }
 
-    // ---- row k-1: only D_{k-1}[L] is needed; then the key of each ordering and the block minimum
-    unsigned long long best = PPO_KEY_NONE;
+    // ---- row k-1: only D_{k-1}[L] is needed; then the key of each ordering, folded into the lane's best
     if (wave < 6) {
         const int sl_ = k - 1, c = wave;
         const uint32_t* in = (sl_ & 1) ? buf0 : buf1;
@@ -381,9 +392,13 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t r = pr * 720u + ((perm >> 18) & 1023u);
         if (active && r >= rank_begin && r < rank_end) {
             if (EXPORT) beta_export[r - rank_begin] = __uint_as_float(bits);
-            best = ((unsigned long long)bits << 32) | r;
+            const unsigned long long key = ((unsigned long long)bits << 32) | r;
+            best = key < best ? key : best;
         }
     }
+    __syncthreads();   // the next group's first row overwrites the buffer this row reads
+    }  // groups of this workgroup
+
     if (!EXPORT) {
         for (int off = 32; off >= 1; off >>= 1) {
             const unsigned long long o = __shfl_xor(best, off, 64);
@@ -401,21 +416,25 @@ hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws,
     if (rank_end <= rank_begin || n_inst == 0) return hipSuccess;
     const GroupedShape gs = GroupedShape::make(y.L, y.k);
     const uint32_t gbeg = 2u * (rank_begin / 720u), gend = 2u * ((rank_end + 719u) / 720u);
-    const dim3 grid(gend - gbeg, n_inst), block(kGrpThreads);
+    // groups per workgroup: enough workgroups to fill the chip several times over, else as many as 8
+    uint32_t gpb = 8;
+    while (gpb > 1 && (uint64_t)((gend - gbeg) / 2 / gpb) * 2u * (uint64_t)n_inst < 4096u) gpb >>= 1;
+    const uint32_t pairs = (gend - gbeg) / 2;
+    const dim3 grid(2u * ((pairs + gpb - 1) / gpb), n_inst), block(kGrpThreads);
     hipError_t e;
     if (beta_export) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(enumerate_grouped_kernel<true>, grid, block, gs.total_bytes, stream, y,
-                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,
                            reinterpret_cast<unsigned long long*>(best_key), beta_export);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(enumerate_grouped_kernel<false>, grid, block, gs.total_bytes, stream, y,
-                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,
                            reinterpret_cast<unsigned long long*>(best_key), beta_export);
     }
     return hipGetLastError();
