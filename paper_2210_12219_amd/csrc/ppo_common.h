@@ -30,6 +30,8 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   qa  [npairs][qa_cols] u32   the codes of qc again, two per dword, in both alignments, for the
 //       grouped kernel: column a < QD holds (q[2a], q[2a+1]); column QD+1+a holds (q[2a+1], q[2a+2])
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
+//   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
+//       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
 // Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, four dwords.
 // With nmin = min(wx,wy), nmax = max(wx,wy), ntail = nmax - nmin:
 //   ctrl      bits 0..6  steps = nmin/2 (both positions take two offsets per step)
@@ -53,7 +55,7 @@ struct WinDesc {
 
 struct Layout {
     int L, k, npairs, wt_cols, qa_cols;
-    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, stride;  // bytes within one instance's slice
+    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, d0_off, stride;  // bytes within one instance's slice
 
     __host__ __device__ static Layout make(int L, int k) {
         Layout y;
@@ -75,7 +77,9 @@ struct Layout {
         off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * 16, 16);
         y.qa_off = (uint32_t)off;
         y.qa_cols = 2 * (L / 2 + 1) + 2;
-        off = align_up(off + (size_t)y.npairs * y.qa_cols * 4, 256);
+        off = align_up(off + (size_t)y.npairs * y.qa_cols * 4, 16);
+        y.d0_off = (uint32_t)off;
+        off = align_up(off + (size_t)k * y.wt_cols * 4, 256);
         y.stride = (uint32_t)off;
         return y;
     }

@@ -126,6 +126,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
     }
     unsigned long long best = PPO_KEY_NONE;
+    uint32_t vzero;   // a zero the compiler cannot see through, kept in a vector register
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
 
     for (uint32_t gi = 0; gi < groups_per_block; ++gi) {
     const uint32_t group = group_first + 2u * gi;
@@ -190,6 +192,14 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         return __umul24((ent >> 5) & 15u, (uint32_t)(NP * 32)) + (ent & 31u);
     };
 
+    // what the last row needs from global memory is requested now, a whole group's work ahead of its use
+    uint32_t last_ent = 0, last_perm = 0, last_lo = 0;
+    if (wave < 6) {
+        last_ent = slotTab[(5 * 6 + wave) * 64 + lane];
+        last_perm = (&kSlotPerm[par][0] + vzero)[last_ent & 511u];
+        last_lo = (low + vzero)[rest_node(wave) * (L + 1) + L];
+    }
+
     // ---- row 0: g_1[i] = max(D_0[i], q_{pi_0,pi_1}[i-1]) at index i, D_0[i] = 0 if layers [0,i) fit node pi_0
     {
         const int c = wave % 6, half = wave / 6;
@@ -198,14 +208,18 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t ent = slotTab[set * 64 + lane];
         uint32_t* out = buf0 + slot_dword(ent);
         const uint32_t* qrow = qtab + link_row(0, ent) * QROW + link_col(0);
-        const uint32_t* lowrow = low + node * (L + 1);
+        // the initial row of the node, two codes per dword (vector loads: see the note on descriptors below)
+        const uint32_t* d0row = reinterpret_cast<const uint32_t*>(base + y.d0_off) + node * y.wt_cols + vzero;
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
-        for (int jj = j0; jj < j1; ++jj) {
-            const int ix = 2 * jj, iy = 2 * jj + 1;
-            const uint32_t dx = (ix >= 1 && ix <= L - k + 1 && lowrow[ix] == 0u) ? kCodeZero : kCodeInf;
-            const uint32_t dy = (iy <= L - k + 1 && lowrow[iy] == 0u) ? kCodeZero : kCodeInf;
-            out[jj * 32] = pk_max(dx | (dy << 16), qrow[jj]);
+        int jj = j0;
+        for (; jj + 4 <= j1; jj += 4) {
+            const uint32_t e0 = d0row[jj], e1 = d0row[jj + 1], e2 = d0row[jj + 2], e3 = d0row[jj + 3];
+            out[jj * 32] = pk_max(e0, qrow[jj]);
+            out[(jj + 1) * 32] = pk_max(e1, qrow[jj + 1]);
+            out[(jj + 2) * 32] = pk_max(e2, qrow[jj + 2]);
+            out[(jj + 3) * 32] = pk_max(e3, qrow[jj + 3]);
         }
+        for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
     }
 
     // ---- rows 1 .. k-2.  A task = (lane set, chunk of four output dwords).  Its inputs are the 13 input
@@ -214,8 +228,6 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //      descriptors.  All of it is requested one task ahead, into a second set of registers, so that a
     //      task never waits for its own loads.
     const uint32_t* __restrict__ wt4 = wt;
-    uint32_t vzero;   // a zero the compiler cannot see through, kept in a vector register
-    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
     constexpr int kNB = kChunkPairs + kDeep + 1;
     struct TaskAux {
         uint4 D[kChunkPairs];
@@ -223,33 +235,54 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         uint32_t fbase;      // LDS byte address of B[0]
         uint32_t out_dw;     // dword offset of the first output in the output buffer
     };
+    const int wsel = wave >= 6 ? 1 : 0;
+    // the lane's schedule entries for the six rounds of row s
+    auto load_ents = [&](int s, uint32_t (&e)[6]) {
+        const int set0 = s < p0 ? 36 : (s - p0) * 6;
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            int c = wave + q;
+            c = c >= 12 ? c - 12 : c;
+            c = c >= 6 ? c - 6 : c;
+            e[q] = slotTab[(set0 + c) * 64 + lane];
+        }
+    };
+    // The chain descriptors of a task.  They are the same for every lane, but they are fetched with vector
+    // loads on purpose: scalar loads complete under the same counter as LDS reads, out of order, so one in
+    // flight would make every wait for an LDS result a wait for everything.
+    auto load_desc = [&](int s, int q, uint4 (&D)[kChunkPairs]) {
+        int c = wave + q;
+        c = c >= 12 ? c - 12 : c;
+        c = c >= 6 ? c - 6 : c;
+        const int jbeg = (2 * q + wsel) * kChunkPairs;
+        const int node = row_node(s, c);
+        const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg)) + vzero;
+#pragma unroll
+        for (int t = 0; t < kChunkPairs; ++t) D[t] = dp[t];
+    };
+    // what the first task of the next row needs and does not depend on the row before it is requested
+    // ahead of the barrier that ends that row
+    uint32_t ents_pre[6];
+    uint4 desc_pre[kChunkPairs];
+    load_ents(1, ents_pre);
+    load_desc(1, 0, desc_pre);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
         const uint32_t* in = (s & 1) ? buf0 : buf1;
         uint32_t* outb = (s & 1) ? buf1 : buf0;
         const int col = link_col(s);
-        const int set0 = s < p0 ? 36 : (s - p0) * 6;
-        const int wsel = wave >= 6 ? 1 : 0;
-
-        // the lane's schedule entries for the six rounds of this row
         uint32_t ents[6];
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
-            int c = wave + q;
-            c = c >= 12 ? c - 12 : c;
-            c = c >= 6 ? c - 6 : c;
-            ents[q] = slotTab[(set0 + c) * 64 + lane];
-        }
+        for (int q = 0; q < 6; ++q) ents[q] = ents_pre[q];
 
         // The register array holds the 13 dwords in descending address order (B[kNB-1-j] = input dword j of
         // the fetch), so that the three register-indexed reads of an output use one and the same index.
-        auto request = [&](int q, uint32_t (&B)[kNB], TaskAux& X) {
+        auto request = [&](int q, uint32_t (&B)[kNB], TaskAux& X, bool with_desc) {
             int c = wave + q;
             c = c >= 12 ? c - 12 : c;
             c = c >= 6 ? c - 6 : c;
             const int jbeg = (2 * q + wsel) * kChunkPairs;
-            const int node = row_node(s, c);
             const uint32_t ent = ents[q];
             const uint32_t slot_dw = slot_dword(ent);
             const uint32_t* qrow = qtab + __umul24((uint32_t)link_row(s, ent), (uint32_t)QROW) + col + jbeg;
@@ -260,12 +293,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             for (int j = 0; j < kNB; ++j) B[kNB - 1 - j] = lds_load(X.fbase + (uint32_t)j * 128u);
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = qrow[t];
-            // The descriptors are the same for every lane, but they are fetched with vector loads on purpose:
-            // scalar loads complete under the same counter as LDS reads, out of order, so one in flight
-            // would make every wait for an LDS result a wait for everything.
-            const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg)) + vzero;
-#pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) X.D[t] = dp[t];
+            if (with_desc) load_desc(s, q, X.D);
         };
 
         auto run = [&](int q, const uint32_t (&B)[kNB], const TaskAux& X) {
@@ -356,28 +384,33 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 
         uint32_t B0[kNB], B1[kNB];
         TaskAux X0, X1;
-        request(0, B0, X0);
+#pragma unroll
+        for (int t = 0; t < kChunkPairs; ++t) X0.D[t] = desc_pre[t];
+        request(0, B0, X0, false);
         for (int q = 0; q < 6; q += 2) {
             const bool live1 = (2 * (q + 1) + wsel) * kChunkPairs < NP;
             const bool live0 = (2 * q + wsel) * kChunkPairs < NP;
-            if (live1) request(q + 1, B1, X1);
+            if (live1) request(q + 1, B1, X1, true);
             if (live0) run(q, B0, X0);
-            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, B0, X0);
+            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, B0, X0, true);
             if (live1) run(q + 1, B1, X1);
+        }
+        if (s + 1 <= k - 2) {
+            load_ents(s + 1, ents_pre);
+            load_desc(s + 1, 0, desc_pre);
         }
         __syncthreads();
     }
 
     // ---- row k-1: only D_{k-1}[L] is needed; then the key of each ordering, folded into the lane's best
     if (wave < 6) {
-        const int sl_ = k - 1, c = wave;
+        const int sl_ = k - 1;
         const uint32_t* in = (sl_ & 1) ? buf0 : buf1;
-        const int node = rest_node(c);
-        const uint32_t ent = slotTab[(5 * 6 + c) * 64 + lane];
+        const uint32_t ent = last_ent;
         const uint32_t slot_dw = slot_dword(ent);
-        const uint32_t perm = kSlotPerm[par][ent & 511u];
+        const uint32_t perm = last_perm;
         const bool active = (perm >> 31) != 0u;   // idle lanes sit on the two unused bank columns
-        const int l = (int)low[node * (L + 1) + L];
+        const int l = (int)__builtin_amdgcn_readfirstlane(last_lo);
         const int w = L - (l > sl_ ? l : sl_);
         // input indices (NE-1-w, NE-1]
         const int ulo = gs.NE - w, uhi = gs.NE - 1;

@@ -73,6 +73,19 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
             WinDesc::pack(w[0], w[1], wt + 4 * idx);
         }
     }
+    {
+        uint32_t* d0 = reinterpret_cast<uint32_t*>(base + y.d0_off);
+        const int cols = y.wt_cols;
+        for (int idx = tid; idx < k * cols; idx += kPreThreads) {
+            const int j = idx / cols, col = idx - j * cols;
+            uint32_t v[2];
+            for (int h = 0; h < 2; ++h) {
+                const int i = 2 * col + h;
+                v[h] = (i >= 1 && i <= L - k + 1 && lo[j * (L + 1) + i] == 0) ? kCodeZero : kCodeInf;
+            }
+            d0[idx] = v[0] | (v[1] << 16);
+        }
+    }
     const int nq = y.npairs * (L - 1);
     for (int idx = tid; idx < nq; idx += kPreThreads) {
         int p = idx / (L - 1), i = idx - p * (L - 1);
