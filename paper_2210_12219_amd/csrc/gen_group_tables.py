@@ -16,10 +16,10 @@ rows are interleaved so that the bank of a slot is its class.  For any position 
 lane `32 + class`, and every half-wave touches 30 distinct banks.
 
 Tables (same for every instance):
-  kLaneSlot[2][42][64]  per lane: bits 0..8 the slot id (index*32 + class) it handles; bits 16..19
-                        the index of the unordered pair {sigma(r), sigma(r+1)} among the 15 pairs of
-                        six (row-major upper triangle) for the set's position r (0 for r = 5 and for
-                        the natural sets); bits 20..22 sigma(0).  Lanes 30, 31, 62, 63 are idle and
+  kLaneSlot[2][42][64]  per lane, 16 bits: bits 0..8 the slot id (index*32 + class) it handles; bits
+                        9..12 the index of the unordered pair {sigma(r), sigma(r+1)} among the 15 pairs
+                        of six (row-major upper triangle) for the set's position r (0 for r = 5 and for
+                        the natural sets); bits 13..15 sigma(0).  Lanes 30, 31, 62, 63 are idle and
                         point at the two unused bank columns (slot ids 30 and 31), so that they never
                         collide with a working lane and need no predicate.
                         Sets 0..35 = (position r, value c) -> r*6 + c; sets 36..41 = all slots in
@@ -112,7 +112,7 @@ def build():
                 v = lane_slot[par][st][lane]
                 p = perm_of.get(v, tuple(range(6)))
                 link = pair6(p[r], p[r + 1]) if (r is not None and r < 5) else 0
-                lane_slot[par][st][lane] = v | (link << 16) | (p[0] << 20)
+                lane_slot[par][st][lane] = v | (link << 9) | (p[0] << 13)
     return lane_slot, slot_perm
 
 
@@ -121,7 +121,7 @@ def main():
     out = ["// Generated by gen_group_tables.py; do not edit.  Lane/slot schedule of the grouped enumeration",
            "// kernel (360 orderings per workgroup, one LDS bank per coset class).",
            "#pragma once", "#include <stdint.h>", "", "namespace ppo {", ""]
-    out.append("__device__ const uint32_t kLaneSlot[2][42][64] = {")
+    out.append("__device__ const uint16_t kLaneSlot[2][42][64] = {")
     for par in range(2):
         out.append(" {")
         for s in range(42):

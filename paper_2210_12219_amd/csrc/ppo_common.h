@@ -24,32 +24,42 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
 //   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
 //   low [k][L+1] u32  the lo table again, one dword per entry (for scalar loads)
-//   wt  [k][k-2][wt_cols][4] u32   chain descriptors for the grouped kernel: for node j, DP row
+//   wt  [k][k-2][wt_cols/4][3][4] u32   chain descriptors for the grouped kernel: for node j, DP row
 //       s = 1..k-2 and output dword jj (positions e = 2jj+s and e+1 of row s), from the window lengths
-//       w = e - max(lo[j][e], s) if s+1 <= e <= L-k+1+s, else 0 (wx for e, wy for e+1), see WinDesc
+//       w = e - max(lo[j][e], s) if s+1 <= e <= L-k+1+s, else 0 (wx for e, wy for e+1), see WinDesc;
+//       the three words of the four outputs of a chunk are stored word by word (ctrl x4, maskA x4, maskB x4)
 //   qa  [npairs][qa_cols] u32   the codes of qc again, two per dword, in both alignments, for the
 //       grouped kernel: column a < QD holds (q[2a], q[2a+1]); column QD+1+a holds (q[2a+1], q[2a+2])
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
 //   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
 //       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
-// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, four dwords.
-// With nmin = min(wx,wy), nmax = max(wx,wy), ntail = nmax - nmin:
-//   ctrl      bits 0..6  steps = nmin/2 (both positions take two offsets per step)
-//             bit  7     ntail >= 2 (only the first position's window can be that much longer)
+// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, three words.
+// With nmin = min(wx,wy), nmax = max(wx,wy), ntail = nmax - nmin and n = nmin/2 full steps, which fold
+// window offsets 0 .. 2n-1 of both positions, one masked step treats offsets 2n and 2n+1:
+//   ctrl      bits 0..6  n
+//             bit  7     ntail >= 2 (only the first position's window can be that much longer; its extra
+//                        offsets nmin .. nmax-1 are folded separately)
 //             bits 8..15 nmin, bits 16..23 nmax
-//   oddmask   0 if nmin is odd, else +inf in both halves: max(v, oddmask) keeps or drops offset nmin-1
-//   tailmask  if ntail == 1: +inf in the half of the shorter window, else +inf in both halves
-//   selmask   all ones if nmin is odd, else 0: picks the dword that holds offset nmin
+//   maskA     per half, 0 if offset 2n is inside that position's window and not left to the separate fold,
+//             else +inf: max(v, maskA) keeps or drops it
+//   maskB     the same for offset 2n+1
 struct WinDesc {
     static constexpr uint32_t kStepsMask = 0x7Fu;
     static constexpr uint32_t kLongTail = 0x80u;
-    __host__ __device__ static void pack(uint32_t wx, uint32_t wy, uint32_t out[4]) {
-        const uint32_t inf = kCodeInf, inf2 = kCodeInf | (kCodeInf << 16);
+    static constexpr int kWords = 3;
+    __host__ __device__ static void pack(uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& maskA, uint32_t& maskB) {
+        const uint32_t inf = kCodeInf;
         const uint32_t nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx, ntail = nmax - nmin;
-        out[0] = (nmin >> 1) | (ntail >= 2u ? kLongTail : 0u) | (nmin << 8) | (nmax << 16);
-        out[1] = (nmin & 1u) ? 0u : inf2;
-        out[2] = ntail == 1u ? (wx > wy ? (inf << 16) : inf) : inf2;
-        out[3] = (nmin & 1u) ? 0xFFFFFFFFu : 0u;
+        const uint32_t n = nmin >> 1;
+        // a window longer by two or more is cut to the shorter one here
+        const uint32_t ex = ntail >= 2u ? nmin : wx, ey = ntail >= 2u ? nmin : wy;
+        ctrl = n | (ntail >= 2u ? kLongTail : 0u) | (nmin << 8) | (nmax << 16);
+        maskA = (2u * n < ex ? 0u : inf) | ((2u * n < ey ? 0u : inf) << 16);
+        maskB = (2u * n + 1u < ex ? 0u : inf) | ((2u * n + 1u < ey ? 0u : inf) << 16);
+    }
+    // dword offset of word `word` of output column jj within the descriptor row of a (node, DP row)
+    __host__ __device__ static uint32_t offset(uint32_t jj, uint32_t word) {
+        return (jj >> 2) * 12u + word * 4u + (jj & 3u);
     }
 };
 
@@ -74,7 +84,7 @@ struct Layout {
         off = align_up(off, 64);
         y.wt_off = (uint32_t)off;
         y.wt_cols = (int)align_up((size_t)((L - k + 2 + 1) / 2), 4);
-        off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * 16, 16);
+        off = align_up(off + (size_t)k * (k > 2 ? k - 2 : 0) * y.wt_cols * WinDesc::kWords * 4, 16);
         y.qa_off = (uint32_t)off;
         y.qa_cols = 2 * (L / 2 + 1) + 2;
         off = align_up(off + (size_t)y.npairs * y.qa_cols * 4, 16);

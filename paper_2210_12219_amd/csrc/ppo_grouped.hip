@@ -26,6 +26,7 @@
 // output dwords.  Wave w takes, in round q = 0..5, the set (w+q) mod 6 and chunk 2q + (w >= 6): every
 // wave meets every node once per row, which evens out the very different window lengths of the nodes.
 #include "ppo_common.h"
+#include "ppo_chain_asm.h"
 #include "ppo_group_tables.h"
 
 namespace ppo {
@@ -34,7 +35,7 @@ constexpr int kGrpWaves = 12;
 constexpr int kGrpThreads = kGrpWaves * 64;
 constexpr int kChunkPairs = 4;                      // output dwords (pairs of positions) per task
 constexpr int kGrpMaxPairs = 6 * 2 * kChunkPairs;   // six rounds of two chunks cover at most 48 dwords
-constexpr int kDeep = 8;                            // input dwords fetched below each output dword
+constexpr int kDeep = PPO_CHAIN_DEPTH;               // chain steps available from prefetched registers
 constexpr uint32_t kInf2 = kCodeInf | (kCodeInf << 16);
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
@@ -74,11 +75,11 @@ struct GroupedShape {
         g.nA = p0 > 1 ? p0 - 1 : 0;   // links inside the prefix
         g.nB = p0 > 0 ? 6 : 0;        // links from the last prefix node to each remaining node
         g.nQ = g.nA + g.nB + 15;      // plus the links among the six remaining nodes
-        g.buf_off = (uint32_t)(kDeep + 1) * 32u;   // room for the fixed-depth fetches below dword 0
+        g.buf_off = (uint32_t)(kDeep + 1) * 32u;   // room for the fixed-depth fetches and the masked step below dword 0
         g.buf_dwords = 12u * g.NP * 32u;
         g.q_off = g.buf_off + 2u * g.buf_dwords;
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
-        g.total_bytes = (g.slot_off + 42u * 64u) * 4u;
+        g.total_bytes = (g.slot_off + 42u * 64u / 2u) * 4u;   // schedule entries are 16 bits
         return g;
     }
 };
@@ -89,6 +90,13 @@ bool grouped_supported(int L, int k) {
     return g.NP <= kGrpMaxPairs && g.total_bytes <= 160u * 1024u;
 }
 
+// 16-bit LDS load and 32-bit LDS store by byte address
+__device__ __forceinline__ uint32_t lds_load_u16(uint32_t addr) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>((uintptr_t)addr);
+}
+__device__ __forceinline__ void lds_store(uint32_t addr, uint32_t v) {
+    *reinterpret_cast<__attribute__((address_space(3))) uint32_t*>((uintptr_t)addr) = v;
+}
 // One step of a chain folds two offsets of both positions: the dword `hi` itself and the dword
 // straddling `lo_` and `hi`.
 #define PPO_STEP(hi, lo_) acc = pk_min3(acc, hi, align16(hi, lo_))
@@ -118,11 +126,11 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     uint32_t* const buf0 = lds + gs.buf_off;
     uint32_t* const buf1 = buf0 + gs.buf_dwords;
     uint32_t* const qtab = lds + gs.q_off;
-    uint32_t* const slotTab = lds + gs.slot_off;
+    uint16_t* const slotTab = reinterpret_cast<uint16_t*>(lds + gs.slot_off);
 
     {
-        const uint32_t* src = &kLaneSlot[par][0][0];
-        for (int i = tid; i < 42 * 64; i += kGrpThreads) slotTab[i] = src[i];
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&kLaneSlot[par][0][0]);
+        for (int i = tid; i < 42 * 64 / 2; i += kGrpThreads) lds[gs.slot_off + i] = src[i];
         for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
     }
     unsigned long long best = PPO_KEY_NONE;
@@ -183,8 +191,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     // lane's schedule entry
     auto link_row = [&](int s, uint32_t ent) -> int {
         if (s + 1 < p0) return s;
-        if (s + 1 == p0) return nA + (int)((ent >> 20) & 7u);
-        return nA + nB + (int)((ent >> 16) & 15u);
+        if (s + 1 == p0) return nA + (int)((ent >> 13) & 7u);
+        return nA + nB + (int)((ent >> 9) & 15u);
     };
     // column of the quotient row holding (q[e-1], q[e]) for the output dword jj of row s (e = 2jj + s)
     auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
@@ -222,113 +230,117 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
     }
 
-    // ---- rows 1 .. k-2.  A task = (lane set, chunk of four output dwords).  Its inputs are the 13 input
-    //      dwords B[j] = dword (jbeg - 9 + j) of the lane's row (the four at the outputs' own indices and
-    //      the nine below them), the next link's quotients for the four outputs and the four chain
+    // ---- rows 1 .. k-2.  A task = (lane set, chunk of four output dwords).  Its inputs are the input
+    //      dwords from (jbeg - kDeep) to (jbeg + 3) of the lane's row (the four at the outputs' own indices
+    //      and the kDeep below them), the next link's quotients for the four outputs and the four chain
     //      descriptors.  All of it is requested one task ahead, into a second set of registers, so that a
-    //      task never waits for its own loads.
-    const uint32_t* __restrict__ wt4 = wt;
-    constexpr int kNB = kChunkPairs + kDeep + 1;
+    //      task never waits for its own loads; the lane's schedule entry is requested two tasks ahead.
+    constexpr int kNB = kChunkPairs + kDeep;
     struct TaskAux {
-        uint4 D[kChunkPairs];
+        uint4 ctrl, maskA, maskB;   // descriptors of the four outputs, word by word
         uint32_t qv[kChunkPairs];
         uint32_t fbase;      // LDS byte address of B[0]
-        uint32_t out_dw;     // dword offset of the first output in the output buffer
+        uint32_t out_addr;   // LDS byte address of the first output
     };
     const int wsel = wave >= 6 ? 1 : 0;
-    // the lane's schedule entries for the six rounds of row s
-    auto load_ents = [&](int s, uint32_t (&e)[6]) {
-        const int set0 = s < p0 ? 36 : (s - p0) * 6;
-#pragma unroll
-        for (int q = 0; q < 6; ++q) {
-            int c = wave + q;
-            c = c >= 12 ? c - 12 : c;
-            c = c >= 6 ? c - 6 : c;
-            e[q] = slotTab[(set0 + c) * 64 + lane];
-        }
+    const uint32_t buf0_addr = lds_addr(buf0), buf1_addr = lds_addr(buf1), qtab_addr = lds_addr(qtab);
+    const uint32_t desc_node_stride = (uint32_t)((k - 2) * y.wt_cols * WinDesc::kWords);
+    uint32_t ent_lane = lds_addr(lds + gs.slot_off) + 2u * (uint32_t)lane;   // the lane's column of the schedule table
+    asm volatile("" : "+v"(ent_lane));
+    // lane set of round q of this wave
+    auto round_set = [&](int q) {
+        int c = wave + q;
+        c = c >= 12 ? c - 12 : c;
+        return c >= 6 ? c - 6 : c;
+    };
+    // the lane's schedule entry for round q of row s
+    auto load_ent = [&](int s, int q) -> uint32_t {
+        const int set = (s < p0 ? 36 : (s - p0) * 6) + round_set(q);
+        return (uint32_t)lds_load_u16(ent_lane + (uint32_t)set * 128u);
     };
     // The chain descriptors of a task.  They are the same for every lane, but they are fetched with vector
     // loads on purpose: scalar loads complete under the same counter as LDS reads, out of order, so one in
     // flight would make every wait for an LDS result a wait for everything.
-    auto load_desc = [&](int s, int q, uint4 (&D)[kChunkPairs]) {
-        int c = wave + q;
-        c = c >= 12 ? c - 12 : c;
-        c = c >= 6 ? c - 6 : c;
-        const int jbeg = (2 * q + wsel) * kChunkPairs;
-        const int node = row_node(s, c);
-        const uint4* dp = reinterpret_cast<const uint4*>(wt4 + 4 * ((node * (k - 2) + (s - 1)) * y.wt_cols + jbeg)) + vzero;
-#pragma unroll
-        for (int t = 0; t < kChunkPairs; ++t) D[t] = dp[t];
+    auto load_desc = [&](int s, int q, TaskAux& X) {
+        const int chunk = 2 * q + wsel;
+        const uint32_t node = (uint32_t)row_node(s, round_set(q));
+        const uint32_t off = node * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords + chunk * 12);
+        const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
+        X.ctrl = dp[0];
+        X.maskA = dp[1];
+        X.maskB = dp[2];
     };
     // what the first task of the next row needs and does not depend on the row before it is requested
     // ahead of the barrier that ends that row
-    uint32_t ents_pre[6];
-    uint4 desc_pre[kChunkPairs];
-    load_ents(1, ents_pre);
-    load_desc(1, 0, desc_pre);
+    TaskAux X0, X1;
+    uint32_t ent_a = load_ent(1, 0), ent_b = 0;
+    load_desc(1, 0, X0);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
-        const uint32_t* in = (s & 1) ? buf0 : buf1;
-        uint32_t* outb = (s & 1) ? buf1 : buf0;
-        const int col = link_col(s);
-        uint32_t ents[6];
-#pragma unroll
-        for (int q = 0; q < 6; ++q) ents[q] = ents_pre[q];
+        const uint32_t in_addr = (s & 1) ? buf0_addr : buf1_addr, out_addr = (s & 1) ? buf1_addr : buf0_addr;
+        // byte address of the quotient dword (q[e-1], q[e]) of output 0, before the row of the link is added
+        const uint32_t q_addr = qtab_addr + 4u * (uint32_t)link_col(s);
+        // row of the quotient table = lr_base + a field of the schedule entry
+        const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
+        const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
 
-        // The register array holds the 13 dwords in descending address order (B[kNB-1-j] = input dword j of
-        // the fetch), so that the three register-indexed reads of an output use one and the same index.
-        auto request = [&](int q, uint32_t (&B)[kNB], TaskAux& X, bool with_desc) {
-            int c = wave + q;
-            c = c >= 12 ? c - 12 : c;
-            c = c >= 6 ? c - 6 : c;
+        // requests the inputs of the task of round q, whose schedule entry is ent; ent_next receives the
+        // entry of the task after it (round q+1, or round 0 of the next row)
+        auto request = [&](int q, uint32_t ent, uint32_t& ent_next, uint32_t (&B)[kNB], TaskAux& X, bool with_desc) {
             const int jbeg = (2 * q + wsel) * kChunkPairs;
-            const uint32_t ent = ents[q];
             const uint32_t slot_dw = slot_dword(ent);
-            const uint32_t* qrow = qtab + __umul24((uint32_t)link_row(s, ent), (uint32_t)QROW) + col + jbeg;
-            X.out_dw = slot_dw + jbeg * 32;
-            X.fbase = lds_addr(in + slot_dw + (jbeg - kDeep - 1) * 32);
-            asm volatile("" : "+v"(X.fbase));
+            const uint32_t lr = lr_base + ((ent >> lr_shift) & lr_mask);
+            uint32_t qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (q_addr + (uint32_t)(jbeg * 4));
+            X.out_addr = out_addr + (uint32_t)(jbeg * 128) + slot_dw * 4u;
+            X.fbase = in_addr + (uint32_t)((jbeg - kDeep) * 128) + slot_dw * 4u;
+            asm volatile("" : "+v"(X.fbase), "+v"(qa_addr));
 #pragma unroll
-            for (int j = 0; j < kNB; ++j) B[kNB - 1 - j] = lds_load(X.fbase + (uint32_t)j * 128u);
+            for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
 #pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = qrow[t];
-            if (with_desc) load_desc(s, q, X.D);
+            for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = lds_load(qa_addr + (uint32_t)t * 4u);
+            if (with_desc) load_desc(s, q, X);
+            if (q + 1 < 6) ent_next = load_ent(s, q + 1);
         };
 
+        // b(t, i): the input dword i below the index of output t (i = 0: the dword at that index)
+#define PPO_B(t, i) B[(t) + kDeep - (i)]
         auto run = [&](int q, const uint32_t (&B)[kNB], const TaskAux& X) {
             const int jbeg = (2 * q + wsel) * kChunkPairs;
             const int np = NP - jbeg;   // outputs beyond the row end are computed from null descriptors, not stored
-            // G[j]: the dword straddling input dwords j and j+1 (upper code of j, lower code of j+1)
-            uint32_t G[kNB - 1];
+            const uint32_t ctrl[kChunkPairs] = {
+                (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.x), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.y),
+                (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.z), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.w)};
+            const uint32_t maskA[kChunkPairs] = {X.maskA.x, X.maskA.y, X.maskA.z, X.maskA.w};
+            const uint32_t maskB[kChunkPairs] = {X.maskB.x, X.maskB.y, X.maskB.z, X.maskB.w};
+            // the two dwords of the masked step, n and n+1 below the output's index, wherever they are
+            uint32_t bn[kChunkPairs], bn1[kChunkPairs];
 #pragma unroll
-            for (int j = 0; j < kNB - 1; ++j) G[j] = align16(B[kNB - 2 - j], B[kNB - 1 - j]);
-            // prefix minima of the four chains: M[t][i] folds steps 1..i of output t, step i = offsets 2i-2
-            // and 2i-1 of both positions = the dword i-1 below the output's index and the one straddling it
-            // and the next.  Four independent chains in one basic block.
-            uint32_t M0[kDeep + 1], M1[kDeep + 1], M2[kDeep + 1], M3[kDeep + 1];   // one register block each
-            uint32_t ctrl[kChunkPairs];
-            M0[0] = M1[0] = M2[0] = M3[0] = kInf2;
-#pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) ctrl[t] = __builtin_amdgcn_readfirstlane(X.D[t].x);
-#pragma unroll
-            for (int i = 1; i <= kDeep; ++i) {
-                M0[i] = pk_min3(M0[i - 1], B[kNB - 1 - (0 + kDeep + 2 - i)], G[0 + kDeep + 1 - i]);
-                M1[i] = pk_min3(M1[i - 1], B[kNB - 1 - (1 + kDeep + 2 - i)], G[1 + kDeep + 1 - i]);
-                M2[i] = pk_min3(M2[i - 1], B[kNB - 1 - (2 + kDeep + 2 - i)], G[2 + kDeep + 1 - i]);
-                M3[i] = pk_min3(M3[i - 1], B[kNB - 1 - (3 + kDeep + 2 - i)], G[3 + kDeep + 1 - i]);
+            for (int t = 0; t < kChunkPairs; ++t) {
+                const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
+                const uint32_t a = X.fbase + ((uint32_t)(t + kDeep - 1) - n) * 128u;
+                bn1[t] = lds_load(a);
+                bn[t] = lds_load(a + 128u);
             }
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                const uint32_t oddmask = X.D[t].y, tailmask = X.D[t].z, selmask = X.D[t].w;
                 const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
-                const uint32_t idx = n < (uint32_t)kDeep ? n : (uint32_t)kDeep;
-                uint32_t acc = t == 0 ? M0[idx] : t == 1 ? M1[idx] : t == 2 ? M2[idx] : M3[idx];
-                uint32_t a0 = B[kNB - 2 - kDeep - t + idx], a1 = B[kNB - 1 - kDeep - t + idx];   // dwords idx, idx+1 below
-                if (n > (uint32_t)kDeep) {
+                const bool deep = n > (uint32_t)kDeep;
+                const uint32_t nc = deep ? (uint32_t)kDeep : n;
+                uint32_t acc = kInf2, tmp;
+                // steps nc .. 1 from registers (see ppo_chain_asm.h)
+                asm volatile(PPO_CHAIN_ASM
+                             : "+v"(acc), "=&v"(tmp)
+                             : "s"(nc * 16u), "v"(PPO_B(t, 0)), "v"(PPO_B(t, 1)), "v"(PPO_B(t, 2)), "v"(PPO_B(t, 3)),
+                               "v"(PPO_B(t, 4)), "v"(PPO_B(t, 5)), "v"(PPO_B(t, 6)), "v"(PPO_B(t, 7)),
+                               "v"(PPO_B(t, 8)), "v"(PPO_B(t, 9)), "v"(PPO_B(t, 10)), "v"(PPO_B(t, 11)),
+                               "v"(PPO_B(t, 12)), "v"(PPO_B(t, 13)), "v"(PPO_B(t, 14)), "v"(PPO_B(t, 15)),
+                               "v"(PPO_B(t, 16))
+                             : "s98", "s99", "scc");
+                if (deep) {
                     // the rest of a long chain walks further down the row
-                    uint32_t pa = X.fbase + (uint32_t)(t + 1) * 128u;   // dword kDeep below the output's index
-                    uint32_t cur = a0;
+                    uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
+                    uint32_t cur = PPO_B(t, kDeep);
                     uint32_t m = n - (uint32_t)kDeep;
                     while (m >= 4u) {
                         pa -= 512u;
@@ -345,21 +357,15 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         cur = b1;
                         m -= 1u;
                     }
-                    a0 = cur;
-                    a1 = lds_load(pa - 128u);
                 }
-                // bottom of the shorter window: offset nmin-1 if nmin is odd (dword a0, both positions),
-                // then the single offset nmin that only the longer window may have (masked to its half)
-                acc = pk_min(acc, pk_max(a0, oddmask));
-                const uint32_t al = align16(a0, a1);
-                const uint32_t v = (al & selmask) | (a0 & ~selmask);
-                acc = pk_min(acc, pk_max(v, tailmask));
+                // the masked step: offsets 2n (dword n, both halves) and 2n+1 (straddling dwords n and n+1)
+                acc = pk_min3(acc, pk_max(bn[t], maskA[t]), pk_max(align16(bn[t], bn1[t]), maskB[t]));
                 if (ctrl[t] & WinDesc::kLongTail) {
                     // the first position's window is longer by two or more: fold its extra offsets
                     // nmin .. nmax-1 dword by dword, then across the two halves.  The dword `a` below the
                     // output's index holds offset 2a in its lower half and offset 2a-1 in its upper half.
                     const uint32_t nmin = (ctrl[t] >> 8) & 0xFFu, nmax = (ctrl[t] >> 16) & 0xFFu;
-                    const uint32_t own = X.fbase + (uint32_t)(t + kDeep + 1) * 128u;   // dword at the output's index
+                    const uint32_t own = X.fbase + (uint32_t)(t + kDeep) * 128u;   // dword at the output's index
                     uint32_t a_first, a_last;
                     uint32_t tacc = kInf2;
                     if ((nmin & 1u) == 0u) {   // top offset nmin is a lower half: the upper half is out of range
@@ -378,26 +384,24 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                     tacc = pk_min(tacc, align16(tacc, tacc));
                     acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                 }
-                if (t < np) outb[X.out_dw + t * 32] = pk_max(acc, X.qv[t]);
+                if (t < np) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc, X.qv[t]));
             }
         };
+#undef PPO_B
 
         uint32_t B0[kNB], B1[kNB];
-        TaskAux X0, X1;
-#pragma unroll
-        for (int t = 0; t < kChunkPairs; ++t) X0.D[t] = desc_pre[t];
-        request(0, B0, X0, false);
+        request(0, ent_a, ent_b, B0, X0, false);
         for (int q = 0; q < 6; q += 2) {
             const bool live1 = (2 * (q + 1) + wsel) * kChunkPairs < NP;
             const bool live0 = (2 * q + wsel) * kChunkPairs < NP;
-            if (live1) request(q + 1, B1, X1, true);
+            if (live1) request(q + 1, ent_b, ent_a, B1, X1, true);
             if (live0) run(q, B0, X0);
-            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, B0, X0, true);
+            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, ent_a, ent_b, B0, X0, true);
             if (live1) run(q + 1, B1, X1);
         }
         if (s + 1 <= k - 2) {
-            load_ents(s + 1, ents_pre);
-            load_desc(s + 1, 0, desc_pre);
+            ent_a = load_ent(s + 1, 0);
+            load_desc(s + 1, 0, X0);
         }
         __syncthreads();
     }

@@ -70,7 +70,9 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                 }
                 w[h] = (uint32_t)v;
             }
-            WinDesc::pack(w[0], w[1], wt + 4 * idx);
+            uint32_t* row = wt + (size_t)(idx - jj) * WinDesc::kWords;
+            WinDesc::pack(w[0], w[1], row[WinDesc::offset(jj, 0)], row[WinDesc::offset(jj, 1)],
+                          row[WinDesc::offset(jj, 2)]);
         }
     }
     {
