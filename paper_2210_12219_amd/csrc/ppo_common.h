@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "ppo.h"
+#include "ppo_chain_asm.h"
 
 namespace ppo {
 
@@ -24,42 +25,56 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   qc  [npairs][L] u16   qc[p][i] = code of t[i] / B[a][b] for the unordered pair p = {a,b}, i < L-1
 //   dec [npairs*(L-1)+2] f32   dec[code - kCodeZero] = value of the code
 //   low [k][L+1] u32  the lo table again, one dword per entry (for scalar loads)
-//   wt  [k][k-2][wt_cols/4][3][4] u32   chain descriptors for the grouped kernel: for node j, DP row
+//   wt  [k][k-2][wt_cols/4][4][4] u32   chain descriptors for the grouped kernel: for node j, DP row
 //       s = 1..k-2 and output dword jj (positions e = 2jj+s and e+1 of row s), from the window lengths
 //       w = e - max(lo[j][e], s) if s+1 <= e <= L-k+1+s, else 0 (wx for e, wy for e+1), see WinDesc;
-//       the three words of the four outputs of a chunk are stored word by word (ctrl x4, maskA x4, maskB x4)
+//       the four words of the four outputs of a chunk are stored word by word (ctrl x4, below x4, ...)
 //   qa  [npairs][qa_cols] u32   the codes of qc again, two per dword, in both alignments, for the
 //       grouped kernel: column a < QD holds (q[2a], q[2a+1]); column QD+1+a holds (q[2a+1], q[2a+2])
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
 //   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
 //       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
-// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, three words.
-// With nmin = min(wx,wy), nmax = max(wx,wy), ntail = nmax - nmin and n = nmin/2 full steps, which fold
-// window offsets 0 .. 2n-1 of both positions, one masked step treats offsets 2n and 2n+1:
-//   ctrl      bits 0..6  n
-//             bit  7     ntail >= 2 (only the first position's window can be that much longer; its extra
+// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, four words.
+// The kernel works on chunks of kChunkPairs output dwords and holds the input dword at an output's own
+// index and the kChainDepth dwords below it in registers.  With nmin = min(wx,wy), nmax = max(wx,wy),
+// ntail = nmax - nmin and n = nmin/2 full steps, which fold window offsets 0 .. 2n-1 of both positions,
+// one masked step treats offsets 2n and 2n+1:
+//   ctrl      bit  0     ntail >= 2 (only the first position's window can be that much longer; its extra
 //                        offsets nmin .. nmax-1 are folded separately)
-//             bits 8..15 nmin, bits 16..23 nmax
+//             bit  1     n > kChainDepth (the chain continues below the registers)
+//             bits 4..8  min(n, kChainDepth), so that ctrl & 0x1F0 is 16 times that
+//             bits 9..15 n, bits 16..23 nmin, bits 24..31 nmax
+//   below     byte distance, in the lane's row (128 bytes per dword), from the first dword the task fetches
+//             (kChainDepth below the chunk's first output) to the dword n+1 below this output; may be
+//             negative (two's complement)
 //   maskA     per half, 0 if offset 2n is inside that position's window and not left to the separate fold,
 //             else +inf: max(v, maskA) keeps or drops it
 //   maskB     the same for offset 2n+1
+constexpr int kChunkPairs = 4;
+constexpr int kChainDepth = PPO_CHAIN_DEPTH;
 struct WinDesc {
-    static constexpr uint32_t kStepsMask = 0x7Fu;
-    static constexpr uint32_t kLongTail = 0x80u;
-    static constexpr int kWords = 3;
-    __host__ __device__ static void pack(uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& maskA, uint32_t& maskB) {
+    static constexpr uint32_t kLongTail = 0x1u, kDeepChain = 0x2u, kJumpMask = 0x1F0u;
+    static constexpr int kWords = 4;
+    __host__ __device__ static uint32_t steps(uint32_t ctrl) { return (ctrl >> 9) & 0x7Fu; }
+    __host__ __device__ static uint32_t nmin(uint32_t ctrl) { return (ctrl >> 16) & 0xFFu; }
+    __host__ __device__ static uint32_t nmax(uint32_t ctrl) { return ctrl >> 24; }
+    // descriptor of output column jj from the two window lengths
+    __host__ __device__ static void pack(uint32_t jj, uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& below,
+                                         uint32_t& maskA, uint32_t& maskB) {
         const uint32_t inf = kCodeInf;
-        const uint32_t nmin = wx < wy ? wx : wy, nmax = wx < wy ? wy : wx, ntail = nmax - nmin;
-        const uint32_t n = nmin >> 1;
+        const uint32_t lo_w = wx < wy ? wx : wy, hi_w = wx < wy ? wy : wx, ntail = hi_w - lo_w;
+        const uint32_t n = lo_w >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
         // a window longer by two or more is cut to the shorter one here
-        const uint32_t ex = ntail >= 2u ? nmin : wx, ey = ntail >= 2u ? nmin : wy;
-        ctrl = n | (ntail >= 2u ? kLongTail : 0u) | (nmin << 8) | (nmax << 16);
+        const uint32_t ex = ntail >= 2u ? lo_w : wx, ey = ntail >= 2u ? lo_w : wy;
+        ctrl = (ntail >= 2u ? kLongTail : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 4) | (n << 9) |
+               (lo_w << 16) | (hi_w << 24);
+        below = ((jj % kChunkPairs) + (uint32_t)kChainDepth - 1u - n) * 128u;
         maskA = (2u * n < ex ? 0u : inf) | ((2u * n < ey ? 0u : inf) << 16);
         maskB = (2u * n + 1u < ex ? 0u : inf) | ((2u * n + 1u < ey ? 0u : inf) << 16);
     }
     // dword offset of word `word` of output column jj within the descriptor row of a (node, DP row)
     __host__ __device__ static uint32_t offset(uint32_t jj, uint32_t word) {
-        return (jj >> 2) * 12u + word * 4u + (jj & 3u);
+        return (jj / kChunkPairs) * (uint32_t)(kWords * kChunkPairs) + word * kChunkPairs + (jj % kChunkPairs);
     }
 };
 

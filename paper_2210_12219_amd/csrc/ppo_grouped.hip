@@ -26,16 +26,14 @@
 // output dwords.  Wave w takes, in round q = 0..5, the set (w+q) mod 6 and chunk 2q + (w >= 6): every
 // wave meets every node once per row, which evens out the very different window lengths of the nodes.
 #include "ppo_common.h"
-#include "ppo_chain_asm.h"
 #include "ppo_group_tables.h"
 
 namespace ppo {
 
 constexpr int kGrpWaves = 12;
 constexpr int kGrpThreads = kGrpWaves * 64;
-constexpr int kChunkPairs = 4;                      // output dwords (pairs of positions) per task
 constexpr int kGrpMaxPairs = 6 * 2 * kChunkPairs;   // six rounds of two chunks cover at most 48 dwords
-constexpr int kDeep = PPO_CHAIN_DEPTH;               // chain steps available from prefetched registers
+constexpr int kDeep = kChainDepth;                   // chain steps available from prefetched registers
 constexpr uint32_t kInf2 = kCodeInf | (kCodeInf << 16);
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
@@ -237,7 +235,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //      task never waits for its own loads; the lane's schedule entry is requested two tasks ahead.
     constexpr int kNB = kChunkPairs + kDeep;
     struct TaskAux {
-        uint4 ctrl, maskA, maskB;   // descriptors of the four outputs, word by word
+        uint4 ctrl, below, maskA, maskB;   // descriptors of the four outputs, word by word
         uint32_t qv[kChunkPairs];
         uint32_t fbase;      // LDS byte address of B[0]
         uint32_t out_addr;   // LDS byte address of the first output
@@ -247,34 +245,46 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     const uint32_t desc_node_stride = (uint32_t)((k - 2) * y.wt_cols * WinDesc::kWords);
     uint32_t ent_lane = lds_addr(lds + gs.slot_off) + 2u * (uint32_t)lane;   // the lane's column of the schedule table
     asm volatile("" : "+v"(ent_lane));
-    // lane set of round q of this wave
-    auto round_set = [&](int q) {
+    // The wave works on lane set (wave + q) mod 6 in round q: the six of them four bits each, and the
+    // number of rounds whose chunk 2q + wsel lies inside the row.
+    uint32_t set_pack = 0;
+    int n_rounds = 0;
+    for (int q = 0; q < 6; ++q) {
         int c = wave + q;
         c = c >= 12 ? c - 12 : c;
-        return c >= 6 ? c - 6 : c;
+        c = c >= 6 ? c - 6 : c;
+        set_pack |= (uint32_t)c << (4 * q);
+        n_rounds += (2 * q + wsel) * kChunkPairs < NP ? 1 : 0;
+    }
+    // the nodes of row s for the six rounds, four bits each
+    auto node_pack = [&](int s) -> uint32_t {
+        if (s < p0) return 0x111111u * (uint32_t)prefix_node(s);
+        uint32_t r = 0;
+        for (int q = 0; q < 6; ++q) r |= (uint32_t)rest_node((int)((set_pack >> (4 * q)) & 15u)) << (4 * q);
+        return r;
     };
-    // the lane's schedule entry for round q of row s
-    auto load_ent = [&](int s, int q) -> uint32_t {
-        const int set = (s < p0 ? 36 : (s - p0) * 6) + round_set(q);
-        return (uint32_t)lds_load_u16(ent_lane + (uint32_t)set * 128u);
-    };
+    // first lane set of row s in the schedule table
+    auto first_set = [&](int s) { return s < p0 ? 36 : (s - p0) * 6; };
+    // the lane's schedule entry for lane set `set`
+    auto load_ent = [&](uint32_t set) -> uint32_t { return (uint32_t)lds_load_u16(ent_lane + set * 128u); };
     // The chain descriptors of a task.  They are the same for every lane, but they are fetched with vector
     // loads on purpose: scalar loads complete under the same counter as LDS reads, out of order, so one in
     // flight would make every wait for an LDS result a wait for everything.
-    auto load_desc = [&](int s, int q, TaskAux& X) {
-        const int chunk = 2 * q + wsel;
-        const uint32_t node = (uint32_t)row_node(s, round_set(q));
-        const uint32_t off = node * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords + chunk * 12);
+    auto load_desc = [&](int s, int q, uint32_t node, TaskAux& X) {
+        const uint32_t off = node * desc_node_stride +
+                             (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords + (2 * q + wsel) * (WinDesc::kWords * kChunkPairs));
         const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
         X.ctrl = dp[0];
-        X.maskA = dp[1];
-        X.maskB = dp[2];
+        X.below = dp[1];
+        X.maskA = dp[2];
+        X.maskB = dp[3];
     };
     // what the first task of the next row needs and does not depend on the row before it is requested
     // ahead of the barrier that ends that row
     TaskAux X0, X1;
-    uint32_t ent_a = load_ent(1, 0), ent_b = 0;
-    load_desc(1, 0, X0);
+    uint32_t nodes_next = node_pack(1);
+    uint32_t ent_a = load_ent((uint32_t)first_set(1) + (set_pack & 15u)), ent_b = 0;
+    load_desc(1, 0, nodes_next & 15u, X0);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
@@ -284,9 +294,12 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         // row of the quotient table = lr_base + a field of the schedule entry
         const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
         const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
+        const uint32_t set0 = (uint32_t)first_set(s);
+        // lane sets and nodes of the rounds not yet requested, this round's in the low four bits
+        uint32_t sets = set_pack, nodes = nodes_next;
 
         // requests the inputs of the task of round q, whose schedule entry is ent; ent_next receives the
-        // entry of the task after it (round q+1, or round 0 of the next row)
+        // entry of the task of round q+1
         auto request = [&](int q, uint32_t ent, uint32_t& ent_next, uint32_t (&B)[kNB], TaskAux& X, bool with_desc) {
             const int jbeg = (2 * q + wsel) * kChunkPairs;
             const uint32_t slot_dw = slot_dword(ent);
@@ -299,8 +312,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = lds_load(qa_addr + (uint32_t)t * 4u);
-            if (with_desc) load_desc(s, q, X);
-            if (q + 1 < 6) ent_next = load_ent(s, q + 1);
+            if (with_desc) load_desc(s, q, nodes & 15u, X);
+            sets >>= 4;
+            nodes >>= 4;
+            if (q + 1 < 6) ent_next = load_ent(set0 + (sets & 15u));
         };
 
         // b(t, i): the input dword i below the index of output t (i = 0: the dword at that index)
@@ -311,78 +326,77 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             const uint32_t ctrl[kChunkPairs] = {
                 (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.x), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.y),
                 (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.z), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.w)};
+            const uint32_t below[kChunkPairs] = {X.below.x, X.below.y, X.below.z, X.below.w};
             const uint32_t maskA[kChunkPairs] = {X.maskA.x, X.maskA.y, X.maskA.z, X.maskA.w};
             const uint32_t maskB[kChunkPairs] = {X.maskB.x, X.maskB.y, X.maskB.z, X.maskB.w};
             // the two dwords of the masked step, n and n+1 below the output's index, wherever they are
             uint32_t bn[kChunkPairs], bn1[kChunkPairs];
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
-                const uint32_t a = X.fbase + ((uint32_t)(t + kDeep - 1) - n) * 128u;
+                const uint32_t a = X.fbase + below[t];
                 bn1[t] = lds_load(a);
                 bn[t] = lds_load(a + 128u);
             }
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                const uint32_t n = ctrl[t] & WinDesc::kStepsMask;
-                const bool deep = n > (uint32_t)kDeep;
-                const uint32_t nc = deep ? (uint32_t)kDeep : n;
                 uint32_t acc = kInf2, tmp;
-                // steps nc .. 1 from registers (see ppo_chain_asm.h)
+                // steps min(n, kDeep) .. 1 from registers (see ppo_chain_asm.h)
                 asm volatile(PPO_CHAIN_ASM
                              : "+v"(acc), "=&v"(tmp)
-                             : "s"(nc * 16u), "v"(PPO_B(t, 0)), "v"(PPO_B(t, 1)), "v"(PPO_B(t, 2)), "v"(PPO_B(t, 3)),
-                               "v"(PPO_B(t, 4)), "v"(PPO_B(t, 5)), "v"(PPO_B(t, 6)), "v"(PPO_B(t, 7)),
+                             : "s"(ctrl[t] & WinDesc::kJumpMask), "v"(PPO_B(t, 0)), "v"(PPO_B(t, 1)), "v"(PPO_B(t, 2)),
+                               "v"(PPO_B(t, 3)), "v"(PPO_B(t, 4)), "v"(PPO_B(t, 5)), "v"(PPO_B(t, 6)), "v"(PPO_B(t, 7)),
                                "v"(PPO_B(t, 8)), "v"(PPO_B(t, 9)), "v"(PPO_B(t, 10)), "v"(PPO_B(t, 11)),
                                "v"(PPO_B(t, 12)), "v"(PPO_B(t, 13)), "v"(PPO_B(t, 14)), "v"(PPO_B(t, 15)),
                                "v"(PPO_B(t, 16))
                              : "s98", "s99", "scc");
-                if (deep) {
-                    // the rest of a long chain walks further down the row
-                    uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
-                    uint32_t cur = PPO_B(t, kDeep);
-                    uint32_t m = n - (uint32_t)kDeep;
-                    while (m >= 4u) {
-                        pa -= 512u;
-                        const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u), b3 = lds_load(pa + 128u),
-                                       b4 = lds_load(pa);
-                        PPO_STEP(cur, b1); PPO_STEP(b1, b2); PPO_STEP(b2, b3); PPO_STEP(b3, b4);
-                        cur = b4;
-                        m -= 4u;
-                    }
-                    while (m >= 1u) {
-                        pa -= 128u;
-                        const uint32_t b1 = lds_load(pa);
-                        PPO_STEP(cur, b1);
-                        cur = b1;
-                        m -= 1u;
-                    }
-                }
                 // the masked step: offsets 2n (dword n, both halves) and 2n+1 (straddling dwords n and n+1)
                 acc = pk_min3(acc, pk_max(bn[t], maskA[t]), pk_max(align16(bn[t], bn1[t]), maskB[t]));
-                if (ctrl[t] & WinDesc::kLongTail) {
-                    // the first position's window is longer by two or more: fold its extra offsets
-                    // nmin .. nmax-1 dword by dword, then across the two halves.  The dword `a` below the
-                    // output's index holds offset 2a in its lower half and offset 2a-1 in its upper half.
-                    const uint32_t nmin = (ctrl[t] >> 8) & 0xFFu, nmax = (ctrl[t] >> 16) & 0xFFu;
-                    const uint32_t own = X.fbase + (uint32_t)(t + kDeep) * 128u;   // dword at the output's index
-                    uint32_t a_first, a_last;
-                    uint32_t tacc = kInf2;
-                    if ((nmin & 1u) == 0u) {   // top offset nmin is a lower half: the upper half is out of range
-                        tacc = pk_max(lds_load(own - (nmin >> 1) * 128u), kCodeInf << 16);
-                        a_first = (nmin >> 1) + 1u;
-                    } else {
-                        a_first = (nmin + 1u) >> 1;
+                if (ctrl[t] & (WinDesc::kDeepChain | WinDesc::kLongTail)) {
+                    if (ctrl[t] & WinDesc::kDeepChain) {
+                        // the rest of a long chain walks further down the row
+                        uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
+                        uint32_t cur = PPO_B(t, kDeep);
+                        uint32_t m = WinDesc::steps(ctrl[t]) - (uint32_t)kDeep;
+                        while (m >= 4u) {
+                            pa -= 512u;
+                            const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u),
+                                           b3 = lds_load(pa + 128u), b4 = lds_load(pa);
+                            PPO_STEP(cur, b1); PPO_STEP(b1, b2); PPO_STEP(b2, b3); PPO_STEP(b3, b4);
+                            cur = b4;
+                            m -= 4u;
+                        }
+                        while (m >= 1u) {
+                            pa -= 128u;
+                            const uint32_t b1 = lds_load(pa);
+                            PPO_STEP(cur, b1);
+                            cur = b1;
+                            m -= 1u;
+                        }
                     }
-                    if ((nmax & 1u) == 0u) {   // bottom offset nmax-1 is an upper half: the lower half is out of range
-                        tacc = pk_min(tacc, pk_max(lds_load(own - (nmax >> 1) * 128u), kCodeInf));
-                        a_last = (nmax >> 1) - 1u;
-                    } else {
-                        a_last = (nmax - 1u) >> 1;
+                    if (ctrl[t] & WinDesc::kLongTail) {
+                        // the first position's window is longer by two or more: fold its extra offsets
+                        // nmin .. nmax-1 dword by dword, then across the two halves.  The dword `a` below the
+                        // output's index holds offset 2a in its lower half and offset 2a-1 in its upper half.
+                        const uint32_t nmin = WinDesc::nmin(ctrl[t]), nmax = WinDesc::nmax(ctrl[t]);
+                        const uint32_t own = X.fbase + (uint32_t)(t + kDeep) * 128u;   // dword at the output's index
+                        uint32_t a_first, a_last;
+                        uint32_t tacc = kInf2;
+                        if ((nmin & 1u) == 0u) {   // top offset nmin is a lower half: the upper half is out of range
+                            tacc = pk_max(lds_load(own - (nmin >> 1) * 128u), kCodeInf << 16);
+                            a_first = (nmin >> 1) + 1u;
+                        } else {
+                            a_first = (nmin + 1u) >> 1;
+                        }
+                        if ((nmax & 1u) == 0u) {   // bottom offset nmax-1 is an upper half: the lower half is out of range
+                            tacc = pk_min(tacc, pk_max(lds_load(own - (nmax >> 1) * 128u), kCodeInf));
+                            a_last = (nmax >> 1) - 1u;
+                        } else {
+                            a_last = (nmax - 1u) >> 1;
+                        }
+                        for (uint32_t a = a_first; a <= a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
+                        tacc = pk_min(tacc, align16(tacc, tacc));
+                        acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                     }
-                    for (uint32_t a = a_first; a <= a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
-                    tacc = pk_min(tacc, align16(tacc, tacc));
-                    acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                 }
                 if (t < np) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc, X.qv[t]));
             }
@@ -390,18 +404,18 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 #undef PPO_B
 
         uint32_t B0[kNB], B1[kNB];
-        request(0, ent_a, ent_b, B0, X0, false);
-        for (int q = 0; q < 6; q += 2) {
-            const bool live1 = (2 * (q + 1) + wsel) * kChunkPairs < NP;
-            const bool live0 = (2 * q + wsel) * kChunkPairs < NP;
+        if (n_rounds > 0) request(0, ent_a, ent_b, B0, X0, false);
+        for (int q = 0; q < n_rounds; q += 2) {
+            const bool live1 = q + 1 < n_rounds;
             if (live1) request(q + 1, ent_b, ent_a, B1, X1, true);
-            if (live0) run(q, B0, X0);
-            if (q + 2 < 6 && (2 * (q + 2) + wsel) * kChunkPairs < NP) request(q + 2, ent_a, ent_b, B0, X0, true);
+            run(q, B0, X0);
+            if (q + 2 < n_rounds) request(q + 2, ent_a, ent_b, B0, X0, true);
             if (live1) run(q + 1, B1, X1);
         }
         if (s + 1 <= k - 2) {
-            ent_a = load_ent(s + 1, 0);
-            load_desc(s + 1, 0, X0);
+            nodes_next = node_pack(s + 1);
+            ent_a = load_ent((uint32_t)first_set(s + 1) + (set_pack & 15u));
+            load_desc(s + 1, 0, nodes_next & 15u, X0);
         }
         __syncthreads();
     }

@@ -71,8 +71,8 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                 w[h] = (uint32_t)v;
             }
             uint32_t* row = wt + (size_t)(idx - jj) * WinDesc::kWords;
-            WinDesc::pack(w[0], w[1], row[WinDesc::offset(jj, 0)], row[WinDesc::offset(jj, 1)],
-                          row[WinDesc::offset(jj, 2)]);
+            WinDesc::pack((uint32_t)jj, w[0], w[1], row[WinDesc::offset(jj, 0)], row[WinDesc::offset(jj, 1)],
+                          row[WinDesc::offset(jj, 2)], row[WinDesc::offset(jj, 3)]);
         }
     }
     {
