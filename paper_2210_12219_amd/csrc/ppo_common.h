@@ -34,43 +34,47 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
 //   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
 //       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
-// Chain descriptor of one output dword (positions e, e+1) of the grouped kernel, four words.
+// Chain descriptor of one output dword (positions x = e and y = e+1) of the grouped kernel, four words.
 // The kernel works on chunks of kChunkPairs output dwords and holds the input dword at an output's own
-// index and the kChainDepth dwords below it in registers.  With nmin = min(wx,wy), nmax = max(wx,wy),
-// ntail = nmax - nmin and n = nmin/2 full steps, which fold window offsets 0 .. 2n-1 of both positions,
-// one masked step treats offsets 2n and 2n+1:
-//   ctrl      bit  0     ntail >= 2 (only the first position's window can be that much longer; its extra
-//                        offsets nmin .. nmax-1 are folded separately)
-//             bit  1     n > kChainDepth (the chain continues below the registers)
-//             bits 4..8  min(n, kChainDepth), so that ctrl & 0x1F0 is 16 times that
-//             bits 9..15 n, bits 16..23 nmin, bits 24..31 nmax
+// index and the kChainDepth dwords below it in registers.  The entries of the row below are counted
+// downwards from x's first candidate: u = 0, 1, ...; entry u is candidate u of x (wanted if u < wx) and
+// candidate u+1 of y (wanted if u+1 < wy); entry u = -1 is y's first candidate.  Dword a below the output's
+// index holds entry 2a in its lower half and entry 2a-1 in its upper half.  Because wy <= wx+1, the entries
+// both positions want are u = 0 .. C-1 with C = wy-1 (0 if wy = 0).  n = C/2 steps fold two of them each
+// into both halves; then one masked step offers entries 2n and 2n+1; what x wants beyond that (entries
+// 2n+2 .. wx-1) is folded separately.
+//   ctrl      bit  0      wx > 2n+2 (entries left for the separate fold)
+//             bit  1      n > kChainDepth (the chain continues below the registers)
+//             bits 3..7   min(n, kChainDepth), so that ctrl & 0xF8 is 8 times that
+//             bits 8..15  wx
+//             bits 16..31 0 if y wants entry -1 (wy >= 1), else +inf: upper half of the accumulator's
+//                         initial mask (the lower half is +inf: x does not want entry -1)
 //   below     byte distance, in the lane's row (128 bytes per dword), from the first dword the task fetches
 //             (kChainDepth below the chunk's first output) to the dword n+1 below this output; may be
 //             negative (two's complement)
-//   maskA     per half, 0 if offset 2n is inside that position's window and not left to the separate fold,
-//             else +inf: max(v, maskA) keeps or drops it
-//   maskB     the same for offset 2n+1
+//   maskA     for entry 2n: per half, 0 if that position wants it, else +inf (max(v, mask) keeps or drops)
+//   maskB     for entry 2n+1: lower half as above; upper half +inf (y never wants it)
 constexpr int kChunkPairs = 4;
 constexpr int kChainDepth = PPO_CHAIN_DEPTH;
 struct WinDesc {
-    static constexpr uint32_t kLongTail = 0x1u, kDeepChain = 0x2u, kJumpMask = 0x1F0u;
+    static constexpr uint32_t kFold = 0x1u, kDeepChain = 0x2u, kJumpMask = 0xF8u;
     static constexpr int kWords = 4;
-    __host__ __device__ static uint32_t steps(uint32_t ctrl) { return (ctrl >> 9) & 0x7Fu; }
-    __host__ __device__ static uint32_t nmin(uint32_t ctrl) { return (ctrl >> 16) & 0xFFu; }
-    __host__ __device__ static uint32_t nmax(uint32_t ctrl) { return ctrl >> 24; }
+    __host__ __device__ static uint32_t wx(uint32_t ctrl) { return (ctrl >> 8) & 0xFFu; }
+    // number of steps, from the second word and the output's place t in its chunk
+    __host__ __device__ static uint32_t steps(uint32_t below, uint32_t t) {
+        return t + (uint32_t)kChainDepth - 1u - (uint32_t)((int32_t)below >> 7);
+    }
     // descriptor of output column jj from the two window lengths
     __host__ __device__ static void pack(uint32_t jj, uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& below,
                                          uint32_t& maskA, uint32_t& maskB) {
         const uint32_t inf = kCodeInf;
-        const uint32_t lo_w = wx < wy ? wx : wy, hi_w = wx < wy ? wy : wx, ntail = hi_w - lo_w;
-        const uint32_t n = lo_w >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
-        // a window longer by two or more is cut to the shorter one here
-        const uint32_t ex = ntail >= 2u ? lo_w : wx, ey = ntail >= 2u ? lo_w : wy;
-        ctrl = (ntail >= 2u ? kLongTail : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 4) | (n << 9) |
-               (lo_w << 16) | (hi_w << 24);
+        const uint32_t C = wy >= 1u ? (wx < wy - 1u ? wx : wy - 1u) : 0u;
+        const uint32_t n = C >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
+        ctrl = (wx > 2u * n + 2u ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 3) | (wx << 8) |
+               ((wy >= 1u ? 0u : inf) << 16);
         below = ((jj % kChunkPairs) + (uint32_t)kChainDepth - 1u - n) * 128u;
-        maskA = (2u * n < ex ? 0u : inf) | ((2u * n < ey ? 0u : inf) << 16);
-        maskB = (2u * n + 1u < ex ? 0u : inf) | ((2u * n + 1u < ey ? 0u : inf) << 16);
+        maskA = (wx > 2u * n ? 0u : inf) | ((C > 2u * n ? 0u : inf) << 16);
+        maskB = (wx > 2u * n + 1u ? 0u : inf) | (inf << 16);
     }
     // dword offset of word `word` of output column jj within the descriptor row of a (node, DP row)
     __host__ __device__ static uint32_t offset(uint32_t jj, uint32_t word) {

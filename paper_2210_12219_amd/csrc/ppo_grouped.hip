@@ -95,9 +95,31 @@ __device__ __forceinline__ uint32_t lds_load_u16(uint32_t addr) {
 __device__ __forceinline__ void lds_store(uint32_t addr, uint32_t v) {
     *reinterpret_cast<__attribute__((address_space(3))) uint32_t*>((uintptr_t)addr) = v;
 }
-// One step of a chain folds two offsets of both positions: the dword `hi` itself and the dword
-// straddling `lo_` and `hi`.
-#define PPO_STEP(hi, lo_) acc = pk_min3(acc, hi, align16(hi, lo_))
+// One step of a chain folds two entries into both halves of the accumulator: the lower half of `hi` and
+// the upper half of `lo_`.
+__device__ __forceinline__ uint32_t chain_step(uint32_t acc, uint32_t hi, uint32_t lo_) {
+    asm(PPO_STEP_ASM : "+v"(acc) : "v"(hi), "v"(lo_));
+    return acc;
+}
+// Start of an accumulator: +inf for x, and for y its first candidate (the upper half of b0) unless the
+// upper half of ctrl says +inf.  init_mask holds +inf in its lower half and 0 in its upper half.
+__device__ __forceinline__ uint32_t chain_init(uint32_t b0, uint32_t ctrl, uint32_t init_mask) {
+    uint32_t r;
+    asm("v_pk_maximum3_f16 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[1,1,1]" : "=v"(r) : "v"(b0), "s"(ctrl), "v"(init_mask));
+    return r;
+}
+// packed maximum with a mask, of the lower half of v in both halves
+__device__ __forceinline__ uint32_t pk_max_lower(uint32_t v, uint32_t mask) {
+    uint32_t r;
+    asm("v_pk_max_u16 %0, %1, %2 op_sel:[0,0] op_sel_hi:[0,1]" : "=v"(r) : "v"(v), "v"(mask));
+    return r;
+}
+// packed maximum with a mask, of the upper half of v in both halves
+__device__ __forceinline__ uint32_t pk_max_upper(uint32_t v, uint32_t mask) {
+    uint32_t r;
+    asm("v_pk_max_u16 %0, %1, %2 op_sel:[1,0] op_sel_hi:[1,1]" : "=v"(r) : "v"(v), "v"(mask));
+    return r;
+}
 
 template <bool EXPORT>
 __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
@@ -134,6 +156,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     unsigned long long best = PPO_KEY_NONE;
     uint32_t vzero;   // a zero the compiler cannot see through, kept in a vector register
     asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+    uint32_t init_mask = kCodeInf;   // kept in a vector register: the instruction using it takes one scalar operand
+    asm volatile("" : "+v"(init_mask));
 
     for (uint32_t gi = 0; gi < groups_per_block; ++gi) {
     const uint32_t group = group_first + 2u * gi;
@@ -257,12 +281,9 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         n_rounds += (2 * q + wsel) * kChunkPairs < NP ? 1 : 0;
     }
     // the nodes of row s for the six rounds, four bits each
-    auto node_pack = [&](int s) -> uint32_t {
-        if (s < p0) return 0x111111u * (uint32_t)prefix_node(s);
-        uint32_t r = 0;
-        for (int q = 0; q < 6; ++q) r |= (uint32_t)rest_node((int)((set_pack >> (4 * q)) & 15u)) << (4 * q);
-        return r;
-    };
+    uint32_t rest_pack = 0;
+    for (int q = 0; q < 6; ++q) rest_pack |= (uint32_t)rest_node((int)((set_pack >> (4 * q)) & 15u)) << (4 * q);
+    auto node_pack = [&](int s) -> uint32_t { return s < p0 ? 0x111111u * (uint32_t)prefix_node(s) : rest_pack; };
     // first lane set of row s in the schedule table
     auto first_set = [&](int s) { return s < p0 ? 36 : (s - p0) * 6; };
     // the lane's schedule entry for lane set `set`
@@ -337,68 +358,76 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 bn1[t] = lds_load(a);
                 bn[t] = lds_load(a + 128u);
             }
+            uint32_t acc[kChunkPairs];
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                uint32_t acc = kInf2, tmp;
+                // y's first candidate is the upper half of the dword at the output's own index
+                uint32_t a = chain_init(PPO_B(t, 0), ctrl[t], init_mask);
                 // steps min(n, kDeep) .. 1 from registers (see ppo_chain_asm.h)
                 asm volatile(PPO_CHAIN_ASM
-                             : "+v"(acc), "=&v"(tmp)
+                             : "+v"(a)
                              : "s"(ctrl[t] & WinDesc::kJumpMask), "v"(PPO_B(t, 0)), "v"(PPO_B(t, 1)), "v"(PPO_B(t, 2)),
                                "v"(PPO_B(t, 3)), "v"(PPO_B(t, 4)), "v"(PPO_B(t, 5)), "v"(PPO_B(t, 6)), "v"(PPO_B(t, 7)),
                                "v"(PPO_B(t, 8)), "v"(PPO_B(t, 9)), "v"(PPO_B(t, 10)), "v"(PPO_B(t, 11)),
                                "v"(PPO_B(t, 12)), "v"(PPO_B(t, 13)), "v"(PPO_B(t, 14)), "v"(PPO_B(t, 15)),
                                "v"(PPO_B(t, 16))
                              : "s98", "s99", "scc");
-                // the masked step: offsets 2n (dword n, both halves) and 2n+1 (straddling dwords n and n+1)
-                acc = pk_min3(acc, pk_max(bn[t], maskA[t]), pk_max(align16(bn[t], bn1[t]), maskB[t]));
-                if (ctrl[t] & (WinDesc::kDeepChain | WinDesc::kLongTail)) {
+                // the masked step: entry 2n (lower half of dword n) for both, entry 2n+1 (upper half of dword n+1) for x
+                acc[t] = pk_min3(a, pk_max_lower(bn[t], maskA[t]), pk_max_upper(bn1[t], maskB[t]));
+            }
+            // the rare rest: chains deeper than the registers and entries only x wants
+            if ((ctrl[0] | ctrl[1] | ctrl[2] | ctrl[3]) & (WinDesc::kDeepChain | WinDesc::kFold)) {
+#pragma unroll
+                for (int t = 0; t < kChunkPairs; ++t) {
+                    if ((ctrl[t] & (WinDesc::kDeepChain | WinDesc::kFold)) == 0u) continue;
+                    const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
                     if (ctrl[t] & WinDesc::kDeepChain) {
                         // the rest of a long chain walks further down the row
+                        uint32_t a = acc[t];
                         uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
                         uint32_t cur = PPO_B(t, kDeep);
-                        uint32_t m = WinDesc::steps(ctrl[t]) - (uint32_t)kDeep;
+                        uint32_t m = n - (uint32_t)kDeep;
                         while (m >= 4u) {
                             pa -= 512u;
                             const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u),
                                            b3 = lds_load(pa + 128u), b4 = lds_load(pa);
-                            PPO_STEP(cur, b1); PPO_STEP(b1, b2); PPO_STEP(b2, b3); PPO_STEP(b3, b4);
+                            a = chain_step(a, cur, b1);
+                            a = chain_step(a, b1, b2);
+                            a = chain_step(a, b2, b3);
+                            a = chain_step(a, b3, b4);
                             cur = b4;
                             m -= 4u;
                         }
                         while (m >= 1u) {
                             pa -= 128u;
                             const uint32_t b1 = lds_load(pa);
-                            PPO_STEP(cur, b1);
+                            a = chain_step(a, cur, b1);
                             cur = b1;
                             m -= 1u;
                         }
+                        acc[t] = a;
                     }
-                    if (ctrl[t] & WinDesc::kLongTail) {
-                        // the first position's window is longer by two or more: fold its extra offsets
-                        // nmin .. nmax-1 dword by dword, then across the two halves.  The dword `a` below the
-                        // output's index holds offset 2a in its lower half and offset 2a-1 in its upper half.
-                        const uint32_t nmin = WinDesc::nmin(ctrl[t]), nmax = WinDesc::nmax(ctrl[t]);
+                    if (ctrl[t] & WinDesc::kFold) {
+                        // x wants entries 2n+2 .. wx-1 as well: fold the dwords n+1 .. wx/2 below the output
+                        // (what else they hold lies inside x's window, except the lower half of the last one
+                        // when wx is even), then across the two halves, into x's half only
+                        const uint32_t wx = WinDesc::wx(ctrl[t]);
                         const uint32_t own = X.fbase + (uint32_t)(t + kDeep) * 128u;   // dword at the output's index
-                        uint32_t a_first, a_last;
-                        uint32_t tacc = kInf2;
-                        if ((nmin & 1u) == 0u) {   // top offset nmin is a lower half: the upper half is out of range
-                            tacc = pk_max(lds_load(own - (nmin >> 1) * 128u), kCodeInf << 16);
-                            a_first = (nmin >> 1) + 1u;
-                        } else {
-                            a_first = (nmin + 1u) >> 1;
-                        }
-                        if ((nmax & 1u) == 0u) {   // bottom offset nmax-1 is an upper half: the lower half is out of range
-                            tacc = pk_min(tacc, pk_max(lds_load(own - (nmax >> 1) * 128u), kCodeInf));
-                            a_last = (nmax >> 1) - 1u;
-                        } else {
-                            a_last = (nmax - 1u) >> 1;
-                        }
-                        for (uint32_t a = a_first; a <= a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
+                        const uint32_t a_last = wx >> 1;
+                        uint32_t tacc = pk_max(lds_load(own - a_last * 128u), (wx & 1u) ? 0u : kCodeInf);
+                        for (uint32_t a = n + 1u; a < a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
                         tacc = pk_min(tacc, align16(tacc, tacc));
-                        acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
+                        acc[t] = pk_min(acc[t], pk_max(tacc, kCodeInf << 16));
                     }
                 }
-                if (t < np) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc, X.qv[t]));
+            }
+            if (np >= kChunkPairs) {
+#pragma unroll
+                for (int t = 0; t < kChunkPairs; ++t) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
+            } else {
+#pragma unroll
+                for (int t = 0; t < kChunkPairs; ++t)
+                    if (t < np) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
             }
         };
 #undef PPO_B
@@ -460,7 +489,6 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         }
     }
 }
-#undef PPO_STEP
 
 hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin,
                                     uint32_t rank_end, uint64_t* best_key, float* beta_export, hipStream_t stream) {
