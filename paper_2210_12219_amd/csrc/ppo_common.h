@@ -45,8 +45,10 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 // 2n+2 .. wx-1) is folded separately.
 //   ctrl      bit  0      wx > 2n+2 (entries left for the separate fold)
 //             bit  1      n > kChainDepth (the chain continues below the registers)
+//             bit  2      bit 0 or bit 1 is set in some descriptor of this output's chunk
 //             bits 3..7   min(n, kChainDepth), so that ctrl & 0xF8 is 8 times that
-//             bits 8..15  wx
+//             bits 8..14  for the separate fold: wx/2 - (n+1), the number of dwords it reads beyond dword n+1
+//             bit  15     wx is even (the lower half of the last of these dwords is not wanted)
 //             bits 16..31 0 if y wants entry -1 (wy >= 1), else +inf: upper half of the accumulator's
 //                         initial mask (the lower half is +inf: x does not want entry -1)
 //   below     byte distance, in the lane's row (128 bytes per dword), from the first dword the task fetches
@@ -57,21 +59,22 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 constexpr int kChunkPairs = 4;
 constexpr int kChainDepth = PPO_CHAIN_DEPTH;
 struct WinDesc {
-    static constexpr uint32_t kFold = 0x1u, kDeepChain = 0x2u, kJumpMask = 0xF8u;
+    static constexpr uint32_t kFold = 0x1u, kDeepChain = 0x2u, kChunkRare = 0x4u, kJumpMask = 0xF8u, kWxEven = 0x8000u;
     static constexpr int kWords = 4;
-    __host__ __device__ static uint32_t wx(uint32_t ctrl) { return (ctrl >> 8) & 0xFFu; }
+    __host__ __device__ static uint32_t fold_dwords(uint32_t ctrl) { return (ctrl >> 8) & 0x7Fu; }
     // number of steps, from the second word and the output's place t in its chunk
     __host__ __device__ static uint32_t steps(uint32_t below, uint32_t t) {
         return t + (uint32_t)kChainDepth - 1u - (uint32_t)((int32_t)below >> 7);
     }
-    // descriptor of output column jj from the two window lengths
+    // descriptor of output column jj from the two window lengths (without bit 2 of ctrl)
     __host__ __device__ static void pack(uint32_t jj, uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& below,
                                          uint32_t& maskA, uint32_t& maskB) {
         const uint32_t inf = kCodeInf;
         const uint32_t C = wy >= 1u ? (wx < wy - 1u ? wx : wy - 1u) : 0u;
         const uint32_t n = C >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
-        ctrl = (wx > 2u * n + 2u ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 3) | (wx << 8) |
-               ((wy >= 1u ? 0u : inf) << 16);
+        const bool fold = wx > 2u * n + 2u;
+        ctrl = (fold ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 3) |
+               (fold ? (((wx >> 1) - (n + 1u)) << 8) | ((wx & 1u) ? 0u : kWxEven) : 0u) | ((wy >= 1u ? 0u : inf) << 16);
         below = ((jj % kChunkPairs) + (uint32_t)kChainDepth - 1u - n) * 128u;
         maskA = (wx > 2u * n ? 0u : inf) | ((C > 2u * n ? 0u : inf) << 16);
         maskB = (wx > 2u * n + 1u ? 0u : inf) | (inf << 16);

@@ -376,13 +376,12 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 acc[t] = pk_min3(a, pk_max_lower(bn[t], maskA[t]), pk_max_upper(bn1[t], maskB[t]));
             }
             // the rare rest: chains deeper than the registers and entries only x wants
-            if ((ctrl[0] | ctrl[1] | ctrl[2] | ctrl[3]) & (WinDesc::kDeepChain | WinDesc::kFold)) {
+            if (ctrl[0] & WinDesc::kChunkRare) {
 #pragma unroll
                 for (int t = 0; t < kChunkPairs; ++t) {
-                    if ((ctrl[t] & (WinDesc::kDeepChain | WinDesc::kFold)) == 0u) continue;
-                    const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
                     if (ctrl[t] & WinDesc::kDeepChain) {
                         // the rest of a long chain walks further down the row
+                        const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
                         uint32_t a = acc[t];
                         uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
                         uint32_t cur = PPO_B(t, kDeep);
@@ -411,11 +410,19 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         // x wants entries 2n+2 .. wx-1 as well: fold the dwords n+1 .. wx/2 below the output
                         // (what else they hold lies inside x's window, except the lower half of the last one
                         // when wx is even), then across the two halves, into x's half only
-                        const uint32_t wx = WinDesc::wx(ctrl[t]);
-                        const uint32_t own = X.fbase + (uint32_t)(t + kDeep) * 128u;   // dword at the output's index
-                        const uint32_t a_last = wx >> 1;
-                        uint32_t tacc = pk_max(lds_load(own - a_last * 128u), (wx & 1u) ? 0u : kCodeInf);
-                        for (uint32_t a = n + 1u; a < a_last; ++a) tacc = pk_min(tacc, lds_load(own - a * 128u));
+                        const uint32_t cnt = WinDesc::fold_dwords(ctrl[t]);
+                        const uint32_t last_mask = (ctrl[t] & WinDesc::kWxEven) ? kCodeInf : 0u;
+                        uint32_t pa = X.fbase + below[t];   // dword n+1
+                        uint32_t tacc = bn1[t];
+                        if (cnt == 0u) {
+                            tacc = pk_max(tacc, last_mask);
+                        } else {
+                            for (uint32_t i = 1; i < cnt; ++i) {
+                                pa -= 128u;
+                                tacc = pk_min(tacc, lds_load(pa));
+                            }
+                            tacc = pk_min(tacc, pk_max(lds_load(pa - 128u), last_mask));
+                        }
                         tacc = pk_min(tacc, align16(tacc, tacc));
                         acc[t] = pk_min(acc[t], pk_max(tacc, kCodeInf << 16));
                     }

@@ -57,22 +57,31 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
     {
         uint32_t* wt = reinterpret_cast<uint32_t*>(base + y.wt_off);
         const int rows = k > 2 ? k - 2 : 0, cols = y.wt_cols;
-        for (int idx = tid; idx < k * rows * cols; idx += kPreThreads) {
-            const int jj = idx % cols, s = (idx / cols) % rows + 1, j = idx / (cols * rows);
+        const int chunks = cols / kChunkPairs;
+        for (int idx = tid; idx < k * rows * chunks; idx += kPreThreads) {
+            const int ch = idx % chunks, s = (idx / chunks) % rows + 1, j = idx / (chunks * rows);
             const int emax = L - k + 1 + s;
-            uint32_t w[2];
-            for (int h = 0; h < 2; ++h) {
-                const int e = 2 * jj + s + h;
-                int v = 0;
-                if (e >= s + 1 && e <= emax) {
-                    const int l = lo[j * (L + 1) + e];
-                    v = e - (l > s ? l : s);
+            uint32_t* row = wt + (size_t)(idx - ch) * (kChunkPairs * WinDesc::kWords);
+            uint32_t rare = 0;
+            for (int t = 0; t < kChunkPairs; ++t) {
+                const int jj = ch * kChunkPairs + t;
+                uint32_t w[2];
+                for (int h = 0; h < 2; ++h) {
+                    const int e = 2 * jj + s + h;
+                    int v = 0;
+                    if (e >= s + 1 && e <= emax) {
+                        const int l = lo[j * (L + 1) + e];
+                        v = e - (l > s ? l : s);
+                    }
+                    w[h] = (uint32_t)v;
                 }
-                w[h] = (uint32_t)v;
+                uint32_t& ctrl = row[WinDesc::offset(jj, 0)];
+                WinDesc::pack((uint32_t)jj, w[0], w[1], ctrl, row[WinDesc::offset(jj, 1)], row[WinDesc::offset(jj, 2)],
+                              row[WinDesc::offset(jj, 3)]);
+                rare |= ctrl & (WinDesc::kFold | WinDesc::kDeepChain);
             }
-            uint32_t* row = wt + (size_t)(idx - jj) * WinDesc::kWords;
-            WinDesc::pack((uint32_t)jj, w[0], w[1], row[WinDesc::offset(jj, 0)], row[WinDesc::offset(jj, 1)],
-                          row[WinDesc::offset(jj, 2)], row[WinDesc::offset(jj, 3)]);
+            if (rare)
+                for (int t = 0; t < kChunkPairs; ++t) row[WinDesc::offset(ch * kChunkPairs + t, 0)] |= WinDesc::kChunkRare;
         }
     }
     {
