@@ -46,7 +46,8 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   ctrl      bit  0      wx > 2n+2 (entries left for the separate fold)
 //             bit  1      n > kChainDepth (the chain continues below the registers)
 //             bit  2      bit 0 or bit 1 is set in some descriptor of this output's chunk
-//             bits 3..7   min(n, kChainDepth), so that ctrl & 0xF8 is 8 times that
+//             bits 3..7   ctrl & 0xF8 = PPO_CHAIN_ENTRY0 + 8 * (kChainDepth - min(n, kChainDepth)): the byte distance
+//                         the chain's computed jump adds to reach the first step to execute
 //             bits 8..14  for the separate fold: wx/2 - (n+1), the number of dwords it reads beyond dword n+1
 //             bit  15     wx is even (the lower half of the last of these dwords is not wanted)
 //             bits 16..31 0 if y wants entry -1 (wy >= 1), else +inf: upper half of the accumulator's
@@ -58,6 +59,7 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   maskB     for entry 2n+1: lower half as above; upper half +inf (y never wants it)
 constexpr int kChunkPairs = 4;
 constexpr int kChainDepth = PPO_CHAIN_DEPTH;
+static_assert(PPO_CHAIN_ENTRY0 % 8 == 0 && PPO_CHAIN_ENTRY0 + 8 * PPO_CHAIN_DEPTH <= 0xF8, "jump distance must fit bits 3..7");
 struct WinDesc {
     static constexpr uint32_t kFold = 0x1u, kDeepChain = 0x2u, kChunkRare = 0x4u, kJumpMask = 0xF8u, kWxEven = 0x8000u;
     static constexpr int kWords = 4;
@@ -73,7 +75,8 @@ struct WinDesc {
         const uint32_t C = wy >= 1u ? (wx < wy - 1u ? wx : wy - 1u) : 0u;
         const uint32_t n = C >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
         const bool fold = wx > 2u * n + 2u;
-        ctrl = (fold ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) | (nc << 3) |
+        ctrl = (fold ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) |
+               ((uint32_t)PPO_CHAIN_ENTRY0 + 8u * ((uint32_t)kChainDepth - nc)) |
                (fold ? (((wx >> 1) - (n + 1u)) << 8) | ((wx & 1u) ? 0u : kWxEven) : 0u) | ((wy >= 1u ? 0u : inf) << 16);
         below = ((jj % kChunkPairs) + (uint32_t)kChainDepth - 1u - n) * 128u;
         maskA = (wx > 2u * n ? 0u : inf) | ((C > 2u * n ? 0u : inf) << 16);
