@@ -28,11 +28,14 @@
 #include "ppo_common.h"
 #include "ppo_group_tables.h"
 
+#include <type_traits>
+
 namespace ppo {
 
 constexpr int kGrpWaves = 12;
 constexpr int kGrpThreads = kGrpWaves * 64;
-constexpr int kGrpMaxPairs = 6 * 2 * kChunkPairs;   // six rounds of two chunks cover at most 48 dwords
+constexpr int kJobPairs = 12;                        // output dwords of a job (three chunks)
+constexpr int kGrpMaxPairs = 4 * kJobPairs;          // a wave runs two jobs per row: at most four parts per lane set
 constexpr int kDeep = kChainDepth;                   // chain steps available from prefetched registers
 constexpr uint32_t kInf2 = kCodeInf | (kCodeInf << 16);
 
@@ -252,98 +255,99 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
     }
 
-    // ---- rows 1 .. k-2.  A task = (lane set, chunk of four output dwords).  Its inputs are the input
-    //      dwords from (jbeg - kDeep) to (jbeg + 3) of the lane's row (the four at the outputs' own indices
-    //      and the kDeep below them), the next link's quotients for the four outputs and the four chain
-    //      descriptors.  All of it is requested one task ahead, into a second set of registers, so that a
-    //      task never waits for its own loads; the lane's schedule entry is requested two tasks ahead.
-    constexpr int kNB = kChunkPairs + kDeep;
-    struct TaskAux {
+    // ---- rows 1 .. k-2.  The output dwords of a lane set's row are cut into parts of kJobPairs dwords; a job
+    //      = (lane set, part).  With the parts numbered from the top, job i is part i/6 of lane set i%6; a
+    //      wave runs jobs number `wave` and, from the other end of the list, `njobs-1-wave` (a long part and a
+    //      short one, of different lane sets), at most two in a row of the DP.  A job fetches the input dwords
+    //      from (first - kDeep) to (first + kJobPairs - 1) of the lane's row into registers, once, and then
+    //      works through its chunks of four output dwords; each chunk's descriptors and next-link quotients
+    //      are requested one chunk ahead.
+    constexpr int kJobChunks = kJobPairs / kChunkPairs, kNB = kJobPairs + kDeep;
+    struct ChunkIn {
         uint4 ctrl, below, maskA, maskB;   // descriptors of the four outputs, word by word
-        uint32_t qv[kChunkPairs];
-        uint32_t fbase;      // LDS byte address of B[0]
-        uint32_t out_addr;   // LDS byte address of the first output
+        uint32_t qv[kChunkPairs];          // quotients of the next link for the four outputs
     };
-    const int wsel = wave >= 6 ? 1 : 0;
+    struct Job {
+        uint32_t ent;        // the lane's schedule entry for the job's lane set
+        uint32_t fbase;      // LDS byte address of the first input dword fetched
+        uint32_t out_addr;   // LDS byte address of the first output dword
+        uint32_t qa_addr;    // LDS byte address of the quotient dword of the first output
+    };
     const uint32_t buf0_addr = lds_addr(buf0), buf1_addr = lds_addr(buf1), qtab_addr = lds_addr(qtab);
     const uint32_t desc_node_stride = (uint32_t)((k - 2) * y.wt_cols * WinDesc::kWords);
     uint32_t ent_lane = lds_addr(lds + gs.slot_off) + 2u * (uint32_t)lane;   // the lane's column of the schedule table
     asm volatile("" : "+v"(ent_lane));
-    // The wave works on lane set (wave + q) mod 6 in round q: the six of them four bits each, and the
-    // number of rounds whose chunk 2q + wsel lies inside the row.
-    uint32_t set_pack = 0;
-    int n_rounds = 0;
-    for (int q = 0; q < 6; ++q) {
-        int c = wave + q;
-        c = c >= 12 ? c - 12 : c;
-        c = c >= 6 ? c - 6 : c;
-        set_pack |= (uint32_t)c << (4 * q);
-        n_rounds += (2 * q + wsel) * kChunkPairs < NP ? 1 : 0;
+    const int nparts = (NP + kJobPairs - 1) / kJobPairs, njobs = 6 * nparts;
+    // the wave's two jobs: lane set and first output dword
+    const int job_index[2] = {wave, njobs - 1 - wave};
+    const bool job_valid[2] = {wave < njobs, njobs - 1 - wave >= kGrpWaves};
+    int job_set[2], job_first[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int i = job_valid[j] ? job_index[j] : 0;
+        job_set[j] = i % 6;
+        job_first[j] = (nparts - 1 - i / 6) * kJobPairs;
     }
-    // the nodes of row s for the six rounds, four bits each
-    uint32_t rest_pack = 0;
-    for (int q = 0; q < 6; ++q) rest_pack |= (uint32_t)rest_node((int)((set_pack >> (4 * q)) & 15u)) << (4 * q);
-    auto node_pack = [&](int s) -> uint32_t { return s < p0 ? 0x111111u * (uint32_t)prefix_node(s) : rest_pack; };
     // first lane set of row s in the schedule table
     auto first_set = [&](int s) { return s < p0 ? 36 : (s - p0) * 6; };
-    // the lane's schedule entry for lane set `set`
-    auto load_ent = [&](uint32_t set) -> uint32_t { return (uint32_t)lds_load_u16(ent_lane + set * 128u); };
-    // The chain descriptors of a task.  They are the same for every lane, but they are fetched with vector
-    // loads on purpose: scalar loads complete under the same counter as LDS reads, out of order, so one in
-    // flight would make every wait for an LDS result a wait for everything.
-    auto load_desc = [&](int s, int q, uint32_t node, TaskAux& X) {
-        const uint32_t off = node * desc_node_stride +
-                             (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords + (2 * q + wsel) * (WinDesc::kWords * kChunkPairs));
-        const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
-        X.ctrl = dp[0];
-        X.below = dp[1];
-        X.maskA = dp[2];
-        X.maskB = dp[3];
+    auto load_ent = [&](int s, int j) -> uint32_t {
+        return (uint32_t)lds_load_u16(ent_lane + (uint32_t)(first_set(s) + job_set[j]) * 128u);
     };
-    // what the first task of the next row needs and does not depend on the row before it is requested
+    // Descriptors and quotients of chunk c of job j in row s.  The descriptors are the same for every lane,
+    // but they are fetched with vector loads on purpose: scalar loads complete under the same counter as LDS
+    // reads, out of order, so one in flight would make every wait for an LDS result a wait for everything.
+    auto chunk_live = [&](int j, int c) { return job_valid[j] && job_first[j] + c * kChunkPairs < NP; };
+    auto request_chunk = [&](int s, int j, int c, const Job& J, ChunkIn& D) {
+        const uint32_t node = (uint32_t)row_node(s, job_set[j]);
+        const uint32_t off = node * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
+                             (uint32_t)((job_first[j] / kChunkPairs + c) * (WinDesc::kWords * kChunkPairs));
+        const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
+        D.ctrl = dp[0];
+        D.below = dp[1];
+        D.maskA = dp[2];
+        D.maskB = dp[3];
+#pragma unroll
+        for (int t = 0; t < kChunkPairs; ++t) D.qv[t] = lds_load(J.qa_addr + (uint32_t)((c * kChunkPairs + t) * 4));
+    };
+    // the parts of a job's addresses that do not depend on the buffers' roles: from the schedule entry
+    auto job_quotients = [&](int s, int j, Job& J) {
+        // row of the quotient table = a base + a field of the schedule entry
+        const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
+        const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
+        const uint32_t lr = lr_base + ((J.ent >> lr_shift) & lr_mask);
+        J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + 4u * (uint32_t)(link_col(s) + job_first[j]));
+    };
+
+    // what the first chunk of the next row needs and does not depend on the row before it is requested
     // ahead of the barrier that ends that row
-    TaskAux X0, X1;
-    uint32_t nodes_next = node_pack(1);
-    uint32_t ent_a = load_ent((uint32_t)first_set(1) + (set_pack & 15u)), ent_b = 0;
-    load_desc(1, 0, nodes_next & 15u, X0);
+    Job J0, J1;
+    ChunkIn DA, DB;
+    J0.ent = load_ent(1, 0);
+    J1.ent = load_ent(1, 1);
+    job_quotients(1, 0, J0);
+    if (chunk_live(0, 0)) request_chunk(1, 0, 0, J0, DA);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
         const uint32_t in_addr = (s & 1) ? buf0_addr : buf1_addr, out_addr = (s & 1) ? buf1_addr : buf0_addr;
-        // byte address of the quotient dword (q[e-1], q[e]) of output 0, before the row of the link is added
-        const uint32_t q_addr = qtab_addr + 4u * (uint32_t)link_col(s);
-        // row of the quotient table = lr_base + a field of the schedule entry
-        const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
-        const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
-        const uint32_t set0 = (uint32_t)first_set(s);
-        // lane sets and nodes of the rounds not yet requested, this round's in the low four bits
-        uint32_t sets = set_pack, nodes = nodes_next;
-
-        // requests the inputs of the task of round q, whose schedule entry is ent; ent_next receives the
-        // entry of the task of round q+1
-        auto request = [&](int q, uint32_t ent, uint32_t& ent_next, uint32_t (&B)[kNB], TaskAux& X, bool with_desc) {
-            const int jbeg = (2 * q + wsel) * kChunkPairs;
-            const uint32_t slot_dw = slot_dword(ent);
-            const uint32_t lr = lr_base + ((ent >> lr_shift) & lr_mask);
-            uint32_t qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (q_addr + (uint32_t)(jbeg * 4));
-            X.out_addr = out_addr + (uint32_t)(jbeg * 128) + slot_dw * 4u;
-            X.fbase = in_addr + (uint32_t)((jbeg - kDeep) * 128) + slot_dw * 4u;
-            asm volatile("" : "+v"(X.fbase), "+v"(qa_addr));
+        uint32_t B0[kNB], B1[kNB];
+        // addresses of a job and the fetch of its input dwords
+        auto start_job = [&](int j, Job& J, uint32_t (&B)[kNB]) {
+            const uint32_t slot_b = slot_dword(J.ent) * 4u;
+            J.out_addr = out_addr + (uint32_t)(job_first[j] * 128) + slot_b;
+            J.fbase = in_addr + (uint32_t)((job_first[j] - kDeep) * 128) + slot_b;
+            asm volatile("" : "+v"(J.fbase));
 #pragma unroll
-            for (int j = 0; j < kNB; ++j) B[j] = lds_load(X.fbase + (uint32_t)j * 128u);
-#pragma unroll
-            for (int t = 0; t < kChunkPairs; ++t) X.qv[t] = lds_load(qa_addr + (uint32_t)t * 4u);
-            if (with_desc) load_desc(s, q, nodes & 15u, X);
-            sets >>= 4;
-            nodes >>= 4;
-            if (q + 1 < 6) ent_next = load_ent(set0 + (sets & 15u));
+            for (int i = 0; i < kNB; ++i) B[i] = lds_load(J.fbase + (uint32_t)i * 128u);
         };
 
-        // b(t, i): the input dword i below the index of output t (i = 0: the dword at that index)
-#define PPO_B(t, i) B[(t) + kDeep - (i)]
-        auto run = [&](int q, const uint32_t (&B)[kNB], const TaskAux& X) {
-            const int jbeg = (2 * q + wsel) * kChunkPairs;
-            const int np = NP - jbeg;   // outputs beyond the row end are computed from null descriptors, not stored
+        // chunk c of a job: B holds the job's input dwords, D the chunk's descriptors and quotients
+        // b(t, i): the input dword i below the index of output t of the chunk (i = 0: the dword at that index)
+#define PPO_B(t, i) B[c * kChunkPairs + (t) + kDeep - (i)]
+        auto run_chunk = [&](int j, auto c_tag, const Job& J, const uint32_t (&B)[kNB], const ChunkIn& X) {
+            constexpr int c = decltype(c_tag)::value;
+            const int np = NP - (job_first[j] + c * kChunkPairs);   // outputs beyond the row end are not stored
+            const uint32_t cbase = J.fbase + (uint32_t)(c * kChunkPairs * 128);   // first dword fetched for this chunk
             const uint32_t ctrl[kChunkPairs] = {
                 (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.x), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.y),
                 (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.z), (uint32_t)__builtin_amdgcn_readfirstlane(X.ctrl.w)};
@@ -354,7 +358,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             uint32_t bn[kChunkPairs], bn1[kChunkPairs];
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                const uint32_t a = X.fbase + below[t];
+                const uint32_t a = cbase + below[t];
                 bn1[t] = lds_load(a);
                 bn[t] = lds_load(a + 128u);
             }
@@ -383,7 +387,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         // the rest of a long chain walks further down the row
                         const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
                         uint32_t a = acc[t];
-                        uint32_t pa = X.fbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
+                        uint32_t pa = cbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
                         uint32_t cur = PPO_B(t, kDeep);
                         uint32_t m = n - (uint32_t)kDeep;
                         while (m >= 4u) {
@@ -412,7 +416,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         // when wx is even), then across the two halves, into x's half only
                         const uint32_t cnt = WinDesc::fold_dwords(ctrl[t]);
                         const uint32_t last_mask = (ctrl[t] & WinDesc::kWxEven) ? kCodeInf : 0u;
-                        uint32_t pa = X.fbase + below[t];   // dword n+1
+                        uint32_t pa = cbase + below[t];   // dword n+1
                         uint32_t tacc = bn1[t];
                         if (cnt == 0u) {
                             tacc = pk_max(tacc, last_mask);
@@ -428,30 +432,48 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                     }
                 }
             }
+            const uint32_t obase = J.out_addr + (uint32_t)(c * kChunkPairs * 128);
             if (np >= kChunkPairs) {
 #pragma unroll
-                for (int t = 0; t < kChunkPairs; ++t) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
+                for (int t = 0; t < kChunkPairs; ++t) lds_store(obase + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
             } else {
 #pragma unroll
                 for (int t = 0; t < kChunkPairs; ++t)
-                    if (t < np) lds_store(X.out_addr + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
+                    if (t < np) lds_store(obase + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
             }
         };
 #undef PPO_B
 
-        uint32_t B0[kNB], B1[kNB];
-        if (n_rounds > 0) request(0, ent_a, ent_b, B0, X0, false);
-        for (int q = 0; q < n_rounds; q += 2) {
-            const bool live1 = q + 1 < n_rounds;
-            if (live1) request(q + 1, ent_b, ent_a, B1, X1, true);
-            run(q, B0, X0);
-            if (q + 2 < n_rounds) request(q + 2, ent_a, ent_b, B0, X0, true);
-            if (live1) run(q + 1, B1, X1);
+        if (job_valid[0]) start_job(0, J0, B0);
+        // the six chunks in turn, each requesting what the next one needs before it starts
+        using C0 = std::integral_constant<int, 0>;
+        using C1 = std::integral_constant<int, 1>;
+        using C2 = std::integral_constant<int, 2>;
+        static_assert(kJobChunks == 3, "the sequence below is written for three chunks per job");
+        if (chunk_live(0, 1)) request_chunk(s, 0, 1, J0, DB);
+        if (chunk_live(0, 0)) run_chunk(0, C0{}, J0, B0, DA);
+        // the second job's input dwords are fetched here rather than with the first job's, right after the
+        // barrier, when every wave of the workgroup is waiting for LDS
+        if (job_valid[1]) {
+            job_quotients(s, 1, J1);
+            start_job(1, J1, B1);
         }
+        if (chunk_live(0, 2)) request_chunk(s, 0, 2, J0, DA);
+        if (chunk_live(0, 1)) run_chunk(0, C1{}, J0, B0, DB);
+        if (chunk_live(1, 0)) request_chunk(s, 1, 0, J1, DB);
+        if (chunk_live(0, 2)) run_chunk(0, C2{}, J0, B0, DA);
+        if (chunk_live(1, 1)) request_chunk(s, 1, 1, J1, DA);
+        if (chunk_live(1, 0)) run_chunk(1, C0{}, J1, B1, DB);
+        if (chunk_live(1, 2)) request_chunk(s, 1, 2, J1, DB);
+        if (chunk_live(1, 1)) run_chunk(1, C1{}, J1, B1, DA);
         if (s + 1 <= k - 2) {
-            nodes_next = node_pack(s + 1);
-            ent_a = load_ent((uint32_t)first_set(s + 1) + (set_pack & 15u));
-            load_desc(s + 1, 0, nodes_next & 15u, X0);
+            J0.ent = load_ent(s + 1, 0);
+            J1.ent = load_ent(s + 1, 1);
+        }
+        if (chunk_live(1, 2)) run_chunk(1, C2{}, J1, B1, DB);
+        if (s + 1 <= k - 2) {
+            job_quotients(s + 1, 0, J0);
+            if (chunk_live(0, 0)) request_chunk(s + 1, 0, 0, J0, DA);
         }
         __syncthreads();
     }
