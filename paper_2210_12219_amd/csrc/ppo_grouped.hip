@@ -65,7 +65,7 @@ __device__ __forceinline__ uint32_t align16(uint32_t hi, uint32_t lo) { return _
 
 struct GroupedShape {
     int NE, NP, QD, QROW, nA, nB, nQ;
-    uint32_t buf_off, buf_dwords, q_off, slot_off, total_bytes;  // offsets in dwords
+    uint32_t buf_off, buf_dwords, q_off, slot_off, d0_off, total_bytes;  // offsets in dwords
     __host__ __device__ static GroupedShape make(int L, int k) {
         GroupedShape g;
         g.NE = L - k + 2;
@@ -80,7 +80,8 @@ struct GroupedShape {
         g.buf_dwords = 12u * g.NP * 32u;
         g.q_off = g.buf_off + 2u * g.buf_dwords;
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
-        g.total_bytes = (g.slot_off + 42u * 64u / 2u) * 4u;   // schedule entries are 16 bits
+        g.d0_off = g.slot_off + 42u * 64u / 2u;   // schedule entries are 16 bits
+        g.total_bytes = (g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4))) * 4u;
         return g;
     }
 };
@@ -155,22 +156,22 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&kLaneSlot[par][0][0]);
         for (int i = tid; i < 42 * 64 / 2; i += kGrpThreads) lds[gs.slot_off + i] = src[i];
         for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
+        // the first rows of all nodes (two codes per dword), the same for every group of the instance
+        const uint32_t* d0src = reinterpret_cast<const uint32_t*>(base + y.d0_off);
+        for (int i = tid; i < k * y.wt_cols; i += kGrpThreads) lds[gs.d0_off + i] = d0src[i];
     }
+    // best (code of beta, rank) of this lane so far: within an instance codes order like the values they stand
+    // for, so the value is looked up once, at the end (the per-ordering export looks every value up)
     unsigned long long best = PPO_KEY_NONE;
     uint32_t vzero;   // a zero the compiler cannot see through, kept in a vector register
     asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
     uint32_t init_mask = kCodeInf;   // kept in a vector register: the instruction using it takes one scalar operand
     asm volatile("" : "+v"(init_mask));
 
-    for (uint32_t gi = 0; gi < groups_per_block; ++gi) {
-    const uint32_t group = group_first + 2u * gi;
-    if (group >= group_end) break;
-    const uint32_t pr = group >> 1;
-
-    // ---- prefix: positions 0..p0-1 from the Lehmer digits of pr (weights (k-1-p)!/6!); `avail` ends up
-    //      holding the six remaining nodes in ascending order, four bits each
-    uint64_t avail_ = 0xBA9876543210ull, prefix_ = 0;
-    {
+    // ---- prefix of a group: positions 0..p0-1 from the Lehmer digits of its index (weights (k-1-p)!/6!);
+    //      `avail` ends up holding the six remaining nodes in ascending order, four bits each
+    auto decode_group = [&](uint32_t pr, uint64_t& prefix_out, uint64_t& avail_out) {
+        uint64_t avail_ = 0xBA9876543210ull, prefix_ = 0;
         uint32_t rem = pr;
         for (int p = 0; p < p0; ++p) {
             const uint32_t f = factorial_u32(k - 1 - p) / 720u;
@@ -182,9 +183,63 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             avail_ = lowbits | ((avail_ >> 4) & ~((1ull << sh) - 1ull));
             prefix_ |= node << (4 * p);
         }
+        prefix_out = prefix_;
+        avail_out = avail_;
+    };
+    // ---- the quotient rows of the links a group can cross: wave w fetches rows w, w+12, ... into registers
+    //      (a group ahead of their use) and writes them to LDS when the group starts
+    constexpr int kQRows = (PPO_MAX_K - 7 + 6 + 15 + kGrpWaves - 1) / kGrpWaves, kQCols = (2 * (PPO_MAX_L / 2 + 1) + 2 + 63) / 64;
+    auto fetch_quotients = [&](uint64_t prefix, uint64_t avail, uint32_t (&qreg)[kQRows * kQCols]) {
+        auto pnode = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
+        auto rnode = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
+#pragma unroll
+        for (int r = 0; r < kQRows; ++r) {
+            const int row = wave + r * kGrpWaves;
+            if (row < gs.nQ) {
+                int a, b;
+                if (row < nA) {
+                    a = pnode(row); b = pnode(row + 1);
+                } else if (row < nA + nB) {
+                    a = pnode(p0 - 1); b = rnode(row - nA);
+                } else {
+                    int pi = row - nA - nB, ca = 0;
+                    while (pi >= 5 - ca) { pi -= 5 - ca; ++ca; }
+                    a = rnode(ca); b = rnode(ca + 1 + pi);
+                }
+                const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
+#pragma unroll
+                for (int c = 0; c < kQCols; ++c) {
+                    const int col = lane + 64 * c;
+                    if (col < QROW) qreg[r * kQCols + c] = qsrc[col];
+                }
+            }
+        }
+    };
+    auto store_quotients = [&](const uint32_t (&qreg)[kQRows * kQCols]) {
+#pragma unroll
+        for (int r = 0; r < kQRows; ++r) {
+            const int row = wave + r * kGrpWaves;
+            if (row < gs.nQ) {
+#pragma unroll
+                for (int c = 0; c < kQCols; ++c) {
+                    const int col = lane + 64 * c;
+                    if (col < QROW) qtab[row * QROW + col] = qreg[r * kQCols + c];
+                }
+            }
+        }
+    };
+    uint32_t qreg[kQRows * kQCols];
+    uint64_t next_prefix = 0, next_avail = 0;
+    if (group_first < group_end) {
+        decode_group(group_first >> 1, next_prefix, next_avail);
+        fetch_quotients(next_prefix, next_avail, qreg);
     }
-    const uint64_t avail = avail_, prefix = prefix_;
-    auto prefix_node = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
+
+    for (uint32_t gi = 0; gi < groups_per_block; ++gi) {
+    const uint32_t group = group_first + 2u * gi;
+    if (group >= group_end) break;
+    const uint32_t pr = group >> 1;
+    const uint64_t avail = next_avail, prefix = next_prefix;
     auto rest_node = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
     // node at DP row s for the lane set of remaining-node index c
     auto row_node = [=](int s, int c) {
@@ -192,24 +247,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const int idx = s < p0 ? s : c;
         return (int)((packed >> (4 * idx)) & 0xFull);
     };
-
-    // ---- stage the quotient rows of the links this group can cross
-    {
-        for (int row = wave; row < gs.nQ; row += kGrpWaves) {
-            int a, b;
-            if (row < nA) {
-                a = prefix_node(row); b = prefix_node(row + 1);
-            } else if (row < nA + nB) {
-                a = prefix_node(p0 - 1); b = rest_node(row - nA);
-            } else {
-                int pi = row - nA - nB, ca = 0;
-                while (pi >= 5 - ca) { pi -= 5 - ca; ++ca; }
-                a = rest_node(ca); b = rest_node(ca + 1 + pi);
-            }
-            const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
-            for (int col = lane; col < QROW; col += 64) qtab[row * QROW + col] = qsrc[col];
-        }
-    }
+    store_quotients(qreg);
     __syncthreads();
 
     // quotient row used when row s is written (the link between the nodes of rows s and s+1), from the
@@ -241,8 +279,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t ent = slotTab[set * 64 + lane];
         uint32_t* out = buf0 + slot_dword(ent);
         const uint32_t* qrow = qtab + link_row(0, ent) * QROW + link_col(0);
-        // the initial row of the node, two codes per dword (vector loads: see the note on descriptors below)
-        const uint32_t* d0row = reinterpret_cast<const uint32_t*>(base + y.d0_off) + node * y.wt_cols + vzero;
+        const uint32_t* d0row = lds + gs.d0_off + node * y.wt_cols;   // the initial row of the node
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
         int jj = j0;
         for (; jj + 4 <= j1; jj += 4) {
@@ -330,6 +367,11 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 
     for (int s = 1; s <= k - 2; ++s) {
         const uint32_t in_addr = (s & 1) ? buf0_addr : buf1_addr, out_addr = (s & 1) ? buf1_addr : buf0_addr;
+        // the next group's quotient rows are requested one row of the DP before this group ends
+        if (s == k - 2 && gi + 1 < groups_per_block && group + 2u < group_end) {
+            decode_group((group + 2u) >> 1, next_prefix, next_avail);
+            fetch_quotients(next_prefix, next_avail, qreg);
+        }
         uint32_t B0[kNB], B1[kNB];
         // addresses of a job and the fetch of its input dwords
         auto start_job = [&](int j, Job& J, uint32_t (&B)[kNB]) {
@@ -497,11 +539,13 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         }
         const uint32_t cx = acc & 0xFFFFu, cy = acc >> 16;
         const uint32_t code = cx < cy ? cx : cy;
-        const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
         const uint32_t r = pr * 720u + ((perm >> 18) & 1023u);
         if (active && r >= rank_begin && r < rank_end) {
-            if (EXPORT) beta_export[r - rank_begin] = __uint_as_float(bits);
-            const unsigned long long key = ((unsigned long long)bits << 32) | r;
+            if (EXPORT) {
+                const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+                beta_export[r - rank_begin] = __uint_as_float(bits);
+            }
+            const unsigned long long key = ((unsigned long long)code << 32) | r;
             best = key < best ? key : best;
         }
     }
@@ -514,7 +558,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             best = o < best ? o : best;
         }
         if (lane == 0 && best != PPO_KEY_NONE) {
-            if (best < best_key[inst]) atomicMin(best_key + inst, best);
+            const uint32_t code = (uint32_t)(best >> 32);
+            const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+            const unsigned long long key = ((unsigned long long)bits << 32) | (best & 0xFFFFFFFFull);
+            if (key < best_key[inst]) atomicMin(best_key + inst, key);
         }
     }
 }
