@@ -293,10 +293,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     }
 
     // ---- rows 1 .. k-2.  The output dwords of a lane set's row are cut into parts of kJobPairs dwords; a job
-    //      = (lane set, part).  With the parts numbered from the top, job i is part i/6 of lane set i%6; a
-    //      wave runs jobs number `wave` and, from the other end of the list, `njobs-1-wave` (a long part and a
-    //      short one, of different lane sets), at most two in a row of the DP.  A job fetches the input dwords
-    //      from (first - kDeep) to (first + kJobPairs - 1) of the lane's row into registers, once, and then
+    //      = (lane set, part).  With the parts numbered from the top, a wave runs part wave/6 and the part two
+    //      below it (the top part is short and the bottom one has short windows, so that the two sums come out
+    //      about even), of lane sets wave%6 and (wave+3)%6, at most two jobs in a row of the DP.  A job fetches
+    //      the input dwords from (first - kDeep) to (first + kJobPairs - 1) of the lane's row into registers, once, and then
     //      works through its chunks of four output dwords; each chunk's descriptors and next-link quotients
     //      are requested one chunk ahead.
     constexpr int kJobChunks = kJobPairs / kChunkPairs, kNB = kJobPairs + kDeep;
@@ -314,16 +314,15 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     const uint32_t desc_node_stride = (uint32_t)((k - 2) * y.wt_cols * WinDesc::kWords);
     uint32_t ent_lane = lds_addr(lds + gs.slot_off) + 2u * (uint32_t)lane;   // the lane's column of the schedule table
     asm volatile("" : "+v"(ent_lane));
-    const int nparts = (NP + kJobPairs - 1) / kJobPairs, njobs = 6 * nparts;
+    const int nparts = (NP + kJobPairs - 1) / kJobPairs;
     // the wave's two jobs: lane set and first output dword
-    const int job_index[2] = {wave, njobs - 1 - wave};
-    const bool job_valid[2] = {wave < njobs, njobs - 1 - wave >= kGrpWaves};
+    const int job_part[2] = {nparts - 1 - wave / 6, nparts - 3 - wave / 6};
+    const bool job_valid[2] = {job_part[0] >= 0, job_part[1] >= 0};
     int job_set[2], job_first[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const int i = job_valid[j] ? job_index[j] : 0;
-        job_set[j] = i % 6;
-        job_first[j] = (nparts - 1 - i / 6) * kJobPairs;
+        job_set[j] = (wave + 3 * j) % 6;
+        job_first[j] = (job_valid[j] ? job_part[j] : 0) * kJobPairs;
     }
     // first lane set of row s in the schedule table
     auto first_set = [&](int s) { return s < p0 ? 36 : (s - p0) * 6; };
