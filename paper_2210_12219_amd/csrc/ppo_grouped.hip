@@ -338,10 +338,11 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t off = node * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
                              (uint32_t)((job_first[j] / kChunkPairs + c) * (WinDesc::kWords * kChunkPairs));
         const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
-        D.ctrl = dp[0];
+        // ctrl is used first: requested last, its arrival means that all four words are there
         D.below = dp[1];
         D.maskA = dp[2];
         D.maskB = dp[3];
+        D.ctrl = dp[0];
 #pragma unroll
         for (int t = 0; t < kChunkPairs; ++t) D.qv[t] = lds_load(J.qa_addr + (uint32_t)((c * kChunkPairs + t) * 4));
     };
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     J0.ent = load_ent(1, 0);
     J1.ent = load_ent(1, 1);
     job_quotients(1, 0, J0);
-    if (chunk_live(0, 0)) request_chunk(1, 0, 0, J0, DA);
+    request_chunk(1, 0, 0, J0, DA);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
@@ -491,21 +492,19 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         using C1 = std::integral_constant<int, 1>;
         using C2 = std::integral_constant<int, 2>;
         static_assert(kJobChunks == 3, "the sequence below is written for three chunks per job");
-        if (chunk_live(0, 1)) request_chunk(s, 0, 1, J0, DB);
+        request_chunk(s, 0, 1, J0, DB);
         if (chunk_live(0, 0)) run_chunk(0, C0{}, J0, B0, DA);
         // the second job's input dwords are fetched here rather than with the first job's, right after the
         // barrier, when every wave of the workgroup is waiting for LDS
-        if (job_valid[1]) {
-            job_quotients(s, 1, J1);
-            start_job(1, J1, B1);
-        }
-        if (chunk_live(0, 2)) request_chunk(s, 0, 2, J0, DA);
+        job_quotients(s, 1, J1);
+        if (job_valid[1]) start_job(1, J1, B1);
+        request_chunk(s, 0, 2, J0, DA);
         if (chunk_live(0, 1)) run_chunk(0, C1{}, J0, B0, DB);
-        if (chunk_live(1, 0)) request_chunk(s, 1, 0, J1, DB);
+        request_chunk(s, 1, 0, J1, DB);
         if (chunk_live(0, 2)) run_chunk(0, C2{}, J0, B0, DA);
-        if (chunk_live(1, 1)) request_chunk(s, 1, 1, J1, DA);
+        request_chunk(s, 1, 1, J1, DA);
         if (chunk_live(1, 0)) run_chunk(1, C0{}, J1, B1, DB);
-        if (chunk_live(1, 2)) request_chunk(s, 1, 2, J1, DB);
+        request_chunk(s, 1, 2, J1, DB);
         if (chunk_live(1, 1)) run_chunk(1, C1{}, J1, B1, DA);
         if (s + 1 <= k - 2) {
             J0.ent = load_ent(s + 1, 0);
@@ -514,7 +513,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         if (chunk_live(1, 2)) run_chunk(1, C2{}, J1, B1, DB);
         if (s + 1 <= k - 2) {
             job_quotients(s + 1, 0, J0);
-            if (chunk_live(0, 0)) request_chunk(s + 1, 0, 0, J0, DA);
+            request_chunk(s + 1, 0, 0, J0, DA);
         }
         __syncthreads();
     }
