@@ -355,6 +355,14 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + 4u * (uint32_t)(link_col(s) + job_first[j]));
     };
 
+    // addresses of job j in row s (the buffers swap roles from row to row)
+    auto job_addresses = [&](int s, int j, Job& J) {
+        const uint32_t slot_b = slot_dword(J.ent) * 4u;
+        J.out_addr = ((s & 1) ? buf1_addr : buf0_addr) + (uint32_t)(job_first[j] * 128) + slot_b;
+        J.fbase = ((s & 1) ? buf0_addr : buf1_addr) + (uint32_t)((job_first[j] - kDeep) * 128) + slot_b;
+        asm volatile("" : "+v"(J.fbase));
+    };
+
     // what the first chunk of the next row needs and does not depend on the row before it is requested
     // ahead of the barrier that ends that row
     Job J0, J1;
@@ -362,25 +370,22 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     J0.ent = load_ent(1, 0);
     J1.ent = load_ent(1, 1);
     job_quotients(1, 0, J0);
+    job_addresses(1, 0, J0);
     request_chunk(1, 0, 0, J0, DA);
     __syncthreads();
 
     for (int s = 1; s <= k - 2; ++s) {
-        const uint32_t in_addr = (s & 1) ? buf0_addr : buf1_addr, out_addr = (s & 1) ? buf1_addr : buf0_addr;
         // the next group's quotient rows are requested one row of the DP before this group ends
         if (s == k - 2 && gi + 1 < groups_per_block && group + 2u < group_end) {
             decode_group((group + 2u) >> 1, next_prefix, next_avail);
             fetch_quotients(next_prefix, next_avail, qreg);
         }
         uint32_t B0[kNB], B1[kNB];
-        // addresses of a job and the fetch of its input dwords
-        auto start_job = [&](int j, Job& J, uint32_t (&B)[kNB]) {
-            const uint32_t slot_b = slot_dword(J.ent) * 4u;
-            J.out_addr = out_addr + (uint32_t)(job_first[j] * 128) + slot_b;
-            J.fbase = in_addr + (uint32_t)((job_first[j] - kDeep) * 128) + slot_b;
-            asm volatile("" : "+v"(J.fbase));
+        // Fetch of a job's input dwords [from, to).  Chunk c reads the dwords 4c .. 4c + kDeep + 3: the first
+        // chunk's are fetched before the job starts and four more during each of its first two chunks.
+        auto fetch = [&](const Job& J, uint32_t (&B)[kNB], auto from_tag, auto to_tag) {
 #pragma unroll
-            for (int i = 0; i < kNB; ++i) B[i] = lds_load(J.fbase + (uint32_t)i * 128u);
+            for (int i = decltype(from_tag)::value; i < decltype(to_tag)::value; ++i) B[i] = lds_load(J.fbase + (uint32_t)i * 128u);
         };
 
         // chunk c of a job: B holds the job's input dwords, D the chunk's descriptors and quotients
@@ -486,33 +491,43 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         };
 #undef PPO_B
 
-        if (job_valid[0]) start_job(0, J0, B0);
-        // the six chunks in turn, each requesting what the next one needs before it starts
+        // The six chunks in turn, each requesting what the next one needs before it starts.  The requests are
+        // unconditional (a dead chunk has null descriptors and its fetches stay inside LDS), so that the waits
+        // the compiler places count exactly the requests made since.
         using C0 = std::integral_constant<int, 0>;
         using C1 = std::integral_constant<int, 1>;
         using C2 = std::integral_constant<int, 2>;
+        using F0 = std::integral_constant<int, 0>;
+        using F1 = std::integral_constant<int, kDeep + kChunkPairs>;
+        using F2 = std::integral_constant<int, kDeep + 2 * kChunkPairs>;
+        using F3 = std::integral_constant<int, kDeep + 3 * kChunkPairs>;
         static_assert(kJobChunks == 3, "the sequence below is written for three chunks per job");
+        fetch(J0, B0, F0{}, F1{});
         request_chunk(s, 0, 1, J0, DB);
+        fetch(J0, B0, F1{}, F2{});
         if (chunk_live(0, 0)) run_chunk(0, C0{}, J0, B0, DA);
-        // the second job's input dwords are fetched here rather than with the first job's, right after the
-        // barrier, when every wave of the workgroup is waiting for LDS
-        job_quotients(s, 1, J1);
-        if (job_valid[1]) start_job(1, J1, B1);
         request_chunk(s, 0, 2, J0, DA);
+        fetch(J0, B0, F2{}, F3{});
+        job_quotients(s, 1, J1);
+        job_addresses(s, 1, J1);
         if (chunk_live(0, 1)) run_chunk(0, C1{}, J0, B0, DB);
         request_chunk(s, 1, 0, J1, DB);
+        fetch(J1, B1, F0{}, F1{});
         if (chunk_live(0, 2)) run_chunk(0, C2{}, J0, B0, DA);
         request_chunk(s, 1, 1, J1, DA);
+        fetch(J1, B1, F1{}, F2{});
         if (chunk_live(1, 0)) run_chunk(1, C0{}, J1, B1, DB);
         request_chunk(s, 1, 2, J1, DB);
-        if (chunk_live(1, 1)) run_chunk(1, C1{}, J1, B1, DA);
+        fetch(J1, B1, F2{}, F3{});
         if (s + 1 <= k - 2) {
             J0.ent = load_ent(s + 1, 0);
             J1.ent = load_ent(s + 1, 1);
         }
+        if (chunk_live(1, 1)) run_chunk(1, C1{}, J1, B1, DA);
         if (chunk_live(1, 2)) run_chunk(1, C2{}, J1, B1, DB);
         if (s + 1 <= k - 2) {
             job_quotients(s + 1, 0, J0);
+            job_addresses(s + 1, 0, J0);
             request_chunk(s + 1, 0, 0, J0, DA);
         }
         __syncthreads();
