@@ -22,9 +22,12 @@
 // with the next link's quotients is folded into the write, so each row is one pass.  The last row
 // needs only D_{k-1}[L].
 //
-// Work split.  A row is 6 lane sets (one per node that can sit at that row) times 12 chunks of four
-// output dwords.  Wave w takes, in round q = 0..5, the set (w+q) mod 6 and chunk 2q + (w >= 6): every
-// wave meets every node once per row, which evens out the very different window lengths of the nodes.
+// Work split.  A row is 6 lane sets (one per node that can sit at that row); the output dwords of a lane
+// set's row are cut into parts of kJobPairs, and a job = (lane set, part).  A wave runs two jobs per row.
+// A job fetches the input dwords it needs into registers once and works through chunks of four output
+// dwords; per output dword a chain of n steps over those registers (entered by a computed jump, see
+// ppo_chain_asm.h), one masked step and, rarely, a longer tail from LDS.  Everything that decides control
+// flow comes from a descriptor table written by the precompute kernel (WinDesc in ppo_common.h).
 #include "ppo_common.h"
 #include "ppo_group_tables.h"
 
@@ -430,6 +433,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             if (ctrl[0] & WinDesc::kChunkRare) {
 #pragma unroll
                 for (int t = 0; t < kChunkPairs; ++t) {
+                    if ((ctrl[t] & (WinDesc::kDeepChain | WinDesc::kFold)) == 0u) continue;
                     if (ctrl[t] & WinDesc::kDeepChain) {
                         // the rest of a long chain walks further down the row
                         const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
@@ -460,20 +464,16 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                     if (ctrl[t] & WinDesc::kFold) {
                         // x wants entries 2n+2 .. wx-1 as well: fold the dwords n+1 .. wx/2 below the output
                         // (what else they hold lies inside x's window, except the lower half of the last one
-                        // when wx is even), then across the two halves, into x's half only
+                        // when wx is even), then across the two halves, into x's half only.  The last dword is
+                        // read whatever the count (it is dword n+1 again if there is no other), so that the
+                        // common short cases run straight through.
                         const uint32_t cnt = WinDesc::fold_dwords(ctrl[t]);
                         const uint32_t last_mask = (ctrl[t] & WinDesc::kWxEven) ? kCodeInf : 0u;
-                        uint32_t pa = cbase + below[t];   // dword n+1
-                        uint32_t tacc = bn1[t];
-                        if (cnt == 0u) {
-                            tacc = pk_max(tacc, last_mask);
-                        } else {
-                            for (uint32_t i = 1; i < cnt; ++i) {
-                                pa -= 128u;
-                                tacc = pk_min(tacc, lds_load(pa));
-                            }
-                            tacc = pk_min(tacc, pk_max(lds_load(pa - 128u), last_mask));
-                        }
+                        const uint32_t first = cbase + below[t];   // dword n+1
+                        const uint32_t last = pk_max(lds_load(first - cnt * 128u), last_mask);
+                        uint32_t tacc = cnt == 0u ? kInf2 : bn1[t];
+                        for (uint32_t i = 1; i < cnt; ++i) tacc = pk_min(tacc, lds_load(first - i * 128u));
+                        tacc = pk_min(tacc, last);
                         tacc = pk_min(tacc, align16(tacc, tacc));
                         acc[t] = pk_min(acc[t], pk_max(tacc, kCodeInf << 16));
                     }
