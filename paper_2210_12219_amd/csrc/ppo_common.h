@@ -44,9 +44,10 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 // into both halves; then one masked step offers entries 2n and 2n+1; what x wants beyond that (entries
 // 2n+2 .. wx-1) is folded separately.
 //   ctrl      bit  0      wx > 2n+2 (entries left for the separate fold)
-//             bit  1      n > kChainDepth (the chain continues below the registers)
+//             bit  1      n > depth (the chain continues below the registers), depth = chain_depth(c) for the
+//                         output's chunk c of its job: later chunks have more of the job's fetch below them
 //             bit  2      bit 0 or bit 1 is set in some descriptor of this output's chunk
-//             bits 3..7   ctrl & 0xF8 = PPO_CHAIN_ENTRY0 + 8 * (kChainDepth - min(n, kChainDepth)): the byte distance
+//             bits 3..7   ctrl & 0xF8 = PPO_CHAIN_ENTRY0 + 8 * (depth - min(n, depth)): the byte distance
 //                         the chain's computed jump adds to reach the first step to execute
 //             bits 8..14  for the separate fold: wx/2 - (n+1), the number of dwords it reads beyond dword n+1
 //             bit  15     wx is even (the lower half of the last of these dwords is not wanted)
@@ -59,7 +60,11 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //   maskB     for entry 2n+1: lower half as above; upper half +inf (y never wants it)
 constexpr int kChunkPairs = 4;
 constexpr int kChainDepth = PPO_CHAIN_DEPTH;
-static_assert(PPO_CHAIN_ENTRY0 % 8 == 0 && PPO_CHAIN_ENTRY0 + 8 * PPO_CHAIN_DEPTH <= 0xF8, "jump distance must fit bits 3..7");
+constexpr int kJobChunks = 3;                         // chunks of a job of the grouped kernel
+constexpr int kJobPairs = kJobChunks * kChunkPairs;   // its output dwords: a part of a row
+__host__ __device__ constexpr int chain_depth(int c) { return PPO_CHAIN_DEPTH + c * PPO_CHAIN_DEPTH_STEP; }
+static_assert(PPO_CHAIN_DEPTH_STEP == kChunkPairs, "a later chunk gains the dwords of the chunks before it");
+static_assert(PPO_CHAIN_ENTRY0 % 8 == 0 && PPO_CHAIN_ENTRY0 + 8 * chain_depth(kJobChunks - 1) <= 0xF8, "jump distance must fit bits 3..7");
 struct WinDesc {
     static constexpr uint32_t kFold = 0x1u, kDeepChain = 0x2u, kChunkRare = 0x4u, kJumpMask = 0xF8u, kWxEven = 0x8000u;
     static constexpr int kWords = 4;
@@ -68,15 +73,16 @@ struct WinDesc {
     __host__ __device__ static uint32_t steps(uint32_t below, uint32_t t) {
         return t + (uint32_t)kChainDepth - 1u - (uint32_t)((int32_t)below >> 7);
     }
-    // descriptor of output column jj from the two window lengths (without bit 2 of ctrl)
-    __host__ __device__ static void pack(uint32_t jj, uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& below,
+    // descriptor of output column jj, in chunk c of its job, from the two window lengths (without bit 2 of ctrl)
+    __host__ __device__ static void pack(uint32_t jj, int c, uint32_t wx, uint32_t wy, uint32_t& ctrl, uint32_t& below,
                                          uint32_t& maskA, uint32_t& maskB) {
         const uint32_t inf = kCodeInf;
         const uint32_t C = wy >= 1u ? (wx < wy - 1u ? wx : wy - 1u) : 0u;
-        const uint32_t n = C >> 1, nc = n < (uint32_t)kChainDepth ? n : (uint32_t)kChainDepth;
+        const uint32_t depth = (uint32_t)chain_depth(c);
+        const uint32_t n = C >> 1, nc = n < depth ? n : depth;
         const bool fold = wx > 2u * n + 2u;
-        ctrl = (fold ? kFold : 0u) | (n > (uint32_t)kChainDepth ? kDeepChain : 0u) |
-               ((uint32_t)PPO_CHAIN_ENTRY0 + 8u * ((uint32_t)kChainDepth - nc)) |
+        ctrl = (fold ? kFold : 0u) | (n > depth ? kDeepChain : 0u) |
+               ((uint32_t)PPO_CHAIN_ENTRY0 + 8u * (depth - nc)) |
                (fold ? (((wx >> 1) - (n + 1u)) << 8) | ((wx & 1u) ? 0u : kWxEven) : 0u) | ((wy >= 1u ? 0u : inf) << 16);
         below = ((jj % kChunkPairs) + (uint32_t)kChainDepth - 1u - n) * 128u;
         maskA = (wx > 2u * n ? 0u : inf) | ((C > 2u * n ? 0u : inf) << 16);

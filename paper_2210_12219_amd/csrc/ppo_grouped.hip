@@ -37,7 +37,6 @@ namespace ppo {
 
 constexpr int kGrpWaves = 12;
 constexpr int kGrpThreads = kGrpWaves * 64;
-constexpr int kJobPairs = 12;                        // output dwords of a job (three chunks)
 constexpr int kGrpMaxPairs = 4 * kJobPairs;          // a wave runs two jobs per row: at most four parts per lane set
 constexpr int kDeep = kChainDepth;                   // chain steps available from prefetched registers
 constexpr uint32_t kInf2 = kCodeInf | (kCodeInf << 16);
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //      the input dwords from (first - kDeep) to (first + kJobPairs - 1) of the lane's row into registers, once, and then
     //      works through its chunks of four output dwords; each chunk's descriptors and next-link quotients
     //      are requested one chunk ahead.
-    constexpr int kJobChunks = kJobPairs / kChunkPairs, kNB = kJobPairs + kDeep;
+    constexpr int kNB = kJobPairs + kDeep;
     struct ChunkIn {
         uint4 ctrl, below, maskA, maskB;   // descriptors of the four outputs, word by word
         uint32_t qv[kChunkPairs];          // quotients of the next link for the four outputs
@@ -417,15 +416,28 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             for (int t = 0; t < kChunkPairs; ++t) {
                 // y's first candidate is the upper half of the dword at the output's own index
                 uint32_t a = chain_init(PPO_B(t, 0), ctrl[t], init_mask);
-                // steps min(n, kDeep) .. 1 from registers (see ppo_chain_asm.h)
-                asm volatile(PPO_CHAIN_ASM
-                             : "+v"(a)
-                             : "s"(ctrl[t] & WinDesc::kJumpMask), "v"(PPO_B(t, 0)), "v"(PPO_B(t, 1)), "v"(PPO_B(t, 2)),
-                               "v"(PPO_B(t, 3)), "v"(PPO_B(t, 4)), "v"(PPO_B(t, 5)), "v"(PPO_B(t, 6)), "v"(PPO_B(t, 7)),
-                               "v"(PPO_B(t, 8)), "v"(PPO_B(t, 9)), "v"(PPO_B(t, 10)), "v"(PPO_B(t, 11)),
-                               "v"(PPO_B(t, 12)), "v"(PPO_B(t, 13)), "v"(PPO_B(t, 14)), "v"(PPO_B(t, 15)),
-                               "v"(PPO_B(t, 16))
-                             : "s98", "s99", "scc");
+                // steps min(n, depth) .. 1 from registers (see ppo_chain_asm.h); chunk c has depth 16 + 4c
+#define PPO_B4(t, i) "v"(PPO_B(t, i)), "v"(PPO_B(t, i + 1)), "v"(PPO_B(t, i + 2)), "v"(PPO_B(t, i + 3))
+                if constexpr (c == 0) {
+                    asm volatile(PPO_CHAIN_ASM_0
+                                 : "+v"(a)
+                                 : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
+                                   PPO_B4(t, 12), "v"(PPO_B(t, 16))
+                                 : "s98", "s99", "scc");
+                } else if constexpr (c == 1) {
+                    asm volatile(PPO_CHAIN_ASM_1
+                                 : "+v"(a)
+                                 : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
+                                   PPO_B4(t, 12), PPO_B4(t, 16), "v"(PPO_B(t, 20))
+                                 : "s98", "s99", "scc");
+                } else {
+                    asm volatile(PPO_CHAIN_ASM_2
+                                 : "+v"(a)
+                                 : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
+                                   PPO_B4(t, 12), PPO_B4(t, 16), PPO_B4(t, 20), "v"(PPO_B(t, 24))
+                                 : "s98", "s99", "scc");
+                }
+#undef PPO_B4
                 // the masked step: entry 2n (lower half of dword n) for both, entry 2n+1 (upper half of dword n+1) for x
                 acc[t] = pk_min3(a, pk_max_lower(bn[t], maskA[t]), pk_max_upper(bn1[t], maskB[t]));
             }
@@ -438,9 +450,11 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         // the rest of a long chain walks further down the row
                         const uint32_t n = WinDesc::steps((uint32_t)__builtin_amdgcn_readfirstlane(below[t]), (uint32_t)t);
                         uint32_t a = acc[t];
-                        uint32_t pa = cbase + (uint32_t)t * 128u;   // dword kDeep below the output's index
-                        uint32_t cur = PPO_B(t, kDeep);
-                        uint32_t m = n - (uint32_t)kDeep;
+                        // the deepest dword in registers, chain_depth(c) below the output's index, is the
+                        // t-th of the job's fetch
+                        uint32_t pa = J.fbase + (uint32_t)t * 128u;
+                        uint32_t cur = PPO_B(t, chain_depth(c));
+                        uint32_t m = n - (uint32_t)chain_depth(c);
                         while (m >= 4u) {
                             pa -= 512u;
                             const uint32_t b1 = lds_load(pa + 384u), b2 = lds_load(pa + 256u),

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                     w[h] = (uint32_t)v;
                 }
                 uint32_t& ctrl = row[WinDesc::offset(jj, 0)];
-                WinDesc::pack((uint32_t)jj, w[0], w[1], ctrl, row[WinDesc::offset(jj, 1)], row[WinDesc::offset(jj, 2)],
+                WinDesc::pack((uint32_t)jj, (jj % kJobPairs) / kChunkPairs, w[0], w[1], ctrl, row[WinDesc::offset(jj, 1)], row[WinDesc::offset(jj, 2)],
                               row[WinDesc::offset(jj, 3)]);
                 rare |= ctrl & (WinDesc::kFold | WinDesc::kDeepChain);
             }
