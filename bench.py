@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain elementwise kernel that reads and writes 256 MiB: the known "
+                         "traffic the HBM counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -94,6 +97,13 @@ def main():
         if events:
             events[3].record(stream)
 
+    if args.copy_probe:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)   # one dispatch: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

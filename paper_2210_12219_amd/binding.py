@@ -47,6 +47,7 @@ def load() -> C.CDLL:
         lib.ppo_prepare.argtypes = inst + [i, vp, sz, vp]
         lib.ppo_init_keys.argtypes = [vp, i, vp]
         lib.ppo_solve_range.argtypes = [i, i, i, vp, sz, u64, u64, vp, vp]
+        lib.ppo_solve_range_bounded.argtypes = [i, i, i, vp, sz, u64, u64, vp, vp, vp]
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
         _lib = lib
@@ -161,6 +162,18 @@ def ppo_solve_range(L, k, n_inst, workspace, rank_begin, rank_end, best_key, str
     assert best_key.dtype == torch.int64 and best_key.numel() == n_inst and workspace.dtype == torch.uint8
     _check(load().ppo_solve_range(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(), int(rank_begin),
                                   int(rank_end), C.c_void_p(best_key.data_ptr()), _stream(stream)))
+
+
+def ppo_solve_range_bounded(L, k, n_inst, workspace, rank_begin, rank_end, best_key, skipped_groups=None, stream=None):
+    """Stage 2 with shared prefix rows and skipped groups: same best_key as ppo_solve_range.  skipped_groups
+    (int64 tensor [n_inst], zeroed by the caller) counts the groups of 360 orderings skipped per instance."""
+    torch = _torch()
+    assert best_key.dtype == torch.int64 and best_key.numel() == n_inst and workspace.dtype == torch.uint8
+    assert skipped_groups is None or (skipped_groups.dtype == torch.int64 and skipped_groups.numel() == n_inst)
+    sk = C.c_void_p(skipped_groups.data_ptr()) if skipped_groups is not None else None
+    _check(load().ppo_solve_range_bounded(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                          int(rank_begin), int(rank_end), C.c_void_p(best_key.data_ptr()), sk,
+                                          _stream(stream)))
 
 
 def ppo_finalize(L, k, n_inst, workspace, best_key, out=None, stream=None):

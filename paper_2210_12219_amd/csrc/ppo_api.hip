@@ -7,7 +7,8 @@ namespace ppo {
 hipError_t launch_precompute(const float*, const float*, const float*, const float*, const Layout&, int, void*,
                              hipStream_t);
 hipError_t launch_init_keys(uint64_t*, int, hipStream_t);
-hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t, uint64_t*, float*, hipStream_t);
+hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t, uint64_t*, float*, bool, uint64_t*,
+                            hipStream_t);
 hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, float*, int32_t*, int32_t*,
                             hipStream_t);
 void set_enumeration_variant(int);
@@ -53,12 +54,13 @@ int run_prepare(const float* t, const float* m, int L, const float* M, const flo
 }
 
 int run_range(int L, int k, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end, uint64_t* best_key,
-              hipStream_t stream) {
+              bool shared_prefix, uint64_t* skipped_groups, hipStream_t stream) {
     const ppo::Layout y = ppo::Layout::make(L, k);
     for (int first = 0; first < n_inst; first += kInstPerLaunch) {
         const int n = (n_inst - first < kInstPerLaunch) ? n_inst - first : kInstPerLaunch;
         const unsigned char* wsi = static_cast<const unsigned char*>(ws) + (size_t)first * y.stride;
-        PPO_HIP(ppo::launch_enumerate(y, n, wsi, rank_begin, rank_end, best_key + first, nullptr, stream),
+        PPO_HIP(ppo::launch_enumerate(y, n, wsi, rank_begin, rank_end, best_key + first, nullptr, shared_prefix,
+                                      skipped_groups ? skipped_groups + first : nullptr, stream),
                 "enumerate launch");
     }
     return PPO_OK;
@@ -81,7 +83,7 @@ int run_finalize(int L, int k, int n_inst, const void* ws, const uint64_t* best_
 
 extern "C" {
 
-int ppo_version(void) { return 101; }
+int ppo_version(void) { return 102; }
 
 int ppo_set_enumeration(int variant) {
     if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC) return PPO_EINVAL;
@@ -133,7 +135,20 @@ int ppo_solve_range(int L, int k, int n_inst, const void* workspace, size_t work
     if (n_inst == 0) return PPO_OK;
     if (!best_key || !workspace) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
-    return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key,
+    return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key, false, nullptr,
+                     static_cast<hipStream_t>(stream));
+}
+
+int ppo_solve_range_bounded(int L, int k, int n_inst, const void* workspace, size_t workspace_bytes,
+                            uint64_t rank_begin, uint64_t rank_end, uint64_t* best_key, uint64_t* skipped_groups,
+                            void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!best_key || !workspace) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key, true, skipped_groups,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -162,7 +177,7 @@ int ppo_solve_ws(const float* t, const float* m, int L, const float* M, const fl
     rc = run_prepare(t, m, L, M, B, k, n_inst, workspace, s);
     if (rc) return rc;
     PPO_HIP(ppo::launch_init_keys(keys, n_inst, s), "init_keys launch");
-    rc = run_range(L, k, n_inst, workspace, 0u, ppo::factorial_u32(k), keys, s);
+    rc = run_range(L, k, n_inst, workspace, 0u, ppo::factorial_u32(k), keys, false, nullptr, s);
     if (rc) return rc;
     return run_finalize(L, k, n_inst, workspace, keys, beta_out, cuts_out, order_out, s);
 }
@@ -196,7 +211,8 @@ int ppo_eval_orderings(const float* t, const float* m, int L, const float* M, co
     PPO_HIP(hipMallocAsync(&ws, tables_bytes(y, 1), s), "hipMallocAsync");
     hipError_t e = ppo::launch_precompute(t, m, M, B, y, 1, ws, s);
     if (e == hipSuccess)
-        e = ppo::launch_enumerate(y, 1, ws, (uint32_t)rank_begin, (uint32_t)rank_end, nullptr, beta_per_ordering, s);
+        e = ppo::launch_enumerate(y, 1, ws, (uint32_t)rank_begin, (uint32_t)rank_end, nullptr, beta_per_ordering, false,
+                                  nullptr, s);
     if (e != hipSuccess) rc = hip_fail(e, "eval_orderings launch");
     hipError_t e2 = hipFreeAsync(ws, s);
     if (rc == PPO_OK && e2 != hipSuccess) rc = hip_fail(e2, "hipFreeAsync");

@@ -67,7 +67,7 @@ __device__ __forceinline__ uint32_t align16(uint32_t hi, uint32_t lo) { return _
 
 struct GroupedShape {
     int NE, NP, QD, QROW, nA, nB, nQ;
-    uint32_t buf_off, buf_dwords, q_off, slot_off, d0_off, total_bytes;  // offsets in dwords
+    uint32_t buf_off, buf_dwords, q_off, slot_off, d0_off, srow_off, total_bytes;  // offsets in dwords
     __host__ __device__ static GroupedShape make(int L, int k) {
         GroupedShape g;
         g.NE = L - k + 2;
@@ -83,7 +83,8 @@ struct GroupedShape {
         g.q_off = g.buf_off + 2u * g.buf_dwords;
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
         g.d0_off = g.slot_off + 42u * 64u / 2u;   // schedule entries are 16 bits
-        g.total_bytes = (g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4))) * 4u;
+        g.srow_off = g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4));
+        g.total_bytes = (g.srow_off + 2u * (uint32_t)(g.NP + 1) + 1u) * 4u;   // two shared rows (one dword below each), one flag
         return g;
     }
 };
@@ -114,6 +115,12 @@ __device__ __forceinline__ uint32_t chain_init(uint32_t b0, uint32_t ctrl, uint3
     asm("v_pk_maximum3_f16 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[1,1,1]" : "=v"(r) : "v"(b0), "s"(ctrl), "v"(init_mask));
     return r;
 }
+// the same with ctrl in a vector register
+__device__ __forceinline__ uint32_t chain_init_v(uint32_t b0, uint32_t ctrl, uint32_t init_mask) {
+    uint32_t r;
+    asm("v_pk_maximum3_f16 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[1,1,1]" : "=v"(r) : "v"(b0), "v"(ctrl), "v"(init_mask));
+    return r;
+}
 // packed maximum with a mask, of the lower half of v in both halves
 __device__ __forceinline__ uint32_t pk_max_lower(uint32_t v, uint32_t mask) {
     uint32_t r;
@@ -127,11 +134,20 @@ __device__ __forceinline__ uint32_t pk_max_upper(uint32_t v, uint32_t mask) {
     return r;
 }
 
-template <bool EXPORT>
+// MODE: kGrpPlain  every ordering runs all of its DP rows (what the headline figure counts);
+//       kGrpExport the same, and beta of every ordering is written out;
+//       kGrpShared the rows of the prefix, which are the same for all orderings of a group, are computed once
+//                  per group, and a group is skipped when the least entry of its last shared row exceeds the
+//                  best beta known so far (every later row's entries are at least that, so no ordering of
+//                  the group can win or tie).  Same results; not the headline's unit of work.
+enum { kGrpPlain = 0, kGrpExport = 1, kGrpShared = 2 };
+
+template <int MODE>
 __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     Layout y, const unsigned char* __restrict__ ws, uint32_t rank_begin, uint32_t rank_end, uint32_t group_begin,
     uint32_t group_end, uint32_t groups_per_block, unsigned long long* __restrict__ best_key,
-    float* __restrict__ beta_export) {
+    float* __restrict__ beta_export, unsigned long long* __restrict__ skipped_groups) {
+    constexpr bool EXPORT = MODE == kGrpExport;
     extern __shared__ __align__(16) uint32_t lds[];
     const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -252,6 +268,83 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     store_quotients(qreg);
     __syncthreads();
 
+    // column of the quotient row holding (q[e-1], q[e]) for the output dword jj of row s (e = 2jj + s)
+    auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
+    // DP row the per-ordering work starts after: row 0, or the last row of the prefix when it is shared
+    const int s_first = (MODE == kGrpShared && p0 >= 1) ? p0 - 1 : 0;
+    if (MODE == kGrpShared && p0 >= 1) {
+        // ---- the rows D_0 .. D_{p0-1} of the prefix, once for the group: wave 0, one output dword per lane,
+        //      in the same packed, sliding layout and from the same descriptors as the rows below, but with
+        //      every lane walking its own window through LDS.  Two rows of NP dwords, each with one +inf
+        //      dword below it.
+        uint32_t* const srow = lds + gs.srow_off;
+        uint32_t* const skip_flag = srow + 2 * (NP + 1);
+        const int SR = NP + 1;
+        auto prefix_node = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
+        if (wave == 0) {
+            const bool live = lane < NP;
+            if (lane < 2) srow[lane * SR] = kInf2;
+            if (live) {
+                const uint32_t d0 = lds[gs.d0_off + prefix_node(0) * y.wt_cols + lane];
+                srow[1 + lane] = p0 >= 2 ? pk_max(d0, qtab[link_col(0) + lane]) : d0;   // quotient row 0: nodes 0, 1
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            for (int s = 1; s <= p0 - 1; ++s) {
+                const uint32_t* in = srow + ((s - 1) & 1) * SR + 1;
+                uint32_t* out = srow + (s & 1) * SR + 1;
+                uint32_t res = kInf2;
+                if (live) {
+                    const uint32_t t = (uint32_t)lane % kChunkPairs;
+                    const uint32_t* dp = wt + (uint32_t)(prefix_node(s) * (k - 2) * y.wt_cols * WinDesc::kWords) + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
+                                         (uint32_t)(lane / kChunkPairs) * (WinDesc::kWords * kChunkPairs) + t;
+                    const uint32_t ctrl = dp[0], below = dp[kChunkPairs], maskA = dp[2 * kChunkPairs], maskB = dp[3 * kChunkPairs];
+                    const uint32_t n = WinDesc::steps(below, t);
+                    const uint32_t* own = in + lane;   // the input dword at the output's own index
+                    uint32_t acc = chain_init_v(own[0], ctrl, init_mask);
+                    for (uint32_t i = 1; i <= n; ++i) acc = chain_step(acc, own[-(int)(i - 1)], own[-(int)i]);
+                    acc = pk_min3(acc, pk_max_lower(own[-(int)n], maskA), pk_max_upper(own[-(int)(n + 1)], maskB));
+                    if (ctrl & WinDesc::kFold) {
+                        const uint32_t cnt = WinDesc::fold_dwords(ctrl);
+                        uint32_t tacc = kInf2;
+                        for (uint32_t i = 0; i < cnt; ++i) tacc = pk_min(tacc, own[-(int)(n + 1 + i)]);
+                        tacc = pk_min(tacc, pk_max(own[-(int)(n + 1 + cnt)], (ctrl & WinDesc::kWxEven) ? kCodeInf : 0u));
+                        tacc = pk_min(tacc, align16(tacc, tacc));
+                        acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
+                    }
+                    // the last shared row stays without a link: each ordering adds its own
+                    res = s < p0 - 1 ? pk_max(acc, qtab[s * QROW + link_col(s) + lane]) : acc;
+                }
+                if (live) out[lane] = res;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            // least entry of the last shared row: a lower bound on beta of every ordering of the group
+            uint32_t lb = kCodeInf;
+            if (live) {
+                const uint32_t v = srow[(s_first & 1) * SR + 1 + lane];
+                lb = (v & 0xFFFFu) < (v >> 16) ? (v & 0xFFFFu) : (v >> 16);
+            }
+            for (int off = 32; off >= 1; off >>= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)lb, off, 64);
+                lb = o < lb ? o : lb;
+            }
+            const uint32_t lb_bits = lb >= kCodeInf ? kInfBits : __float_as_uint(dec[lb - kCodeZero]);
+            const uint32_t known = (uint32_t)(__atomic_load_n(best_key + inst, __ATOMIC_RELAXED) >> 32);
+            if (lane == 0) {
+                *skip_flag = lb_bits > known ? 1u : 0u;
+                if (lb_bits > known && skipped_groups) atomicAdd(skipped_groups + inst, 1ull);
+            }
+        }
+        __syncthreads();
+        if (*skip_flag) {
+            if (gi + 1 < groups_per_block && group + 2u < group_end) {
+                decode_group((group + 2u) >> 1, next_prefix, next_avail);
+                fetch_quotients(next_prefix, next_avail, qreg);
+            }
+            __syncthreads();   // the flag and the quotient rows are rewritten by the next group
+            continue;
+        }
+    }
+
     // quotient row used when row s is written (the link between the nodes of rows s and s+1), from the
     // lane's schedule entry
     auto link_row = [&](int s, uint32_t ent) -> int {
@@ -259,8 +352,6 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         if (s + 1 == p0) return nA + (int)((ent >> 13) & 7u);
         return nA + nB + (int)((ent >> 9) & 15u);
     };
-    // column of the quotient row holding (q[e-1], q[e]) for the output dword jj of row s (e = 2jj + s)
-    auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
     auto slot_dword = [&](uint32_t ent) -> uint32_t {
         return __umul24((ent >> 5) & 15u, (uint32_t)(NP * 32)) + (ent & 31u);
     };
@@ -273,25 +364,30 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         last_lo = (low + vzero)[rest_node(wave) * (L + 1) + L];
     }
 
-    // ---- row 0: g_1[i] = max(D_0[i], q_{pi_0,pi_1}[i-1]) at index i, D_0[i] = 0 if layers [0,i) fit node pi_0
+    // ---- row 0: g_1[i] = max(D_0[i], q_{pi_0,pi_1}[i-1]) at index i, D_0[i] = 0 if layers [0,i) fit node pi_0.
+    //      With a shared prefix: the same for its last row s_first, from the row computed above.
     {
         const int c = wave % 6, half = wave / 6;
-        const int node = row_node(0, c);
         const int set = p0 > 0 ? 36 + c : c;
         const uint32_t ent = slotTab[set * 64 + lane];
-        uint32_t* out = buf0 + slot_dword(ent);
-        const uint32_t* qrow = qtab + link_row(0, ent) * QROW + link_col(0);
-        const uint32_t* d0row = lds + gs.d0_off + node * y.wt_cols;   // the initial row of the node
+        uint32_t* out = ((s_first & 1) ? buf1 : buf0) + slot_dword(ent);
+        const uint32_t* qrow = qtab + link_row(s_first, ent) * QROW + link_col(s_first);
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
-        int jj = j0;
-        for (; jj + 4 <= j1; jj += 4) {
-            const uint32_t e0 = d0row[jj], e1 = d0row[jj + 1], e2 = d0row[jj + 2], e3 = d0row[jj + 3];
-            out[jj * 32] = pk_max(e0, qrow[jj]);
-            out[(jj + 1) * 32] = pk_max(e1, qrow[jj + 1]);
-            out[(jj + 2) * 32] = pk_max(e2, qrow[jj + 2]);
-            out[(jj + 3) * 32] = pk_max(e3, qrow[jj + 3]);
+        if (MODE == kGrpShared && p0 >= 1) {
+            const uint32_t* fin = lds + gs.srow_off + (s_first & 1) * (NP + 1) + 1;
+            for (int jj = j0; jj < j1; ++jj) out[jj * 32] = pk_max(fin[jj], qrow[jj]);
+        } else {
+            const uint32_t* d0row = lds + gs.d0_off + row_node(0, c) * y.wt_cols;   // the initial row of the node
+            int jj = j0;
+            for (; jj + 4 <= j1; jj += 4) {
+                const uint32_t e0 = d0row[jj], e1 = d0row[jj + 1], e2 = d0row[jj + 2], e3 = d0row[jj + 3];
+                out[jj * 32] = pk_max(e0, qrow[jj]);
+                out[(jj + 1) * 32] = pk_max(e1, qrow[jj + 1]);
+                out[(jj + 2) * 32] = pk_max(e2, qrow[jj + 2]);
+                out[(jj + 3) * 32] = pk_max(e3, qrow[jj + 3]);
+            }
+            for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
         }
-        for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
     }
 
     // ---- rows 1 .. k-2.  The output dwords of a lane set's row are cut into parts of kJobPairs dwords; a job
@@ -369,14 +465,14 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     // ahead of the barrier that ends that row
     Job J0, J1;
     ChunkIn DA, DB;
-    J0.ent = load_ent(1, 0);
-    J1.ent = load_ent(1, 1);
-    job_quotients(1, 0, J0);
-    job_addresses(1, 0, J0);
-    request_chunk(1, 0, 0, J0, DA);
+    J0.ent = load_ent(s_first + 1, 0);
+    J1.ent = load_ent(s_first + 1, 1);
+    job_quotients(s_first + 1, 0, J0);
+    job_addresses(s_first + 1, 0, J0);
+    request_chunk(s_first + 1, 0, 0, J0, DA);
     __syncthreads();
 
-    for (int s = 1; s <= k - 2; ++s) {
+    for (int s = s_first + 1; s <= k - 2; ++s) {
         // the next group's quotient rows are requested one row of the DP before this group ends
         if (s == k - 2 && gi + 1 < groups_per_block && group + 2u < group_end) {
             decode_group((group + 2u) >> 1, next_prefix, next_avail);
@@ -593,8 +689,25 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     }
 }
 
+template <int MODE>
+static hipError_t launch_mode(const dim3& grid, const GroupedShape& gs, hipStream_t stream, const Layout& y, const void* ws,
+                              uint32_t rank_begin, uint32_t rank_end, uint32_t gbeg, uint32_t gend, uint32_t gpb,
+                              uint64_t* best_key, float* beta_export, uint64_t* skipped_groups) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<MODE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(enumerate_grouped_kernel<MODE>, grid, dim3(kGrpThreads), gs.total_bytes, stream, y,
+                       static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,
+                       reinterpret_cast<unsigned long long*>(best_key), beta_export,
+                       reinterpret_cast<unsigned long long*>(skipped_groups));
+    return hipGetLastError();
+}
+
+// shared_prefix: compute the rows of a group's prefix once and skip groups that cannot win (see kGrpShared);
+// skipped_groups (device, one counter per instance, may be null) is incremented per skipped group
 hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin,
-                                    uint32_t rank_end, uint64_t* best_key, float* beta_export, hipStream_t stream) {
+                                    uint32_t rank_end, uint64_t* best_key, float* beta_export, bool shared_prefix,
+                                    uint64_t* skipped_groups, hipStream_t stream) {
     if (rank_end <= rank_begin || n_inst == 0) return hipSuccess;
     const GroupedShape gs = GroupedShape::make(y.L, y.k);
     const uint32_t gbeg = 2u * (rank_begin / 720u), gend = 2u * ((rank_end + 719u) / 720u);
@@ -602,24 +715,12 @@ hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws,
     uint32_t gpb = 8;
     while (gpb > 1 && (uint64_t)((gend - gbeg) / 2 / gpb) * 2u * (uint64_t)n_inst < 4096u) gpb >>= 1;
     const uint32_t pairs = (gend - gbeg) / 2;
-    const dim3 grid(2u * ((pairs + gpb - 1) / gpb), n_inst), block(kGrpThreads);
-    hipError_t e;
-    if (beta_export) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(enumerate_grouped_kernel<true>, grid, block, gs.total_bytes, stream, y,
-                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,
-                           reinterpret_cast<unsigned long long*>(best_key), beta_export);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(enumerate_grouped_kernel<false>, grid, block, gs.total_bytes, stream, y,
-                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,
-                           reinterpret_cast<unsigned long long*>(best_key), beta_export);
-    }
-    return hipGetLastError();
+    const dim3 grid(2u * ((pairs + gpb - 1) / gpb), n_inst);
+    if (beta_export)
+        return launch_mode<kGrpExport>(grid, gs, stream, y, ws, rank_begin, rank_end, gbeg, gend, gpb, best_key, beta_export, nullptr);
+    if (shared_prefix)
+        return launch_mode<kGrpShared>(grid, gs, stream, y, ws, rank_begin, rank_end, gbeg, gend, gpb, best_key, nullptr, skipped_groups);
+    return launch_mode<kGrpPlain>(grid, gs, stream, y, ws, rank_begin, rank_end, gbeg, gend, gpb, best_key, nullptr, nullptr);
 }
 
 }  // namespace ppo

@@ -307,7 +307,8 @@ hipError_t launch_init_keys(uint64_t* keys, int n_inst, hipStream_t stream) {
 
 bool grouped_supported(int L, int k);
 hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin,
-                                    uint32_t rank_end, uint64_t* best_key, float* beta_export, hipStream_t stream);
+                                    uint32_t rank_end, uint64_t* best_key, float* beta_export, bool shared_prefix,
+                                    uint64_t* skipped_groups, hipStream_t stream);
 
 // 0: pick per shape (grouped kernel when k >= 6 and the rows fit LDS), 1: always the generic kernel
 static int g_enumeration_variant = 0;
@@ -315,12 +316,16 @@ void set_enumeration_variant(int v) { g_enumeration_variant = v; }
 
 size_t enumerate_lds_bytes(const Layout& y) { return (size_t)y.dec_off + (size_t)(y.L + 1) * kEnumThreads * 2; }
 
+// shared_prefix asks for the grouped kernel's shared-prefix, bounded mode where that kernel applies; elsewhere
+// every ordering is evaluated in full
 hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
-                            uint64_t* best_key, float* beta_export, hipStream_t stream) {
+                            uint64_t* best_key, float* beta_export, bool shared_prefix, uint64_t* skipped_groups,
+                            hipStream_t stream) {
     const uint32_t span = rank_end - rank_begin;
     if (span == 0 || n_inst == 0) return hipSuccess;
     if (g_enumeration_variant == 0 && grouped_supported(y.L, y.k))
-        return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, stream);
+        return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, shared_prefix,
+                                        skipped_groups, stream);
     const size_t lds = enumerate_lds_bytes(y);
     uint32_t gx = (span + kEnumThreads - 1) / kEnumThreads;
     if (gx > 4096u) gx = 4096u;

@@ -27,7 +27,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"ppo_solve", "ppo_solve_ws", "ppo_prepare", "ppo_solve_range", "ppo_finalize", "ppo_eval_orderings", "ppo_init_keys",
+    assert {"ppo_solve", "ppo_solve_ws", "ppo_prepare", "ppo_solve_range", "ppo_solve_range_bounded", "ppo_finalize", "ppo_eval_orderings", "ppo_init_keys",
             "ppo_workspace_bytes", "ppo_strerror", "ppo_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -77,6 +77,8 @@ def test_bad_arguments_are_refused_without_a_gpu(lib):
     assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 5, 4, p, s) == binding.PPO_EINVAL
     assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 0, 7, p, s) == binding.PPO_EINVAL
     assert lib.ppo_solve_range(4, 3, 1, p, 16, 0, 6, p, s) == binding.PPO_ENOSPC
+    assert lib.ppo_solve_range_bounded(4, 3, 1, p, 1 << 20, 5, 4, p, None, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range_bounded(4, 3, 1, p, 16, 0, 6, p, None, s) == binding.PPO_ENOSPC
     assert lib.ppo_prepare(p, p, 4, p, p, 3, 1, p, 16, s) == binding.PPO_ENOSPC
     assert lib.ppo_prepare(p, null, 4, p, p, 3, 1, p, 1 << 20, s) == binding.PPO_EINVAL
     assert lib.ppo_eval_orderings(p, p, 4, p, p, 3, 0, 7, p, s) == binding.PPO_EINVAL
