@@ -84,7 +84,7 @@ struct GroupedShape {
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
         g.d0_off = g.slot_off + 42u * 64u / 2u;   // schedule entries are 16 bits
         g.srow_off = g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4));
-        g.total_bytes = (g.srow_off + 2u * (uint32_t)(g.NP + 1) + 1u) * 4u;   // two shared rows (one dword below each), one flag
+        g.total_bytes = (g.srow_off + 3u * (uint32_t)g.NP + 2u) * 4u;   // two shared rows, their linked form (one dword below it), one flag
         return g;
     }
 };
@@ -248,6 +248,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     };
     uint32_t qreg[kQRows * kQCols];
     uint64_t next_prefix = 0, next_avail = 0;
+    uint64_t shared_prefix_done = 0;   // prefix whose shared rows are in LDS (kGrpShared)
     if (group_first < group_end) {
         decode_group(group_first >> 1, next_prefix, next_avail);
         fetch_quotients(next_prefix, next_avail, qreg);
@@ -275,31 +276,36 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     if (MODE == kGrpShared && p0 >= 1) {
         // ---- the rows D_0 .. D_{p0-1} of the prefix, once for the group: wave 0, one output dword per lane,
         //      in the same packed, sliding layout and from the same descriptors as the rows below, but with
-        //      every lane walking its own window through LDS.  Two rows of NP dwords, each with one +inf
-        //      dword below it.
+        //      every lane walking its own window through LDS.  Rows D_s alternate between two buffers; the
+        //      input of row s is a third buffer holding max(D_{s-1}, quotients of the link s-1 -> s), with one
+        //      +inf dword below it.  When only the last node of the prefix differs from the previous group's,
+        //      rows 0 .. p0-2 are still there and only the last row is computed.
         uint32_t* const srow = lds + gs.srow_off;
-        uint32_t* const skip_flag = srow + 2 * (NP + 1);
-        const int SR = NP + 1;
+        uint32_t* const linked = srow + 2 * NP + 1;
+        uint32_t* const skip_flag = srow + 3 * NP + 1;
         auto prefix_node = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
         if (wave == 0) {
+            const uint32_t known = (uint32_t)(__atomic_load_n(best_key + inst, __ATOMIC_RELAXED) >> 32);
             const bool live = lane < NP;
-            if (lane < 2) srow[lane * SR] = kInf2;
-            if (live) {
-                const uint32_t d0 = lds[gs.d0_off + prefix_node(0) * y.wt_cols + lane];
-                srow[1 + lane] = p0 >= 2 ? pk_max(d0, qtab[link_col(0) + lane]) : d0;   // quotient row 0: nodes 0, 1
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            for (int s = 1; s <= p0 - 1; ++s) {
-                const uint32_t* in = srow + ((s - 1) & 1) * SR + 1;
-                uint32_t* out = srow + (s & 1) * SR + 1;
+            const uint64_t parent_mask = (1ull << (4 * (p0 - 1))) - 1ull;
+            const bool same_parent = p0 >= 2 && gi > 0 && ((prefix ^ shared_prefix_done) & parent_mask) == 0ull;
+            if (lane == 0) linked[-1] = kInf2;
+            if (!same_parent && live) srow[lane] = lds[gs.d0_off + prefix_node(0) * y.wt_cols + lane];
+            for (int s = same_parent ? p0 - 1 : 1; s <= p0 - 1; ++s) {
+                const uint32_t* prev = srow + ((s - 1) & 1) * NP;
+                uint32_t* out = srow + (s & 1) * NP;
                 uint32_t res = kInf2;
+                // quotient row s-1: the link between prefix nodes s-1 and s
+                if (live) linked[lane] = pk_max(prev[lane], qtab[(s - 1) * QROW + link_col(s - 1) + lane]);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 if (live) {
                     const uint32_t t = (uint32_t)lane % kChunkPairs;
-                    const uint32_t* dp = wt + (uint32_t)(prefix_node(s) * (k - 2) * y.wt_cols * WinDesc::kWords) + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
+                    const uint32_t* dp = wt + (uint32_t)(prefix_node(s) * (k - 2) * y.wt_cols * WinDesc::kWords) +
+                                         (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
                                          (uint32_t)(lane / kChunkPairs) * (WinDesc::kWords * kChunkPairs) + t;
                     const uint32_t ctrl = dp[0], below = dp[kChunkPairs], maskA = dp[2 * kChunkPairs], maskB = dp[3 * kChunkPairs];
                     const uint32_t n = WinDesc::steps(below, t);
-                    const uint32_t* own = in + lane;   // the input dword at the output's own index
+                    const uint32_t* own = linked + lane;   // the input dword at the output's own index
                     uint32_t acc = chain_init_v(own[0], ctrl, init_mask);
                     for (uint32_t i = 1; i <= n; ++i) acc = chain_step(acc, own[-(int)(i - 1)], own[-(int)i]);
                     acc = pk_min3(acc, pk_max_lower(own[-(int)n], maskA), pk_max_upper(own[-(int)(n + 1)], maskB));
@@ -311,8 +317,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         tacc = pk_min(tacc, align16(tacc, tacc));
                         acc = pk_min(acc, pk_max(tacc, kCodeInf << 16));
                     }
-                    // the last shared row stays without a link: each ordering adds its own
-                    res = s < p0 - 1 ? pk_max(acc, qtab[s * QROW + link_col(s) + lane]) : acc;
+                    res = acc;
                 }
                 if (live) out[lane] = res;
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -320,7 +325,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             // least entry of the last shared row: a lower bound on beta of every ordering of the group
             uint32_t lb = kCodeInf;
             if (live) {
-                const uint32_t v = srow[(s_first & 1) * SR + 1 + lane];
+                const uint32_t v = srow[(s_first & 1) * NP + lane];
                 lb = (v & 0xFFFFu) < (v >> 16) ? (v & 0xFFFFu) : (v >> 16);
             }
             for (int off = 32; off >= 1; off >>= 1) {
@@ -328,12 +333,12 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 lb = o < lb ? o : lb;
             }
             const uint32_t lb_bits = lb >= kCodeInf ? kInfBits : __float_as_uint(dec[lb - kCodeZero]);
-            const uint32_t known = (uint32_t)(__atomic_load_n(best_key + inst, __ATOMIC_RELAXED) >> 32);
             if (lane == 0) {
                 *skip_flag = lb_bits > known ? 1u : 0u;
                 if (lb_bits > known && skipped_groups) atomicAdd(skipped_groups + inst, 1ull);
             }
         }
+        shared_prefix_done = prefix;
         __syncthreads();
         if (*skip_flag) {
             if (gi + 1 < groups_per_block && group + 2u < group_end) {
@@ -374,7 +379,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t* qrow = qtab + link_row(s_first, ent) * QROW + link_col(s_first);
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
         if (MODE == kGrpShared && p0 >= 1) {
-            const uint32_t* fin = lds + gs.srow_off + (s_first & 1) * (NP + 1) + 1;
+            const uint32_t* fin = lds + gs.srow_off + (s_first & 1) * NP;
             for (int jj = j0; jj < j1; ++jj) out[jj * 32] = pk_max(fin[jj], qrow[jj]);
         } else {
             const uint32_t* d0row = lds + gs.d0_off + row_node(0, c) * y.wt_cols;   // the initial row of the node
