@@ -52,6 +52,13 @@ def algorithmic_ops_per_ordering(w):
     return cand, maxops
 
 
+# HBM bytes per launch of the enumeration kernel at the headline workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE) of `bench.py --steps 1 --warmup 0 --no-cpu-baseline --copy-probe`, each counter
+# scaled by what it reads for the probe's 256 MiB (see profiles/).  Keyed by ppo_version(): a library whose
+# kernel has changed since reports no traffic.
+MEASURED_TRAFFIC_BYTES = {("headline", 102): 4.854e7}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,7 +146,8 @@ def main():
                    "orderings_per_step": n * kf},
         "stage_ms": {"prepare": prep_ms, "enumerate": enum_ms, "finalize": fin_ms},
         "roofline": {"bound": "alu", "kernel": "enumerate", "achieved": achieved, "peak": VALU_PEAK_TOPS,
-                     "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_TOPS, "traffic": None,
+                     "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_TOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, ppo.load().ppo_version())),
                      "ops_per_ordering": {"min": cand, "max": maxops},
                      "kernel_ms": enum_ms},
     }
