@@ -412,6 +412,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         uint32_t fbase;      // LDS byte address of the first input dword fetched
         uint32_t out_addr;   // LDS byte address of the first output dword
         uint32_t qa_addr;    // LDS byte address of the quotient dword of the first output
+        uint32_t desc_base;  // dword offset of the job's first chunk in the descriptor table (wave-uniform)
     };
     const uint32_t buf0_addr = lds_addr(buf0), buf1_addr = lds_addr(buf1), qtab_addr = lds_addr(qtab);
     const uint32_t desc_node_stride = (uint32_t)((k - 2) * y.wt_cols * WinDesc::kWords);
@@ -436,11 +437,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     // but they are fetched with vector loads on purpose: scalar loads complete under the same counter as LDS
     // reads, out of order, so one in flight would make every wait for an LDS result a wait for everything.
     auto chunk_live = [&](int j, int c) { return job_valid[j] && job_first[j] + c * kChunkPairs < NP; };
-    auto request_chunk = [&](int s, int j, int c, const Job& J, ChunkIn& D) {
-        const uint32_t node = (uint32_t)row_node(s, job_set[j]);
-        const uint32_t off = node * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
-                             (uint32_t)((job_first[j] / kChunkPairs + c) * (WinDesc::kWords * kChunkPairs));
-        const uint4* dp = reinterpret_cast<const uint4*>(wt + off) + vzero;
+    auto request_chunk = [&](int c, const Job& J, ChunkIn& D) {
+        const uint4* dp = reinterpret_cast<const uint4*>(wt + J.desc_base + (uint32_t)(c * (WinDesc::kWords * kChunkPairs))) + vzero;
         // ctrl is used first: requested last, its arrival means that all four words are there
         D.below = dp[1];
         D.maskA = dp[2];
@@ -449,8 +447,11 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 #pragma unroll
         for (int t = 0; t < kChunkPairs; ++t) D.qv[t] = lds_load(J.qa_addr + (uint32_t)((c * kChunkPairs + t) * 4));
     };
-    // the parts of a job's addresses that do not depend on the buffers' roles: from the schedule entry
+    // the parts of a job's addresses that do not depend on the buffers' roles: descriptors of (node, row, part),
+    // and the quotient row from the schedule entry
     auto job_quotients = [&](int s, int j, Job& J) {
+        J.desc_base = (uint32_t)row_node(s, job_set[j]) * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
+                      (uint32_t)((job_first[j] / kChunkPairs) * (WinDesc::kWords * kChunkPairs));
         // row of the quotient table = a base + a field of the schedule entry
         const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
         const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     J1.ent = load_ent(s_first + 1, 1);
     job_quotients(s_first + 1, 0, J0);
     job_addresses(s_first + 1, 0, J0);
-    request_chunk(s_first + 1, 0, 0, J0, DA);
+    request_chunk(0, J0, DA);
     __syncthreads();
 
     for (int s = s_first + 1; s <= k - 2; ++s) {
@@ -618,21 +619,21 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         using F3 = std::integral_constant<int, kDeep + 3 * kChunkPairs>;
         static_assert(kJobChunks == 3, "the sequence below is written for three chunks per job");
         fetch(J0, B0, F0{}, F1{});
-        request_chunk(s, 0, 1, J0, DB);
+        request_chunk(1, J0, DB);
         fetch(J0, B0, F1{}, F2{});
         if (chunk_live(0, 0)) run_chunk(0, C0{}, J0, B0, DA);
-        request_chunk(s, 0, 2, J0, DA);
+        request_chunk(2, J0, DA);
         fetch(J0, B0, F2{}, F3{});
         job_quotients(s, 1, J1);
         job_addresses(s, 1, J1);
         if (chunk_live(0, 1)) run_chunk(0, C1{}, J0, B0, DB);
-        request_chunk(s, 1, 0, J1, DB);
+        request_chunk(0, J1, DB);
         fetch(J1, B1, F0{}, F1{});
         if (chunk_live(0, 2)) run_chunk(0, C2{}, J0, B0, DA);
-        request_chunk(s, 1, 1, J1, DA);
+        request_chunk(1, J1, DA);
         fetch(J1, B1, F1{}, F2{});
         if (chunk_live(1, 0)) run_chunk(1, C0{}, J1, B1, DB);
-        request_chunk(s, 1, 2, J1, DB);
+        request_chunk(2, J1, DB);
         fetch(J1, B1, F2{}, F3{});
         if (s + 1 <= k - 2) {
             J0.ent = load_ent(s + 1, 0);
@@ -643,7 +644,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         if (s + 1 <= k - 2) {
             job_quotients(s + 1, 0, J0);
             job_addresses(s + 1, 0, J0);
-            request_chunk(s + 1, 0, 0, J0, DA);
+            request_chunk(0, J0, DA);
         }
         __syncthreads();
     }
