@@ -212,3 +212,16 @@ def test_division_is_correctly_rounded_on_a_million_pairs(ppo):
     beta, cuts, order = gpu_solve(ppo, w)
     assert np.array_equal(bits(beta), bits(t0 / b))
     assert (cuts == 1).all() and (order == np.array([0, 1])).all()
+
+
+def test_grouped_kernel_row_lengths(ppo):
+    """The grouped kernel cuts a row of NP = ceil((L-k+2)/2) output dwords into one to four parts of three
+    chunks: sweep NP from 1 to its maximum of 48 (and one past it, which goes to the generic kernel), with
+    k = 6, 7 and 9, against the subset DP."""
+    cases = [(6, 6), (6, 7), (6, 9), (6, 13), (6, 27), (6, 28), (6, 29), (6, 51), (6, 52), (6, 53), (6, 75),
+             (6, 76), (6, 77), (6, 99), (6, 100), (6, 101), (7, 7), (7, 30), (7, 54), (7, 78), (7, 101), (7, 102),
+             (9, 9), (9, 20), (9, 57), (9, 103)]
+    for n, (k, L) in enumerate(cases):
+        w = W.random_instances(7000 + n, 3 if k == 9 else 10, L, k, capacity_factor=1.15 + 0.1 * (n % 4),
+                               quantised=bool(n % 3 == 0))
+        assert_same(gpu_solve(ppo, w), O.subset_dp(w.t, w.m, w.M, w.B), f"grouped row lengths k={k} L={L}")
