@@ -100,3 +100,15 @@ def test_bounded_small_and_ragged(ppo):
         got2, keys2, _ = solve_bounded(ppo, w, ranges=pieces)
         assert_same(got2, ref, f"bounded, ragged ranges L={L} k={k}")
         assert np.array_equal(keys2, keys)
+
+
+def test_bounded_row_lengths(ppo):
+    """Row lengths from one dword to the maximum, prefixes of one to three nodes."""
+    cases = [(7, 7), (7, 8), (7, 31), (7, 55), (7, 79), (7, 101), (7, 102), (8, 8), (8, 33), (8, 80), (8, 102),
+             (9, 9), (9, 58), (9, 103)]
+    for n, (k, L) in enumerate(cases):
+        w = W.random_instances(8000 + n, 3 if k == 9 else 8, L, k, capacity_factor=1.1 + 0.1 * (n % 4),
+                               quantised=bool(n % 2))
+        got, keys, _ = solve_bounded(ppo, w)
+        assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), f"bounded row lengths k={k} L={L}")
+        assert np.array_equal(keys, solve_full_keys(ppo, w)), (k, L)
