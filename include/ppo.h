@@ -126,6 +126,17 @@ int ppo_solve_range_bounded(int L, int k, int n_inst, const void *workspace, siz
                             uint64_t rank_begin, uint64_t rank_end, uint64_t *best_key, uint64_t *skipped_groups,
                             void *stream);
 
+/* Stage 2 by another route: dynamic programming over node subsets.  The
+ * bottleneck of Eq. 2 is a maximum over links, so what is still to be paid after a cut depends only on
+ * the node before the cut, the cut and the set of nodes not yet used; k 2^(k-1) rows of L+1 entries
+ * replace k! DPs.  Sets best_key [n_inst] to exactly what ppo_solve_range leaves after the whole range
+ * [0, k!): the optimum's beta and, among the orderings that reach it, the lowest rank (found position by
+ * position as the smallest node that can still reach the optimum).  best_key is overwritten, not folded.
+ * Allocates (k 2^k)(L+2) 16-bit entries of scratch per instance, for at most 1 GiB of instances at a
+ * time, with the stream-ordered allocator. */
+int ppo_solve_subsets(int L, int k, int n_inst, const void *workspace, size_t workspace_bytes, uint64_t *best_key,
+                      void *stream);
+
 /* Stage 3 — turn best_key into (beta, cuts, order): decodes the winning rank, reruns its DP keeping
  * every row, and walks back with the cut rule stated at the top.  A key whose beta is +inf (or
  * PPO_KEY_NONE) gives beta = +inf, cuts = order = -1. */

@@ -48,6 +48,7 @@ def load() -> C.CDLL:
         lib.ppo_init_keys.argtypes = [vp, i, vp]
         lib.ppo_solve_range.argtypes = [i, i, i, vp, sz, u64, u64, vp, vp]
         lib.ppo_solve_range_bounded.argtypes = [i, i, i, vp, sz, u64, u64, vp, vp, vp]
+        lib.ppo_solve_subsets.argtypes = [i, i, i, vp, sz, vp, vp]
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
         _lib = lib
@@ -174,6 +175,14 @@ def ppo_solve_range_bounded(L, k, n_inst, workspace, rank_begin, rank_end, best_
     _check(load().ppo_solve_range_bounded(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                           int(rank_begin), int(rank_end), C.c_void_p(best_key.data_ptr()), sk,
                                           _stream(stream)))
+
+
+def ppo_solve_subsets(L, k, n_inst, workspace, best_key, stream=None):
+    """Stage 2 by dynamic programming over node subsets: best_key as after ppo_solve_range over [0, k!)."""
+    torch = _torch()
+    assert best_key.dtype == torch.int64 and best_key.numel() == n_inst and workspace.dtype == torch.uint8
+    _check(load().ppo_solve_subsets(L, k, n_inst, C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                    C.c_void_p(best_key.data_ptr()), _stream(stream)))
 
 
 def ppo_finalize(L, k, n_inst, workspace, best_key, out=None, stream=None):

@@ -12,6 +12,8 @@ hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t,
 hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, float*, int32_t*, int32_t*,
                             hipStream_t);
 void set_enumeration_variant(int);
+size_t subset_scratch_bytes_per_instance(int L, int k);
+hipError_t launch_subset(const Layout&, int, const void*, void*, uint64_t*, hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -83,7 +85,7 @@ int run_finalize(int L, int k, int n_inst, const void* ws, const uint64_t* best_
 
 extern "C" {
 
-int ppo_version(void) { return 102; }
+int ppo_version(void) { return 103; }
 
 int ppo_set_enumeration(int variant) {
     if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC) return PPO_EINVAL;
@@ -150,6 +152,34 @@ int ppo_solve_range_bounded(int L, int k, int n_inst, const void* workspace, siz
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key, true, skipped_groups,
                      static_cast<hipStream_t>(stream));
+}
+
+int ppo_solve_subsets(int L, int k, int n_inst, const void* workspace, size_t workspace_bytes, uint64_t* best_key,
+                      void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!best_key || !workspace) return PPO_EINVAL;
+    if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const ppo::Layout y = ppo::Layout::make(L, k);
+    // rows of the subset DP: scratch for as many instances at a time as fit in 1 GiB
+    const size_t per = ppo::subset_scratch_bytes_per_instance(L, k);
+    size_t batch = ((size_t)1 << 30) / per;
+    if (batch < 1) batch = 1;
+    if (batch > (size_t)n_inst) batch = (size_t)n_inst;
+    void* scratch = nullptr;
+    PPO_HIP(hipMallocAsync(&scratch, per * batch, s), "hipMallocAsync (subset DP rows)");
+    hipError_t e = hipSuccess;
+    for (size_t first = 0; first < (size_t)n_inst && e == hipSuccess; first += batch) {
+        const int n = (int)(((size_t)n_inst - first < batch) ? (size_t)n_inst - first : batch);
+        e = ppo::launch_subset(y, n, static_cast<const unsigned char*>(workspace) + first * y.stride, scratch,
+                               best_key + first, s);
+    }
+    const hipError_t e2 = hipFreeAsync(scratch, s);
+    PPO_HIP(e, "subset DP launch");
+    PPO_HIP(e2, "hipFreeAsync (subset DP rows)");
+    return PPO_OK;
 }
 
 int ppo_finalize(int L, int k, int n_inst, const void* workspace, size_t workspace_bytes, const uint64_t* best_key,

@@ -27,7 +27,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"ppo_solve", "ppo_solve_ws", "ppo_prepare", "ppo_solve_range", "ppo_solve_range_bounded", "ppo_finalize", "ppo_eval_orderings", "ppo_init_keys",
+    assert {"ppo_solve", "ppo_solve_ws", "ppo_prepare", "ppo_solve_range", "ppo_solve_range_bounded", "ppo_solve_subsets", "ppo_finalize", "ppo_eval_orderings", "ppo_init_keys",
             "ppo_workspace_bytes", "ppo_strerror", "ppo_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
