@@ -229,8 +229,7 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
                                                        float* __restrict__ beta_out, int32_t* __restrict__ cuts_out,
                                                        int32_t* __restrict__ order_out) {
     __shared__ uint16_t rows[PPO_MAX_K][PPO_MAX_L + 1];
-    const int L = y.L, k = y.k, inst = blockIdx.x;
-    if (threadIdx.x != 0) return;
+    const int L = y.L, k = y.k, inst = blockIdx.x, lane = threadIdx.x;
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const unsigned char* lo_t = base + y.lo_off;
     const uint16_t* qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
@@ -240,34 +239,40 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
     const unsigned long long key = best_key[inst];
     const uint32_t bits = (uint32_t)(key >> 32), r = (uint32_t)(key & 0xFFFFFFFFull);
     if (key == PPO_KEY_NONE || bits >= kInfBits || r >= factorial_u32(k)) {
-        beta_out[inst] = __uint_as_float(kInfBits);
-        for (int s = 0; s < k; ++s) order[s] = -1;
-        for (int s = 0; s + 1 < k; ++s) cuts[s] = -1;
+        if (lane == 0) {
+            beta_out[inst] = __uint_as_float(kInfBits);
+            for (int s = 0; s < k; ++s) order[s] = -1;
+            for (int s = 0; s + 1 < k; ++s) cuts[s] = -1;
+        }
         return;
     }
+    // the rows of the winner's DP: one wave, lanes over the segment end
     const uint64_t perm = unrank_packed(r, k);
-    for (int s = 0; s < k; ++s)
-        for (int e = 0; e <= L; ++e) rows[s][e] = (uint16_t)kCodeInf;
     {
         const unsigned char* lo0 = lo_t + perm_at(perm, 0) * (L + 1);
-        for (int e = 1; e <= L - (k - 1); ++e)
-            if (lo0[e] == 0) rows[0][e] = (uint16_t)kCodeZero;
+        for (int e = lane; e <= L; e += 64)
+            rows[0][e] = (uint16_t)((e >= 1 && e <= L - (k - 1) && lo0[e] == 0) ? kCodeZero : kCodeInf);
     }
+    __syncthreads();
     for (int s = 1; s < k; ++s) {
         const int node = perm_at(perm, s);
         const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), node, k) * L;
         const unsigned char* lo = lo_t + node * (L + 1);
-        for (int e = s + 1; e <= L - (k - 1 - s); ++e) {
-            int first = lo[e] > s ? lo[e] : s;
+        for (int e = lane; e <= L; e += 64) {
             uint32_t acc = kCodeInf;
-            for (int i = first; i < e; ++i) {
-                uint32_t d = rows[s - 1][i], g = q[i - 1];
-                uint32_t c = d > g ? d : g;
-                acc = c < acc ? c : acc;
+            if (e >= s + 1 && e <= L - (k - 1 - s)) {
+                const int first = lo[e] > s ? lo[e] : s;
+                for (int i = first; i < e; ++i) {
+                    const uint32_t d = rows[s - 1][i], g = q[i - 1];
+                    const uint32_t c = d > g ? d : g;
+                    acc = c < acc ? c : acc;
+                }
             }
             rows[s][e] = (uint16_t)acc;
         }
+        __syncthreads();
     }
+    if (lane != 0) return;
     const uint32_t beta_code = rows[k - 1][L];
     beta_out[inst] = (beta_code >= kCodeInf) ? __uint_as_float(kInfBits) : dec[beta_code - kCodeZero];
     for (int s = 0; s < k; ++s) order[s] = perm_at(perm, s);
