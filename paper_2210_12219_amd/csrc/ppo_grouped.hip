@@ -84,7 +84,7 @@ struct GroupedShape {
         g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
         g.d0_off = g.slot_off + 42u * 64u / 2u;   // schedule entries are 16 bits
         g.srow_off = g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4));
-        g.total_bytes = (g.srow_off + 3u * (uint32_t)g.NP + 2u) * 4u;   // two shared rows, their linked form (one dword below it), one flag
+        g.total_bytes = (g.srow_off + 3u * (uint32_t)g.NP + 3u) * 4u;   // two shared rows, their linked form (one dword below it), two flags
         return g;
     }
 };
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     uint32_t qreg[kQRows * kQCols];
     uint64_t next_prefix = 0, next_avail = 0;
     uint64_t shared_prefix_done = 0;   // prefix whose shared rows are in LDS (kGrpShared)
-    if (group_first < group_end) {
+    if (!(MODE == kGrpShared && p0 >= 1) && group_first < group_end) {
         decode_group(group_first >> 1, next_prefix, next_avail);
         fetch_quotients(next_prefix, next_avail, qreg);
     }
@@ -258,16 +258,15 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     const uint32_t group = group_first + 2u * gi;
     if (group >= group_end) break;
     const uint32_t pr = group >> 1;
-    const uint64_t avail = next_avail, prefix = next_prefix;
-    auto rest_node = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
-    // node at DP row s for the lane set of remaining-node index c
-    auto row_node = [=](int s, int c) {
-        const uint64_t packed = s < p0 ? prefix : avail;
-        const int idx = s < p0 ? s : c;
-        return (int)((packed >> (4 * idx)) & 0xFull);
-    };
-    store_quotients(qreg);
-    __syncthreads();
+    if (MODE == kGrpShared && p0 >= 1) {
+        // no group ahead here: a group may be skipped.  Only wave 0, which decides that, needs the prefix now;
+        // the other waves decode it (and everybody fetches the quotient rows) once the group is known to stay.
+        if (wave == 0) decode_group(pr, next_prefix, next_avail);
+    }
+    if (!(MODE == kGrpShared && p0 >= 1)) {
+        store_quotients(qreg);
+        __syncthreads();
+    }
 
     // column of the quotient row holding (q[e-1], q[e]) for the output dword jj of row s (e = 2jj + s)
     auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
@@ -282,7 +281,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         //      rows 0 .. p0-2 are still there and only the last row is computed.
         uint32_t* const srow = lds + gs.srow_off;
         uint32_t* const linked = srow + 2 * NP + 1;
-        uint32_t* const skip_flag = srow + 3 * NP + 1;
+        uint32_t* const skip_flag = srow + 3 * NP + 1 + (gi & 1u);   // two flags in turn: one barrier per group suffices
+        const uint64_t prefix = next_prefix;   // wave 0's; the other waves do not use it in this block
         auto prefix_node = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
         if (wave == 0) {
             const uint32_t known = (uint32_t)(__atomic_load_n(best_key + inst, __ATOMIC_RELAXED) >> 32);
@@ -296,7 +296,10 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 uint32_t* out = srow + (s & 1) * NP;
                 uint32_t res = kInf2;
                 // quotient row s-1: the link between prefix nodes s-1 and s
-                if (live) linked[lane] = pk_max(prev[lane], qtab[(s - 1) * QROW + link_col(s - 1) + lane]);
+                // (read from global memory: the quotient rows of this group are not staged in LDS yet)
+                if (live)
+                    linked[lane] = pk_max(prev[lane], qa[pair_index(prefix_node(s - 1), prefix_node(s), k) * y.qa_cols +
+                                                         link_col(s - 1) + lane]);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 if (live) {
                     const uint32_t t = (uint32_t)lane % kChunkPairs;
@@ -307,7 +310,23 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                     const uint32_t n = WinDesc::steps(below, t);
                     const uint32_t* own = linked + lane;   // the input dword at the output's own index
                     uint32_t acc = chain_init_v(own[0], ctrl, init_mask);
-                    for (uint32_t i = 1; i <= n; ++i) acc = chain_step(acc, own[-(int)(i - 1)], own[-(int)i]);
+                    {
+                        // four steps per round, their LDS reads issued together
+                        uint32_t cur = own[0], i = 1;
+                        for (; i + 3u <= n; i += 4u) {
+                            const uint32_t b1 = own[-(int)i], b2 = own[-(int)(i + 1)], b3 = own[-(int)(i + 2)], b4 = own[-(int)(i + 3)];
+                            acc = chain_step(acc, cur, b1);
+                            acc = chain_step(acc, b1, b2);
+                            acc = chain_step(acc, b2, b3);
+                            acc = chain_step(acc, b3, b4);
+                            cur = b4;
+                        }
+                        for (; i <= n; ++i) {
+                            const uint32_t b1 = own[-(int)i];
+                            acc = chain_step(acc, cur, b1);
+                            cur = b1;
+                        }
+                    }
                     acc = pk_min3(acc, pk_max_lower(own[-(int)n], maskA), pk_max_upper(own[-(int)(n + 1)], maskB));
                     if (ctrl & WinDesc::kFold) {
                         const uint32_t cnt = WinDesc::fold_dwords(ctrl);
@@ -340,15 +359,20 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         }
         shared_prefix_done = prefix;
         __syncthreads();
-        if (*skip_flag) {
-            if (gi + 1 < groups_per_block && group + 2u < group_end) {
-                decode_group((group + 2u) >> 1, next_prefix, next_avail);
-                fetch_quotients(next_prefix, next_avail, qreg);
-            }
-            __syncthreads();   // the flag and the quotient rows are rewritten by the next group
-            continue;
-        }
+        if (*skip_flag) continue;
+        if (wave != 0) decode_group(pr, next_prefix, next_avail);
+        fetch_quotients(next_prefix, next_avail, qreg);
+        store_quotients(qreg);
+        __syncthreads();
     }
+    const uint64_t avail = next_avail, prefix = next_prefix;
+    auto rest_node = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
+    // node at DP row s for the lane set of remaining-node index c
+    auto row_node = [=](int s, int c) {
+        const uint64_t packed = s < p0 ? prefix : avail;
+        const int idx = s < p0 ? s : c;
+        return (int)((packed >> (4 * idx)) & 0xFull);
+    };
 
     // quotient row used when row s is written (the link between the nodes of rows s and s+1), from the
     // lane's schedule entry
@@ -480,7 +504,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 
     for (int s = s_first + 1; s <= k - 2; ++s) {
         // the next group's quotient rows are requested one row of the DP before this group ends
-        if (s == k - 2 && gi + 1 < groups_per_block && group + 2u < group_end) {
+        if (!(MODE == kGrpShared && p0 >= 1) && s == k - 2 && gi + 1 < groups_per_block && group + 2u < group_end) {
             decode_group((group + 2u) >> 1, next_prefix, next_avail);
             fetch_quotients(next_prefix, next_avail, qreg);
         }
