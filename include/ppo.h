@@ -48,7 +48,8 @@ extern "C" {
 #endif
 
 #define PPO_OK 0
-#define PPO_EINVAL (-1)   /* null pointer, L < 1, k < 1, k > L, n_inst < 0, bad rank range */
+#define PPO_EINVAL (-1)   /* null pointer, L < 1, k < 1, k > L, n_inst < 0, bad rank range, a workspace that is
+                             not 256-byte aligned, a key or counter array that is not 8-byte aligned */
 #define PPO_ETOOBIG (-2)  /* k > PPO_MAX_K or L > PPO_MAX_L */
 #define PPO_EHIP (-3)     /* a HIP call failed; ppo_strerror gives the runtime's text */
 #define PPO_ENOSPC (-4)   /* workspace smaller than ppo_workspace_bytes() */

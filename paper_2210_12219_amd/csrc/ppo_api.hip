@@ -83,6 +83,12 @@ int run_finalize(int L, int k, int n_inst, const void* ws, const uint64_t* best_
 
 }  // namespace
 
+// The kernels read the tables with 16-byte loads at offsets that are multiples of 16 within the workspace
+// and update the keys with 64-bit atomics: pointers that break these alignments are refused here.
+static bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+static bool bad_workspace(const void* ws) { return !ws || misaligned(ws, 256); }
+static bool bad_keys(const void* keys) { return !keys || misaligned(keys, 8); }
+
 extern "C" {
 
 int ppo_version(void) { return 103; }
@@ -116,7 +122,7 @@ int ppo_prepare(const float* t, const float* m, int L, const float* M, const flo
     int rc = check_shape(L, k, n_inst);
     if (rc) return rc;
     if (n_inst == 0) return PPO_OK;
-    if (!t || !m || !M || !B || !workspace) return PPO_EINVAL;
+    if (!t || !m || !M || !B || bad_workspace(workspace)) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     return run_prepare(t, m, L, M, B, k, n_inst, workspace, static_cast<hipStream_t>(stream));
 }
@@ -124,7 +130,7 @@ int ppo_prepare(const float* t, const float* m, int L, const float* M, const flo
 int ppo_init_keys(uint64_t* best_key, int n_inst, void* stream) {
     if (n_inst < 0) return PPO_EINVAL;
     if (n_inst == 0) return PPO_OK;
-    if (!best_key) return PPO_EINVAL;
+    if (bad_keys(best_key)) return PPO_EINVAL;
     PPO_HIP(ppo::launch_init_keys(best_key, n_inst, static_cast<hipStream_t>(stream)), "init_keys launch");
     return PPO_OK;
 }
@@ -135,7 +141,7 @@ int ppo_solve_range(int L, int k, int n_inst, const void* workspace, size_t work
     if (rc) return rc;
     if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
     if (n_inst == 0) return PPO_OK;
-    if (!best_key || !workspace) return PPO_EINVAL;
+    if (bad_keys(best_key) || bad_workspace(workspace)) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key, false, nullptr,
                      static_cast<hipStream_t>(stream));
@@ -148,7 +154,7 @@ int ppo_solve_range_bounded(int L, int k, int n_inst, const void* workspace, siz
     if (rc) return rc;
     if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
     if (n_inst == 0) return PPO_OK;
-    if (!best_key || !workspace) return PPO_EINVAL;
+    if (bad_keys(best_key) || bad_workspace(workspace) || (skipped_groups && misaligned(skipped_groups, 8))) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     return run_range(L, k, n_inst, workspace, (uint32_t)rank_begin, (uint32_t)rank_end, best_key, true, skipped_groups,
                      static_cast<hipStream_t>(stream));
@@ -159,7 +165,7 @@ int ppo_solve_subsets(int L, int k, int n_inst, const void* workspace, size_t wo
     int rc = check_shape(L, k, n_inst);
     if (rc) return rc;
     if (n_inst == 0) return PPO_OK;
-    if (!best_key || !workspace) return PPO_EINVAL;
+    if (bad_keys(best_key) || bad_workspace(workspace)) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const ppo::Layout y = ppo::Layout::make(L, k);
@@ -187,7 +193,7 @@ int ppo_finalize(int L, int k, int n_inst, const void* workspace, size_t workspa
     int rc = check_shape(L, k, n_inst);
     if (rc) return rc;
     if (n_inst == 0) return PPO_OK;
-    if (!workspace || !best_key || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
+    if (bad_workspace(workspace) || bad_keys(best_key) || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     return run_finalize(L, k, n_inst, workspace, best_key, beta_out, cuts_out, order_out,
                         static_cast<hipStream_t>(stream));
@@ -199,7 +205,7 @@ int ppo_solve_ws(const float* t, const float* m, int L, const float* M, const fl
     int rc = check_shape(L, k, n_inst);
     if (rc) return rc;
     if (n_inst == 0) return PPO_OK;
-    if (!t || !m || !M || !B || !beta_out || !order_out || (k > 1 && !cuts_out) || !workspace) return PPO_EINVAL;
+    if (!t || !m || !M || !B || !beta_out || !order_out || (k > 1 && !cuts_out) || bad_workspace(workspace)) return PPO_EINVAL;
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const ppo::Layout y = ppo::Layout::make(L, k);

@@ -84,3 +84,13 @@ def test_bad_arguments_are_refused_without_a_gpu(lib):
     assert lib.ppo_eval_orderings(p, p, 4, p, p, 3, 0, 7, p, s) == binding.PPO_EINVAL
     assert lib.ppo_eval_orderings(p, p, 4, p, p, 3, 2, 2, p, s) == binding.PPO_OK   # empty range
     assert lib.ppo_finalize(4, 2, 1, p, 1 << 20, null, p, p, p, s) == binding.PPO_EINVAL
+    # misaligned workspace (256 bytes), keys and counters (8 bytes)
+    odd_ws, odd_key = C.c_void_p(0x1010), C.c_void_p(0x1004)
+    assert lib.ppo_prepare(p, p, 4, p, p, 3, 1, odd_ws, 1 << 20, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_ws(p, p, 4, p, p, 2, 1, p, p, p, odd_ws, 1 << 20, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range(4, 3, 1, odd_ws, 1 << 20, 0, 6, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 0, 6, odd_key, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_range_bounded(4, 3, 1, p, 1 << 20, 0, 6, p, odd_key, s) == binding.PPO_EINVAL
+    assert lib.ppo_solve_subsets(4, 3, 1, odd_ws, 1 << 20, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_finalize(4, 2, 1, p, 1 << 20, odd_key, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_init_keys(odd_key, 3, s) == binding.PPO_EINVAL
