@@ -212,3 +212,56 @@ def random_instances(seed: int, n_inst: int, L: int, k: int, *, capacity_factor:
             B = _symmetric_bandwidth(rng, k, 2.0, 50.0)
         ts.append(t); ms.append(m); Ms.append(cap); Bs.append(B)
     return _finish("random", L, k, n_inst, seed, ts, ms, Ms, Bs)
+
+
+# ---------------------------------------------------------------------------------------------
+# Cluster form: more nodes than segments.  Same arrays, with k read as the cluster size n.
+# ---------------------------------------------------------------------------------------------
+_SHANNON_A = 283230.0   # Sec. IV: chosen so that a device 80 m from the router gets 5.5 Mbps
+
+
+def _geometric_bandwidth(rng: np.random.Generator, n: int) -> np.ndarray:
+    """Sec. IV, Eq. 12: device positions with |x|, |y| uniform in (1, 150) m and a random sign each,
+    rate of a device r = log2(1 + a / (x^2 + y^2)).  The paper gives the rate as a function of ONE
+    position (relative to the router) but needs a weight per PAIR of devices; the reading taken here
+    is that traffic between two devices passes the router, so the pair gets the lower of the two
+    rates."""
+    mag = rng.uniform(1.0, 150.0, (n, 2))
+    sign = rng.choice(np.array([-1.0, 1.0]), size=(n, 2))
+    pos = mag * sign
+    r = np.log2(1.0 + _SHANNON_A / np.sum(pos * pos, axis=1))
+    B = np.minimum(r[:, None], r[None, :])
+    np.fill_diagonal(B, 0.0)
+    return B
+
+
+def cluster_geometric(n: int, capacity_mb: float, n_inst: int = 16, seed: int = 5) -> Workload:
+    """The paper's evaluation cluster (Sec. IV): n randomly placed devices of ONE capacity (64, 128, 256
+    or 512 MB there) under the 50-layer bottleneck-block chain of resnet50_shaped (about 94 MB of
+    weights), activation sizes jittered by +-20 % per instance.  Bandwidths come in few distinct
+    values (each device's rate), so equal latencies are common."""
+    L = 50
+    base_t, base_m = _resnet50_chain()
+    rng = np.random.default_rng(seed)
+    ts, ms, Ms, Bs = [], [], [], []
+    for _ in range(n_inst):
+        ts.append(base_t * rng.uniform(0.8, 1.2, L)); ms.append(base_m.copy())
+        Ms.append(np.full(n, float(capacity_mb)))
+        Bs.append(_geometric_bandwidth(rng, n))
+    return _finish(f"cluster_geometric_n{n}_c{int(capacity_mb)}", L, n, n_inst, seed, ts, ms, Ms, Bs)
+
+
+def cluster_mixed(n: int, L: int = 100, n_inst: int = 8, seed: int = 6, capacity_factor: float = 0.25) -> Workload:
+    """n nodes with capacities of 1x, 2x, 4x or 8x a unit (each about capacity_factor of the model on
+    average) and log-uniform bandwidths, under a log-uniform chain as in `headline`: at least
+    1/capacity_factor segments are needed, and which nodes to leave out is part of the search."""
+    rng = np.random.default_rng(seed)
+    ts, ms, Ms, Bs = [], [], [], []
+    for _ in range(n_inst):
+        t = _log_uniform(rng, 0.5, 40.0, L)
+        m = _log_uniform(rng, 0.1, 100.0, L)
+        raw = rng.choice(np.array([1.0, 2.0, 4.0, 8.0]), size=n)
+        ts.append(t); ms.append(m)
+        Ms.append(raw * (capacity_factor * float(np.sum(m)) / float(np.mean(raw))))
+        Bs.append(_symmetric_bandwidth(rng, n, 1.0, 100.0))
+    return _finish(f"cluster_mixed_n{n}", L, n, n_inst, seed, ts, ms, Ms, Bs)

@@ -1,0 +1,197 @@
+"""Pins for the cluster-form oracle (oracle/ppo_cluster_oracle.c): facts fixed by the problem statement
+and by the mathematics.  The expected values come from the fixed-k oracle's definition route on node
+subsets assembled here, from closed forms, or from invariants; none from the HIP path."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import ppo_cluster_oracle as CO
+from oracle import ppo_oracle as O
+from paper_2210_12219_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+ROUTES = {"bruteforce": CO.bruteforce, "exhaustive": CO.exhaustive, "subset_dp": CO.subset_dp}
+
+
+def bits(x):
+    return int(np.asarray(x, dtype=np.float32).view(np.uint32))
+
+
+def inst(w, i):
+    return w.t[i], w.m[i], w.M[i], w.B[i]
+
+
+def by_node_subsets(t, m, M, B, pmax):
+    """The cluster optimum assembled from the fixed-k definition route: for every node subset of every
+    size p <= pmax, the exact-k optimum on that subset; then rule C1 over the node sequences."""
+    n, L = len(M), len(t)
+    best = None
+    for p in range(1, min(pmax, L) + 1):
+        for S in itertools.combinations(range(n), p):
+            idx = np.array(S)
+            beta, cuts, order = O.bruteforce(t, m, M[idx], B[np.ix_(idx, idx)])
+            if not np.isfinite(beta[0]):
+                continue
+            seq = tuple(int(idx[j]) for j in order[0])     # lowest rank within S = smallest sequence over S
+            cand = (bits(beta[0]), seq, tuple(int(c) for c in cuts[0]))
+            if best is None or cand[:2] < best[:2]:
+                best = cand
+    return best
+
+
+def as_tuple(res):
+    beta, p, cuts, order = res
+    if p == 0:
+        return None
+    return (bits(beta), tuple(int(x) for x in order[:p]), tuple(int(x) for x in cuts[:p - 1]))
+
+
+@pytest.mark.parametrize("route", ROUTES)
+@pytest.mark.parametrize("quantised", [False, True])
+def test_equals_the_fixed_k_definition_over_node_subsets(route, quantised):
+    w = W.random_instances(seed=100 + quantised, n_inst=12, L=8, k=5, capacity_factor=2.5, quantised=quantised)
+    for i in range(w.n_inst):
+        t, m, M, B = inst(w, i)
+        for pmax in (1, 2, 3, 5):
+            got = ROUTES[route](t, m, M, B, pmax)
+            want = by_node_subsets(t, m, M, B, pmax)
+            assert as_tuple(got) == want, (i, pmax)
+            beta, p, cuts, order = got
+            assert list(order[p:]) == [-1] * (len(M) - p) and list(cuts[max(p - 1, 0):]) == [-1] * (len(M) - 1 - max(p - 1, 0))
+
+
+@pytest.mark.parametrize("route", ROUTES)
+def test_worked_example_in_a_larger_cluster(route):
+    """Sec. I: 10.2 Mbit over 6 Mbps is about 1.7 s.  Two layers, neither node holds both; the third and
+    fourth node are too small for any layer, so the example's two nodes and its link decide."""
+    g = {}
+    with open(os.path.join(GOLDEN, "worked_example.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                g[k] = v
+    t = np.array([float(g["t_mbit"]), 3.0], np.float32)
+    m = np.array([4.0, 4.0], np.float32)
+    M = np.array([0.5, 5.0, 0.25, 5.0], np.float32)
+    B = np.full((4, 4), 100.0, np.float32)
+    B[1, 3] = B[3, 1] = float(g["bandwidth_mbps"])
+    np.fill_diagonal(B, 0)
+    beta, p, cuts, order = ROUTES[route](t, m, M, B)
+    assert bits(beta) == int(g["beta_bits"], 16) and abs(float(beta) - float(g["paper_seconds"])) < 1e-6
+    assert p == 2 and list(order) == [1, 3, -1, -1] and list(cuts) == [1, -1, -1]
+
+
+@pytest.mark.parametrize("route", ROUTES)
+def test_closed_forms(route):
+    f = ROUTES[route]
+    t = np.array([8.0, 2.0, 6.0, 1.0], np.float32)
+    m = np.array([1.0, 2.0, 3.0, 4.0], np.float32)
+    B = np.array([[0, 4, 2], [4, 0, 8], [2, 8, 0]], np.float32)
+    # the whole model fits node 1 (and node 2): one segment, no link, the smallest such node
+    beta, p, cuts, order = f(t, m, np.array([9.0, 10.0, 11.0], np.float32), B)
+    assert (float(beta), p, list(order), list(cuts)) == (0.0, 1, [1, -1, -1], [-1, -1])
+    # capacities 6, 6, 3: two segments need cut 3 ([1,2,3 | 4]: 6 and 4 <= 6) on nodes {0,1}: 6/4;
+    # three segments allow [1,2 | 3 | 4] or [1,2|3|4] variants; the cheapest tensors are t[1] = 2 and t[3]...
+    M = np.array([6.0, 6.0, 3.0], np.float32)
+    beta, p, cuts, order = f(t, m, M, B, 2)
+    assert (float(beta), p, list(order[:2]), list(cuts[:1])) == (6.0 / 4.0, 2, [0, 1], [3])
+    # nothing fits: three nodes of capacity 3 cannot hold layer 4 (weight 4)
+    beta, p, cuts, order = f(t, m, np.array([3.0, 3.0, 3.0], np.float32), B)
+    assert np.isinf(beta) and p == 0 and list(order) == [-1, -1, -1] and list(cuts) == [-1, -1]
+    # one segment allowed only: feasible iff some node holds everything
+    beta, p, _, order = f(t, m, np.array([9.0, 12.0, 11.0], np.float32), B, 1)
+    assert (float(beta), p, int(order[0])) == (0.0, 1, 1)
+    beta, p, _, _ = f(t, m, M, B, 1)
+    assert np.isinf(beta) and p == 0
+
+
+@pytest.mark.parametrize("route", ROUTES)
+def test_more_segments_can_beat_fewer(route):
+    """Capacities force the only two-segment cut onto the largest tensor; a third node lets the chain
+    be cut at the two small tensors instead."""
+    t = np.array([1.0, 64.0, 1.0, 5.0], np.float32)
+    m = np.array([2.0, 2.0, 2.0, 2.0], np.float32)
+    M = np.array([4.0, 4.0, 4.0], np.float32)
+    B = np.full((3, 3), 2.0, np.float32)
+    np.fill_diagonal(B, 0)
+    f = ROUTES[route]
+    beta2, p2, cuts2, _ = f(t, m, M, B, 2)
+    assert (float(beta2), p2, int(cuts2[0])) == (32.0, 2, 2)
+    beta3, p3, cuts3, order3 = f(t, m, M, B, 3)
+    assert (float(beta3), p3, list(cuts3), list(order3)) == (0.5, 3, [1, 3], [0, 1, 2])
+
+
+def test_routes_agree_and_invariants_hold():
+    rng = np.random.default_rng(7)
+    for seed, (L, n, q, cf) in enumerate([(10, 6, False, 2.0), (10, 6, True, 2.0), (16, 7, False, 3.0), (9, 7, True, 4.0)]):
+        w = W.random_instances(seed=200 + seed, n_inst=6, L=L, k=n, capacity_factor=cf, quantised=q)
+        for i in range(w.n_inst):
+            t, m, M, B = inst(w, i)
+            prev = None
+            for pmax in range(1, n + 1):
+                a = as_tuple(CO.exhaustive(t, m, M, B, pmax))
+                b = as_tuple(CO.subset_dp(t, m, M, B, pmax))
+                assert a == b, (seed, i, pmax)
+                if L <= 10:
+                    assert as_tuple(CO.bruteforce(t, m, M, B, pmax)) == a
+                # more segments allowed never hurts
+                if prev is not None and a is not None:
+                    assert a[0] <= prev[0]
+                if a is not None:
+                    prev = a
+                    # the reported solution is feasible with exactly that bottleneck, by the fixed-k evaluator
+                    idx = np.array(a[1])
+                    beta, feas = O.evaluate(t, m, M[idx], B[np.ix_(idx, idx)], np.arange(len(idx)), np.array(a[2], np.int32))
+                    assert feas and bits(beta) == a[0]
+                    # and no sampled sequence does better
+                    for _ in range(20):
+                        p = int(rng.integers(1, pmax + 1))
+                        seq = rng.permutation(n)[:p]
+                        assert bits(CO.sequence_beta(t, m, M, B, seq)) >= a[0]
+            full = as_tuple(CO.subset_dp(t, m, M, B))
+            # a node too small for any layer changes nothing; an extra copy of a node never hurts
+            M2 = np.concatenate([M, [0.0]]).astype(np.float32)
+            B2 = np.pad(B, ((0, 1), (0, 1)), constant_values=1.0).astype(np.float32)
+            B2[n, n] = 0
+            assert as_tuple(CO.subset_dp(t, m + np.float32(0.01), M2, B2, n)) == as_tuple(CO.subset_dp(t, m + np.float32(0.01), M, B, n))
+            if full is not None:
+                M3 = np.concatenate([M, M[:1]]).astype(np.float32)
+                B3 = np.pad(B, ((0, 1), (0, 1))).astype(np.float32)
+                B3[n, :n] = B[0]; B3[:n, n] = B[0]; B3[n, 0] = B3[0, n] = 1.0
+                got = as_tuple(CO.subset_dp(t, m, M3, B3))
+                assert got[0] <= full[0]
+
+
+def test_relabelling_the_nodes_moves_the_answer_with_them():
+    w = W.random_instances(seed=300, n_inst=8, L=12, k=6, capacity_factor=2.5)
+    rng = np.random.default_rng(1)
+    for i in range(w.n_inst):
+        t, m, M, B = inst(w, i)
+        base = CO.subset_dp(t, m, M, B)
+        perm = rng.permutation(6)
+        beta, p, cuts, order = CO.subset_dp(t, m, M[perm], B[np.ix_(perm, perm)])
+        assert bits(beta) == bits(base[0])
+        if p:
+            # same bottleneck through the relabelled nodes, evaluated from the definition
+            seq = perm[order[:p]]
+            assert bits(CO.sequence_beta(t, m, M, B, seq)) == bits(base[0])
+
+
+def test_equals_fixed_k_when_every_node_is_needed():
+    """Capacities so tight that fewer than n segments cannot hold the model: the cluster optimum is the
+    fixed-k optimum, ordering and cuts included."""
+    for seed in range(6):
+        w = W.random_instances(seed=400 + seed, n_inst=4, L=12, k=4, capacity_factor=1.15)
+        for i in range(w.n_inst):
+            t, m, M, B = inst(w, i)
+            # drop the instance unless no three nodes can hold the model
+            if np.sort(M)[1:].sum() >= m.sum():
+                continue
+            beta, cuts, order = O.bruteforce(t, m, M, B)
+            got = CO.subset_dp(t, m, M, B)
+            if np.isinf(beta[0]):
+                assert got[1] == 0
+            else:
+                assert as_tuple(got) == (bits(beta[0]), tuple(order[0]), tuple(cuts[0]))
