@@ -50,12 +50,13 @@ extern "C" {
 #define PPO_OK 0
 #define PPO_EINVAL (-1)   /* null pointer, L < 1, k < 1, k > L, n_inst < 0, bad rank range, a workspace that is
                              not 256-byte aligned, a key or counter array that is not 8-byte aligned */
-#define PPO_ETOOBIG (-2)  /* k > PPO_MAX_K or L > PPO_MAX_L */
+#define PPO_ETOOBIG (-2)  /* k > PPO_MAX_K, n > PPO_CLUSTER_MAX_N or L > PPO_MAX_L */
 #define PPO_EHIP (-3)     /* a HIP call failed; ppo_strerror gives the runtime's text */
 #define PPO_ENOSPC (-4)   /* workspace smaller than ppo_workspace_bytes() */
 
 #define PPO_MAX_K 12
 #define PPO_MAX_L 128
+#define PPO_CLUSTER_MAX_N 20   /* cluster size of ppo_solve_cluster */
 
 /* Key of an ordering: (IEEE bits of its beta) << 32 | lexicographic rank.  For beta >= +0 the bit
  * pattern orders like the value, so the unsigned minimum of keys is the lowest beta and, among
@@ -149,6 +150,31 @@ int ppo_finalize(int L, int k, int n_inst, const void *workspace, size_t workspa
  * arithmetic as the search; allocates and releases its scratch on the stream. */
 int ppo_eval_orderings(const float *t, const float *m, int L, const float *M, const float *B, int k,
                        uint64_t rank_begin, uint64_t rank_end, float *beta_per_ordering, void *stream);
+
+/* Cluster form (paper Sec. III-B: the partitioner fixes how many partitions there are and the placement
+ * picks that many nodes of the communication graph as a simple path; Sec. IV: clusters of 5 to 50
+ * devices).  The exact counterpart: over every number of segments p, 1 <= p <= min(max_segments, L),
+ * every sequence of p DISTINCT nodes out of the n of the cluster and every cut vector, the minimum of
+ * beta (Eq. 2, Eq. 3; memory rule and arithmetic as stated at the top).  Found by dynamic programming over
+ * the sets of nodes not yet used: n 2^n rows of L+1 16-bit entries per instance, level by level.
+ *   t, m [n_inst][L]   M [n_inst][n]   B [n_inst][n][n]      1 <= n <= PPO_CLUSTER_MAX_N, L <= PPO_MAX_L;
+ *                                                            n may exceed L
+ *   max_segments       1..n
+ *   beta_out  [n_inst]        +inf if no feasible solution
+ *   segs_out  [n_inst]        p of the solution returned; 0 if infeasible
+ *   order_out [n_inst][n]     the p hosting nodes in chain order, then -1
+ *   cuts_out  [n_inst][n-1]   c_1..c_{p-1}, then -1 (may be NULL when n = 1)
+ * Uniqueness: among the optimal node sequences the lexicographically smallest, a sequence sorting before
+ * every sequence it is a proper prefix of; then the cut rule stated at the top.
+ * workspace: device, 256-byte aligned, at least ppo_cluster_workspace_bytes(L, n, 1) bytes; it holds the
+ * tables of all instances and the DP rows of as many instances as fit (they are solved that many at a
+ * time), so a larger workspace runs more instances per launch.  ppo_cluster_workspace_bytes(L, n, n_inst)
+ * is the size at which all n_inst run together, capped at 16 GiB of rows (but never below one instance's:
+ * 4.3 GB at n = 20, L = 100).  Returns 0 on a bad shape. */
+size_t ppo_cluster_workspace_bytes(int L, int n, int n_inst);
+int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, const float *B, int n, int n_inst,
+                      int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(PKG, "libppo.so")
 
 PPO_OK, PPO_EINVAL, PPO_ETOOBIG, PPO_EHIP, PPO_ENOSPC = 0, -1, -2, -3, -4
 PPO_MAX_K, PPO_MAX_L = 12, 128
+PPO_CLUSTER_MAX_N = 20
 PPO_KEY_NONE = 0xFFFFFFFFFFFFFFFF
 
 
@@ -51,6 +52,9 @@ def load() -> C.CDLL:
         lib.ppo_solve_subsets.argtypes = [i, i, i, vp, sz, vp, vp]
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
+        lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
+        lib.ppo_cluster_workspace_bytes.restype = sz
+        lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -205,6 +209,31 @@ def ppo_eval_orderings(t, m, M, B, rank_begin, rank_end, stream=None):
     _check(load().ppo_eval_orderings(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, int(rank_begin),
                                      int(rank_end), C.c_void_p(out.data_ptr()), _stream(stream)))
     return out
+
+
+def ppo_cluster_workspace_bytes(L: int, n: int, n_inst: int) -> int:
+    return int(load().ppo_cluster_workspace_bytes(L, n, n_inst))
+
+
+def ppo_solve_cluster(t, m, M, B, max_segments=None, workspace=None, out=None, stream=None):
+    """Cluster form: (beta [n_inst], segs [n_inst], cuts [n_inst, n-1], order [n_inst, n]) over every number of
+    segments up to max_segments (default n) and every sequence of distinct nodes."""
+    torch = _torch()
+    n_inst, L = t.shape
+    n = M.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    if workspace is None:
+        workspace = torch.empty(ppo_cluster_workspace_bytes(L, n, n_inst), dtype=torch.uint8, device=t.device)
+    if out is None:
+        out = (torch.empty(n_inst, dtype=f32, device=t.device), torch.empty(n_inst, dtype=i32, device=t.device),
+               torch.empty((n_inst, max(n - 1, 0)), dtype=i32, device=t.device),
+               torch.empty((n_inst, n), dtype=i32, device=t.device))
+    beta, segs, cuts, order = out
+    _check(load().ppo_solve_cluster(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), n, n_inst,
+                                    n if max_segments is None else int(max_segments), _dev(beta, f32),
+                                    _dev(segs, i32), C.c_void_p(cuts.data_ptr()), _dev(order, i32),
+                                    C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    return beta, segs, cuts, order
 
 
 def orderings_per_instance(k: int) -> int:

@@ -14,6 +14,12 @@ hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, fl
 void set_enumeration_variant(int);
 size_t subset_scratch_bytes_per_instance(int L, int k);
 hipError_t launch_subset(const Layout&, int, const void*, void*, uint64_t*, hipStream_t);
+size_t cluster_tables_bytes(int L, int n);
+size_t cluster_rows_bytes(int L, int n);
+hipError_t launch_cluster_tables(const float*, const float*, const float*, const float*, int, int, int, void*,
+                                 hipStream_t);
+hipError_t launch_cluster_solve(int, int, int, int, const void*, void*, float*, int32_t*, int32_t*, int32_t*,
+                                hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -91,7 +97,7 @@ static bool bad_keys(const void* keys) { return !keys || misaligned(keys, 8); }
 
 extern "C" {
 
-int ppo_version(void) { return 103; }
+int ppo_version(void) { return 104; }
 
 int ppo_set_enumeration(int variant) {
     if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC) return PPO_EINVAL;
@@ -185,6 +191,55 @@ int ppo_solve_subsets(int L, int k, int n_inst, const void* workspace, size_t wo
     const hipError_t e2 = hipFreeAsync(scratch, s);
     PPO_HIP(e, "subset DP launch");
     PPO_HIP(e2, "hipFreeAsync (subset DP rows)");
+    return PPO_OK;
+}
+
+static int check_cluster_shape(int L, int n, int n_inst) {
+    if (L < 1 || n < 1 || n_inst < 0) return PPO_EINVAL;
+    if (n > PPO_CLUSTER_MAX_N || L > PPO_MAX_L) return PPO_ETOOBIG;
+    return PPO_OK;
+}
+
+size_t ppo_cluster_workspace_bytes(int L, int n, int n_inst) {
+    if (check_cluster_shape(L, n, n_inst) != PPO_OK) return 0;
+    const size_t rows = ppo::cluster_rows_bytes(L, n);
+    size_t together = ((size_t)16 << 30) / rows;
+    if (together < 1) together = 1;
+    if (together > (size_t)n_inst) together = (size_t)n_inst;
+    return ppo::cluster_tables_bytes(L, n) * (size_t)n_inst + rows * together;
+}
+
+int ppo_solve_cluster(const float* t, const float* m, int L, const float* M, const float* B, int n, int n_inst,
+                      int max_segments, float* beta_out, int32_t* segs_out, int32_t* cuts_out, int32_t* order_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_cluster_shape(L, n, n_inst);
+    if (rc) return rc;
+    if (max_segments < 1 || max_segments > n) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_out || !segs_out || !order_out || (n > 1 && !cuts_out) || bad_workspace(workspace))
+        return PPO_EINVAL;
+    const size_t tables = ppo::cluster_tables_bytes(L, n), rows = ppo::cluster_rows_bytes(L, n);
+    if (workspace_bytes < tables * (size_t)n_inst + rows) return PPO_ENOSPC;
+    size_t together = (workspace_bytes - tables * (size_t)n_inst) / rows;
+    if (together > (size_t)kInstPerLaunch) together = (size_t)kInstPerLaunch;
+    if (together > (size_t)n_inst) together = (size_t)n_inst;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    unsigned char* row_area = ws + tables * (size_t)n_inst;   // tables is a multiple of 256
+    const int pmax = max_segments < L ? max_segments : L;
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int cnt = n_inst - first < kInstPerLaunch ? n_inst - first : kInstPerLaunch;
+        PPO_HIP(ppo::launch_cluster_tables(t + (size_t)first * L, m + (size_t)first * L, M + (size_t)first * n,
+                                           B + (size_t)first * n * n, L, n, cnt, ws + tables * (size_t)first, s),
+                "cluster tables launch");
+    }
+    for (size_t first = 0; first < (size_t)n_inst; first += together) {
+        const int cnt = (int)(((size_t)n_inst - first < together) ? (size_t)n_inst - first : together);
+        PPO_HIP(ppo::launch_cluster_solve(L, n, cnt, pmax, ws + tables * first, row_area, beta_out + first,
+                                          segs_out + first, cuts_out ? cuts_out + first * (size_t)(n - 1) : nullptr,
+                                          order_out + first * (size_t)n, s),
+                "cluster DP launch");
+    }
     return PPO_OK;
 }
 

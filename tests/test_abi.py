@@ -94,3 +94,26 @@ def test_bad_arguments_are_refused_without_a_gpu(lib):
     assert lib.ppo_solve_subsets(4, 3, 1, odd_ws, 1 << 20, p, s) == binding.PPO_EINVAL
     assert lib.ppo_finalize(4, 2, 1, p, 1 << 20, odd_key, p, p, p, s) == binding.PPO_EINVAL
     assert lib.ppo_init_keys(odd_key, 3, s) == binding.PPO_EINVAL
+
+
+def test_cluster_entry_point_without_a_gpu(lib):
+    p, null, s = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0)
+    lib.ppo_cluster_workspace_bytes.restype = C.c_size_t
+    one = lib.ppo_cluster_workspace_bytes(100, 20, 1)
+    assert one >= 20 * (1 << 20) * 101 * 2 and one % 256 == 0           # n 2^n rows of L+1 16-bit entries
+    assert lib.ppo_cluster_workspace_bytes(100, 21, 1) == 0 and lib.ppo_cluster_workspace_bytes(129, 5, 1) == 0
+    assert lib.ppo_cluster_workspace_bytes(100, 20, 64) < 64 * one      # rows capped, tables for all
+    assert lib.ppo_cluster_workspace_bytes(4, 9, 3) > 0                 # more nodes than layers is allowed
+    args = lambda L, n, ni, pmax, ws=p, nbytes=1 << 30: (p, p, L, p, p, n, ni, pmax, p, p, p, p, ws, nbytes, s)
+    assert lib.ppo_solve_cluster(*args(0, 3, 1, 1)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 0, 1, 1)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 3, -1, 1)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 3, 1, 0)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 3, 1, 4)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 21, 1, 2)) == binding.PPO_ETOOBIG
+    assert lib.ppo_solve_cluster(*args(129, 3, 1, 2)) == binding.PPO_ETOOBIG
+    assert lib.ppo_solve_cluster(*args(10, 3, 0, 2, null, 0)) == binding.PPO_OK
+    assert lib.ppo_solve_cluster(*args(10, 3, 1, 2, null)) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 3, 1, 2, C.c_void_p(0x1010))) == binding.PPO_EINVAL
+    assert lib.ppo_solve_cluster(*args(10, 3, 1, 2, p, 64)) == binding.PPO_ENOSPC
+    assert lib.ppo_solve_cluster(p, p, 10, p, p, 3, 1, 2, null, p, p, p, p, 1 << 30, s) == binding.PPO_EINVAL

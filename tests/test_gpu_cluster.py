@@ -1,0 +1,174 @@
+"""Cluster form (ppo_solve_cluster): number of segments, hosting nodes and cuts, compared bit for bit with
+the CPU oracle of the cluster form; at sizes the oracle cannot reach, with what holds at any size."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import ppo_cluster_oracle as CO
+from oracle import ppo_oracle as O
+from paper_2210_12219_amd import workloads as W
+
+
+@pytest.fixture(scope="module")
+def ppo():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2210_12219_amd import binding
+    binding.load()
+    return binding
+
+
+def bits(x):
+    return np.asarray(x, dtype=np.float32).view(np.uint32)
+
+
+def solve(ppo, w, pmax=None, workspace_bytes=None):
+    import torch
+    dev = ppo.to_device(w)
+    ws = None
+    if workspace_bytes is not None:
+        ws = torch.empty(workspace_bytes, dtype=torch.uint8, device="cuda:0")
+    out = ppo.ppo_solve_cluster(*dev, max_segments=pmax, workspace=ws)
+    torch.cuda.synchronize()
+    return tuple(x.cpu().numpy() for x in out)
+
+
+def oracle(w, pmax, route):
+    n = w.k
+    beta = np.zeros(w.n_inst, np.float32)
+    segs = np.zeros(w.n_inst, np.int32)
+    cuts = np.zeros((w.n_inst, max(n - 1, 0)), np.int32)
+    order = np.zeros((w.n_inst, n), np.int32)
+    for i in range(w.n_inst):
+        beta[i], segs[i], cuts[i], order[i] = route(w.t[i], w.m[i], w.M[i], w.B[i], pmax)
+    return beta, segs, cuts, order
+
+
+def assert_same(got, ref, what):
+    bad = np.nonzero(bits(got[0]) != bits(ref[0]))[0]
+    assert bad.size == 0, f"{what}: beta differs at instances {bad[:8]}: {got[0][bad[:4]]} vs {ref[0][bad[:4]]}"
+    assert np.array_equal(got[1], ref[1]), f"{what}: number of segments differs"
+    assert np.array_equal(got[3], ref[3]), f"{what}: node sequence differs"
+    assert np.array_equal(got[2], ref[2]), f"{what}: cuts differ"
+
+
+def test_cluster_small_shapes_ties_and_infeasible(ppo):
+    """Random shapes from n = 1 and L = 1 up, clusters larger than the chain included, capacities from
+    'nothing fits' to 'one node holds everything', values with few distinct levels every other seed."""
+    for seed in range(40):
+        rng = np.random.default_rng(7000 + seed)
+        L = int(rng.integers(1, 15))
+        n = int(rng.integers(1, 8))
+        cf = float(rng.uniform(0.5, 1.0) * n) if seed % 3 else float(rng.uniform(0.8, 1.3))
+        w = W.random_instances(seed, 24, L, n, capacity_factor=cf, quantised=bool(seed % 2))
+        for pmax in sorted({1, max(1, n // 2), n}):
+            print(f"cluster small seed={seed} L={L} n={n} pmax={pmax}", flush=True)
+            ref = oracle(w, pmax, CO.exhaustive)
+            assert_same(solve(ppo, w, pmax), ref, f"cluster L={L} n={n} pmax={pmax} seed={seed}")
+
+
+def test_cluster_brute_force_definition(ppo):
+    w = W.random_instances(11, 16, 9, 5, capacity_factor=2.0, quantised=True)
+    print("cluster brute force L=9 n=5", flush=True)
+    assert_same(solve(ppo, w), oracle(w, 5, CO.bruteforce), "cluster vs the definition")
+
+
+@pytest.mark.parametrize("n,cap", [(5, 32), (5, 64), (10, 32), (10, 64), (10, 128), (12, 24), (15, 32)])
+def test_cluster_paper_shaped(ppo, n, cap):
+    """Sec. IV clusters: equal capacities, Shannon-rate bandwidths (few distinct values, many ties)."""
+    w = W.cluster_geometric(n, cap, n_inst=2 if n >= 15 else 6)
+    print(f"cluster geometric n={n} capacity={cap}", flush=True)
+    assert_same(solve(ppo, w), oracle(w, n, CO.subset_dp), f"geometric n={n} cap={cap}")
+
+
+def test_cluster_mixed_capacities_several_tiles(ppo):
+    """L = 100 (two lanes-of-64 passes per row, ragged tail), n = 12 and 14, every max_segments."""
+    w = W.cluster_mixed(12, L=100, n_inst=5)
+    for pmax in (1, 2, 3, 5, 8, 12):
+        print(f"cluster mixed n=12 pmax={pmax}", flush=True)
+        assert_same(solve(ppo, w, pmax), oracle(w, pmax, CO.subset_dp), f"mixed n=12 pmax={pmax}")
+    w = W.cluster_mixed(14, L=100, n_inst=2, seed=9)
+    print("cluster mixed n=14", flush=True)
+    assert_same(solve(ppo, w), oracle(w, 14, CO.subset_dp), "mixed n=14")
+    w = W.random_instances(5, 3, 128, 11, capacity_factor=3.0)
+    print("cluster L=128 n=11", flush=True)
+    assert_same(solve(ppo, w), oracle(w, 11, CO.subset_dp), "L=128 n=11")
+
+
+def test_cluster_batches_follow_the_workspace(ppo):
+    """A workspace sized for four instances solves seven in batches of three; results do not depend on it."""
+    w = W.cluster_mixed(9, L=60, n_inst=7, seed=3)
+    full = solve(ppo, w)
+    four = ppo.ppo_cluster_workspace_bytes(60, 9, 4)
+    assert ppo.ppo_cluster_workspace_bytes(60, 9, 1) < four < ppo.ppo_cluster_workspace_bytes(60, 9, 7)
+    print("cluster smaller workspace", flush=True)
+    batched = solve(ppo, w, workspace_bytes=four)
+    for a, b in zip(full, batched):
+        assert np.array_equal(a, b)
+    assert_same(full, oracle(w, 9, CO.subset_dp), "mixed n=9")
+    with pytest.raises(ppo.PpoError) as err:
+        solve(ppo, w, workspace_bytes=1 << 16)
+    assert err.value.code == ppo.PPO_ENOSPC
+
+
+def check_solution(w, i, got, pmax, rng, samples=300):
+    """What must hold at any size: the reported solution is feasible with exactly the reported bottleneck
+    (fixed-k evaluator on its nodes), and no other sequence tried does better or ties with a smaller one."""
+    beta, p, cuts, order = got[0][i], int(got[1][i]), got[2][i], got[3][i]
+    t, m, M, B = w.t[i], w.m[i], w.M[i], w.B[i]
+    n = w.k
+    assert 1 <= p <= pmax and list(order[p:]) == [-1] * (n - p) and list(cuts[p - 1:]) == [-1] * (n - p)
+    idx = order[:p]
+    assert len(set(idx.tolist())) == p
+    b, feas = O.evaluate(t, m, M[idx], B[np.ix_(idx, idx)], np.arange(p), cuts[:p - 1])
+    assert feas and bits(b) == bits(beta)
+    assert bits(CO.sequence_beta(t, m, M, B, idx)) == bits(beta)
+    mine = tuple(int(x) for x in idx)
+    for s in range(samples):
+        if s % 3 == 0:      # a random sequence
+            q = int(rng.integers(1, pmax + 1))
+            seq = rng.permutation(n)[:q]
+        elif s % 3 == 1:    # the solution with one node replaced
+            seq = idx.copy()
+            free = np.setdiff1d(np.arange(n), idx)
+            if free.size == 0:
+                continue
+            seq[int(rng.integers(0, p))] = int(rng.choice(free))
+        else:               # the solution with two nodes swapped, or its last node dropped
+            seq = idx.copy()
+            if p >= 2 and s % 2:
+                a, c = rng.choice(p, 2, replace=False)
+                seq[a], seq[c] = seq[c], seq[a]
+            elif p >= 2:
+                seq = seq[:-1]
+        other = bits(CO.sequence_beta(t, m, M, B, seq))
+        assert other >= bits(beta)
+        if other == bits(beta):
+            assert mine <= tuple(int(x) for x in seq)
+
+
+def test_cluster_of_twenty(ppo):
+    """n = 20: a million node sets per instance.  Exact against the oracle for up to three segments;
+    properties for the unrestricted search."""
+    rng = np.random.default_rng(20)
+    for w in (W.cluster_geometric(20, 32, n_inst=2), W.cluster_mixed(20, L=100, n_inst=1)):
+        print(f"cluster n=20 {w.name} pmax=3", flush=True)
+        three = solve(ppo, w, 3)
+        assert_same(three, oracle(w, 3, CO.exhaustive), f"{w.name} pmax=3")
+        print(f"cluster n=20 {w.name} unrestricted", flush=True)
+        full = solve(ppo, w)
+        for i in range(w.n_inst):
+            assert bits(full[0][i]) <= bits(three[0][i])
+            check_solution(w, i, full, 20, rng)
+        print(f"cluster n=20 {w.name} pmax=6", flush=True)
+        six = solve(ppo, w, 6)
+        for i in range(w.n_inst):
+            assert bits(full[0][i]) <= bits(six[0][i]) <= bits(three[0][i])
+            check_solution(w, i, six, 6, rng)
+
+
+def test_cluster_sixteen_against_the_oracle(ppo):
+    w = W.cluster_mixed(16, L=100, n_inst=1, seed=12)
+    print("cluster n=16 L=100", flush=True)
+    assert_same(solve(ppo, w), oracle(w, 16, CO.subset_dp), "mixed n=16")
