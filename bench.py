@@ -59,6 +59,36 @@ def algorithmic_ops_per_ordering(w):
 MEASURED_TRAFFIC_BYTES = {("headline", 104): 4.853e7}   # re-measure when the kernel changes
 
 
+def bench_cluster(args, torch, ppo, workloads):
+    """Not the headline: whole exact solves per second of the cluster form (ppo_solve_cluster)."""
+    N = args.cluster
+    n_inst = args.cluster_instances or (64 if N <= 12 else 8 if N <= 16 else 1)
+    pmax = args.max_segments or N
+    w = workloads.cluster_mixed(N, L=100, n_inst=n_inst)
+    dev = ppo.to_device(w)
+    ws = torch.empty(ppo.ppo_cluster_workspace_bytes(w.L, N, n_inst), dtype=torch.uint8, device="cuda:0")
+    out = None
+    for _ in range(args.warmup):
+        out = ppo.ppo_solve_cluster(*dev, max_segments=pmax, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = ppo.ppo_solve_cluster(*dev, max_segments=pmax, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rows = sum(math.comb(N, r) * r for r in range(N - pmax + 1, N + 1))
+    result = {
+        "metric": f"clusters solved exactly/sec at n={N},L={w.L}, up to {pmax} segments (dynamic programming over sets of unused nodes)",
+        "value": n_inst / (wall / args.steps), "unit": "instances/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {n_inst} instances x (L={w.L}, n={N}), seed={w.seed}",
+                   "dp_rows_per_instance": rows, "segments_found": [int(x) for x in out[1].cpu().numpy()[:8]]},
+        "roofline": None,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +102,11 @@ def main():
     ap.add_argument("--subsets", action="store_true",
                     help="time ppo_solve_subsets (dynamic programming over node subsets) instead of the "
                          "enumeration: a separate figure in instances per second")
+    ap.add_argument("--cluster", type=int, default=0, metavar="N",
+                    help="time ppo_solve_cluster on clusters of N nodes (hosting nodes and number of segments "
+                         "free; L=100, mixed capacities): a separate figure in instances per second")
+    ap.add_argument("--cluster-instances", type=int, default=0, help="instances per step with --cluster")
+    ap.add_argument("--max-segments", type=int, default=0, help="with --cluster: most segments allowed (default N)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes 256 MiB: the known "
                          "traffic the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -87,6 +122,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     ppo.load()
+    if args.cluster:
+        return bench_cluster(args, torch, ppo, workloads)
     w = workloads.WORKLOADS[args.workload]()
     L, k, n = w.L, w.k, w.n_inst
     kf = math.factorial(k)

@@ -20,14 +20,12 @@ namespace ppo {
 
 constexpr uint32_t kClZero = 0u, kClInf = 0xFFFFu;   // codes: 0 = value 0, 1 + #smaller quotients, 0xFFFF = +inf
 constexpr int kClPreThreads = 1024;
-constexpr int kClLevelWaves = 4;
 constexpr int kClRow = PPO_MAX_L + 2;
-static_assert((PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) <= 24 * kClPreThreads,
-              "quotients per thread of the tables kernel");
 static_assert((PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) + 1 < (int)kClInf, "codes fit 16 bits");
 
 struct ClusterLayout {
-    int L, n, npairs, nq, rs;                       // rs: entries per row of A (L+1 rounded up to even)
+    int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
+                                                    // and not stored), rounded up to even
     uint32_t hi_off, qc_off, dec_off, qv_off, stride;   // bytes within one instance's tables
 
     __host__ __device__ static ClusterLayout make(int L, int n) {
@@ -36,7 +34,7 @@ struct ClusterLayout {
         y.n = n;
         y.npairs = n * (n - 1) / 2;
         y.nq = y.npairs * (L - 1);
-        y.rs = (L + 2) & ~1;
+        y.rs = (L + 1) & ~1;
         size_t off = 0;
         y.hi_off = (uint32_t)off;
         off = align_up(off + (size_t)n * (L + 1), 16);
@@ -57,18 +55,15 @@ size_t cluster_rows_bytes(int L, int n) { return ClusterLayout::make(L, n).rows_
 
 // ---------------------------------------------------------------------------------------------
 // Tables of one instance: hi[j][e] = last e' such that layers [e, e') fit node j (e if none; the memory
-// rule with binary64 prefix sums), the quotients of Eq. 3 and their order codes.
-// R = quotients per thread (nq <= R * kClPreThreads).
+// rule with binary64 prefix sums) and the quotients of Eq. 3; then, in a second kernel over slices of
+// the quotients, their order codes (1 + the number of strictly smaller quotients of the instance).
 // ---------------------------------------------------------------------------------------------
-template <int R>
 __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const float* __restrict__ t,
                                                                       const float* __restrict__ m,
                                                                       const float* __restrict__ M,
                                                                       const float* __restrict__ B, ClusterLayout y,
                                                                       unsigned char* __restrict__ ws) {
-    constexpr int kTile = 4096;
     __shared__ double P[PPO_MAX_L + 1];
-    __shared__ float tile[kTile];
     const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
     const float* ti = t + (size_t)inst * L;
     const float* mi = m + (size_t)inst * L;
@@ -76,7 +71,6 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
     const float* Bi = B + (size_t)inst * n * n;
     unsigned char* base = ws + (size_t)inst * y.stride;
     unsigned char* hi = base + y.hi_off;
-    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
     float* dec = reinterpret_cast<float*>(base + y.dec_off);
     float* qv = reinterpret_cast<float*>(base + y.qv_off);
     if (tid == 0) {
@@ -86,6 +80,7 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
             acc = acc + (double)mi[i];
             P[i + 1] = acc;
         }
+        dec[0] = 0.0f;
     }
     __syncthreads();
     for (int idx = tid; idx < n * (L + 1); idx += kClPreThreads) {
@@ -95,45 +90,39 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
         while (e2 < L && (P[e2 + 1] - P[e]) <= cap) ++e2;
         hi[idx] = (unsigned char)e2;
     }
-    const int nq = y.nq;
-    float x[R];
-    int below[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int idx = tid + r * kClPreThreads;
-        x[r] = 0.0f;
-        below[r] = 0;
-        if (idx < nq) {
-            const int p = idx / (L - 1), i = idx - p * (L - 1);
-            int a = 0, rem = p;
-            while (rem >= n - 1 - a) { rem -= n - 1 - a; ++a; }
-            const int b = a + 1 + rem;
-            x[r] = __fdiv_rn(ti[i], Bi[a * n + b]);
-            qv[idx] = x[r];
-        }
+    for (int idx = tid; idx < y.nq; idx += kClPreThreads) {
+        const int p = idx / (L - 1), i = idx - p * (L - 1);
+        int a = 0, rem = p;
+        while (rem >= n - 1 - a) { rem -= n - 1 - a; ++a; }
+        const int b = a + 1 + rem;
+        qv[idx] = __fdiv_rn(ti[i], Bi[a * n + b]);
     }
-    __syncthreads();   // qv of the whole instance written (global, one workgroup)
+}
+
+// grid.x slices of kClPreThreads quotients, grid.y = instance
+__global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
+    constexpr int kTile = 4096;
+    __shared__ float tile[kTile];
+    const int L = y.L, nq = y.nq, inst = blockIdx.y, tid = threadIdx.x;
+    unsigned char* base = ws + (size_t)inst * y.stride;
+    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
+    float* dec = reinterpret_cast<float*>(base + y.dec_off);
+    const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
+    const int idx = blockIdx.x * kClPreThreads + tid;
+    const float x = idx < nq ? qv[idx] : 0.0f;
+    int below = 0;
     for (int first = 0; first < nq; first += kTile) {
         const int len = nq - first < kTile ? nq - first : kTile;
         __syncthreads();
         for (int j = tid; j < len; j += kClPreThreads) tile[j] = qv[first + j];
         __syncthreads();
-        for (int j = 0; j < len; ++j) {
-            const float v = tile[j];
-#pragma unroll
-            for (int r = 0; r < R; ++r) below[r] += (v < x[r]) ? 1 : 0;
-        }
+        for (int j = 0; j < len; ++j) below += (tile[j] < x) ? 1 : 0;
     }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int idx = tid + r * kClPreThreads;
-        if (idx < nq) {
-            const int p = idx / (L - 1), i = idx - p * (L - 1);
-            qc[p * L + i] = (uint16_t)(1 + below[r]);
-            dec[1 + below[r]] = x[r];
-        }
+    if (idx < nq) {
+        const int p = idx / (L - 1), i = idx - p * (L - 1);
+        qc[p * L + i] = (uint16_t)(1 + below);
+        dec[1 + below] = x;
     }
-    if (tid == 0) dec[0] = 0.0f;
 }
 
 // rest[R'][j][e'] for e' = lane, lane + 64, ... <= L into `out` (one wave).  A: rows of the instance.
@@ -159,45 +148,150 @@ __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const u
 }
 
 // ---------------------------------------------------------------------------------------------
-// One level: every row A[R][j] with |R| = level.  grid.x waves share the masks, grid.y = instance.
+// One level: every row A[R][j] with |R| = level.  The unit of work of a wave is a set R' with |R'| =
+// level - 1: it loads the rows A[R'][j''] once (two entries per lane) and produces A[R' + j][j] for every
+// j outside R'.  For each j: the `rest` row (quotients from a copy of the table in LDS, shifted so that
+// entry e holds q[e-1]), then a table of minima over runs of 1, 2, 4 .. 64 entries of it in LDS, from which
+// the minimum over the window (e, hi[j][e]] is two reads.  grid.x waves share the sets, grid.y = instance.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kClLevelWaves * 64) void cluster_level_kernel(ClusterLayout y,
-                                                                          const unsigned char* __restrict__ ws,
-                                                                          uint16_t* __restrict__ rows, int level,
-                                                                          int pmax) {
-    __shared__ unsigned char hi_s[PPO_CLUSTER_MAX_N * (PPO_MAX_L + 1)];
-    __shared__ uint16_t rest_s[kClLevelWaves][kClRow];
-    const int L = y.L, n = y.n, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+constexpr int kClWaves = 8;        // waves per workgroup of the level kernel
+constexpr int kClRunLevels = 7;    // runs of 2^0 .. 2^6 entries
+constexpr int kClRunRow = 192;     // entries per run-minimum row: 128 computed per set, the rest constant
+constexpr int kClHiRow = 130;      // bytes per node of the window table in LDS (entries above L read 0)
+
+typedef unsigned short cl_ushort2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cl_pk_min(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(cl_ushort2, a), __builtin_bit_cast(cl_ushort2, b)));
+}
+__device__ __forceinline__ uint32_t cl_pk_max(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(cl_ushort2, a), __builtin_bit_cast(cl_ushort2, b)));
+}
+
+// Binomial coefficients C(i, j), i, j <= PPO_CLUSTER_MAX_N, and the set of a given size with a given index:
+// sets of c nodes are numbered by sum over their members b_c > ... > b_1 of C(b_i, i) (the combinatorial
+// number system), so that the sets of one level can be dealt out evenly to the waves.
+struct ClusterBinomials {
+    uint32_t c[PPO_CLUSTER_MAX_N + 1][PPO_CLUSTER_MAX_N + 1];
+    constexpr ClusterBinomials() : c{} {
+        for (int i = 0; i <= PPO_CLUSTER_MAX_N; ++i) {
+            c[i][0] = 1;
+            for (int j = 1; j <= i; ++j) c[i][j] = c[i - 1][j - 1] + (j <= i - 1 ? c[i - 1][j] : 0u);
+        }
+    }
+};
+constexpr ClusterBinomials kClBinomialsHost = ClusterBinomials();
+__constant__ ClusterBinomials kClBinomials = ClusterBinomials();
+
+__device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int n) {
+    uint32_t set = 0;
+    int b = n;
+    for (int i = size; i >= 1; --i) {
+        do { --b; } while (kClBinomials.c[b][i] > index);
+        set |= 1u << b;
+        index -= kClBinomials.c[b][i];
+    }
+    return set;
+}
+
+struct ClusterLds {
+    uint32_t q_bytes, hi_off, run_off, total;
+    __host__ __device__ static ClusterLds make(const ClusterLayout& y) {
+        ClusterLds s;
+        s.q_bytes = (uint32_t)align_up((size_t)y.npairs * y.rs * 2, 16);
+        s.hi_off = s.q_bytes;
+        s.run_off = (uint32_t)align_up((size_t)s.hi_off + (size_t)y.n * kClHiRow, 16);
+        s.total = s.run_off + kClWaves * kClRunLevels * kClRunRow * 2;
+        return s;
+    }
+};
+
+__global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLayout y,
+                                                                     const unsigned char* __restrict__ ws,
+                                                                     uint16_t* __restrict__ rows, int level,
+                                                                     int pmax) {
+    extern __shared__ __align__(16) unsigned char cl_smem[];
+    const int L = y.L, n = y.n, rs = y.rs, rd = y.rs / 2;
+    const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const ClusterLds lds = ClusterLds::make(y);
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
-    uint16_t* A = rows + (size_t)inst * (((size_t)n << n) * y.rs);
-    for (int i = tid; i < n * (L + 1); i += kClLevelWaves * 64) hi_s[i] = base[y.hi_off + i];
+    uint16_t* q16 = reinterpret_cast<uint16_t*>(cl_smem);
+    const uint32_t* q32 = reinterpret_cast<const uint32_t*>(cl_smem);
+    unsigned char* hi_s = cl_smem + lds.hi_off;
+    uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
+    uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (((size_t)n << n) * rd);
+    // entry e of a quotient row in LDS: q[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
+    for (int i = tid; i < y.npairs * rs; i += kClWaves * 64) {
+        const int p = i / rs, e = i - p * rs;
+        q16[i] = (uint16_t)((e >= 1 && e <= L - 1) ? qc[p * L + e - 1] : kClInf);
+    }
+    for (int i = tid; i < n * kClHiRow; i += kClWaves * 64) {
+        const int j = i / kClHiRow, e = i - j * kClHiRow;
+        hi_s[i] = e <= L ? base[y.hi_off + j * (L + 1) + e] : (unsigned char)0;
+    }
+    // entries 128.. of the run-minimum rows never change: rest[L] = 0 if L = 128, +inf beyond the chain
+    for (int i = lane; i < kClRunLevels * (kClRunRow - 128); i += 64) {
+        const int k = i / (kClRunRow - 128), e = 128 + i % (kClRunRow - 128);
+        run[k * kClRunRow + e] = (uint16_t)(e == L ? kClZero : kClInf);
+    }
     __syncthreads();
     const bool more = n - level + 1 < pmax;   // segments up to and including this row's: n - level + 1
-    const uint32_t nmask = 1u << n;
-    const uint32_t stride = gridDim.x * kClLevelWaves;
-    uint16_t* rest = rest_s[wave];
-    uint32_t mask = blockIdx.x * kClLevelWaves + wave;
-    if (level == n) mask = mask == 0u ? nmask - 1u : nmask;   // the one set of this level goes to the first wave
-    for (; mask < nmask; mask += stride) {
-        if (__popc(mask) != level) continue;
-        for (uint32_t jb = mask; jb; jb &= jb - 1u) {
+    const uint32_t inf2 = kClInf | (kClInf << 16);
+    const uint32_t all = (1u << n) - 1u;
+    const int e0 = 2 * lane, e1 = e0 + 1;
+    const uint32_t end_mask = (e0 == L ? 0u : 0xFFFFu) | (e1 == L ? 0u : 0xFFFF0000u);   // rest[L] = 0
+    const uint32_t after_last = L == 128 ? kClZero : kClInf;                             // entry 128 of rest
+    const int lq = lane < rd ? lane : rd - 1;
+    uint32_t* run32 = reinterpret_cast<uint32_t*>(run);
+    const uint32_t nsets = kClBinomials.c[n][level - 1];
+    const uint32_t stride = gridDim.x * kClWaves;
+    for (uint32_t u = blockIdx.x * kClWaves + wave; u < nsets; u += stride) {
+        const uint32_t mp = cluster_set_at(u, level - 1, n);
+        uint32_t a[PPO_CLUSTER_MAX_N];
+#pragma unroll
+        for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
+            a[j2] = inf2;
+            if (more && j2 < n && ((mp >> j2) & 1u) && lane < rd) a[j2] = A32[((size_t)mp * n + j2) * rd + lane];
+        }
+        for (uint32_t jb = all & ~mp; jb; jb &= jb - 1u) {
             const int j = __ffs(jb) - 1;
-            cluster_rest_row(y, qc, A, mask & ~(1u << j), j, more, lane, rest);
+            uint32_t v = inf2;
+            if (more) {
+#pragma unroll
+                for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2)
+                    if (j2 < n && ((mp >> j2) & 1u)) v = cl_pk_min(v, cl_pk_max(q32[pair_index(j, j2, n) * rd + lq], a[j2]));
+            }
+            v &= end_mask;
+            // minima over runs of 2^k entries starting at each entry
+            run32[lane] = v;
+            uint32_t next = (uint32_t)__shfl_down((int)v, 1, 64);
+            if (lane == 63) next = after_last;
+            uint32_t cur = cl_pk_min(v, (v >> 16) | (next << 16));
+            run32[(kClRunRow / 2) + lane] = cur;
+#pragma unroll
+            for (int k = 2; k < kClRunLevels; ++k) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                cur = cl_pk_min(cur, run32[(k - 1) * (kClRunRow / 2) + lane + (1 << (k - 2))]);
+                run32[k * (kClRunRow / 2) + lane] = cur;
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            uint16_t* out = A + ((size_t)mask * n + j) * y.rs;
-            for (int e = lane; e <= L; e += 64) {
-                uint32_t v = kClInf;
-                if (e < L) {
-                    const int h = hi_s[j * (L + 1) + e];
-                    for (int e2 = e + 1; e2 <= h; ++e2) {
-                        const uint32_t r = rest[e2];
-                        v = r < v ? r : v;
-                    }
+            const uint32_t hh = *reinterpret_cast<const uint16_t*>(hi_s + j * kClHiRow + e0);
+            uint32_t res[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e = e0 + h, top = (int)((hh >> (8 * h)) & 0xFFu);
+                uint32_t r = kClInf;
+                if (top > e) {   // entries at and above L have top = 0
+                    int k = 31 - __clz(top - e);
+                    k = k > kClRunLevels - 1 ? kClRunLevels - 1 : k;
+                    const uint32_t r1 = run[k * kClRunRow + e + 1], r2 = run[k * kClRunRow + top - (1 << k) + 1];
+                    r = r1 < r2 ? r1 : r2;
                 }
-                out[e] = (uint16_t)v;
+                res[h] = r;
             }
+            if (lane < rd) A32[((size_t)(mp | (1u << j)) * n + j) * rd + lane] = res[0] | (res[1] << 16);
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -315,10 +409,11 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
                                  int n_inst, void* ws, hipStream_t stream) {
     const ClusterLayout y = ClusterLayout::make(L, n);
     unsigned char* w = static_cast<unsigned char*>(ws);
-    if (y.nq <= 8 * kClPreThreads)
-        hipLaunchKernelGGL(cluster_tables_kernel<8>, dim3(n_inst), dim3(kClPreThreads), 0, stream, t, m, M, B, y, w);
-    else
-        hipLaunchKernelGGL(cluster_tables_kernel<24>, dim3(n_inst), dim3(kClPreThreads), 0, stream, t, m, M, B, y, w);
+    hipLaunchKernelGGL(cluster_tables_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, t, m, M, B, y, w);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || y.nq == 0) return e;
+    hipLaunchKernelGGL(cluster_codes_kernel, dim3((y.nq + kClPreThreads - 1) / kClPreThreads, n_inst), dim3(kClPreThreads),
+                       0, stream, y, w);
     return hipGetLastError();
 }
 
@@ -328,14 +423,16 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, const void* 
     const ClusterLayout y = ClusterLayout::make(L, n);
     const unsigned char* w = static_cast<const unsigned char*>(ws);
     uint16_t* r = static_cast<uint16_t*>(rows);
-    const uint32_t nmask = 1u << n;
-    uint32_t blocks = nmask / (kClLevelWaves * 4u);
-    if (blocks < 1u) blocks = 1u;
-    if (blocks > 2048u) blocks = 2048u;
+    const ClusterLds lds = ClusterLds::make(y);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_level_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds.total);
+    if (e != hipSuccess) return e;
     for (int level = n - pmax + 1; level <= n; ++level) {
-        hipLaunchKernelGGL(cluster_level_kernel, dim3(level == n ? 1u : blocks, n_inst), dim3(kClLevelWaves * 64), 0,
-                           stream, y, w, r, level, pmax);
-        const hipError_t e = hipGetLastError();
+        uint32_t blocks = (kClBinomialsHost.c[n][level - 1] + kClWaves - 1u) / kClWaves;   // a set per wave, at most
+        if (blocks > 2048u) blocks = 2048u;
+        hipLaunchKernelGGL(cluster_level_kernel, dim3(blocks, n_inst), dim3(kClWaves * 64), lds.total, stream, y, w, r,
+                           level, pmax);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(64), 0, stream, y, w, r, pmax, beta_out, segs_out,
