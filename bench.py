@@ -77,6 +77,10 @@ def bench_cluster(args, torch, ppo, workloads):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     rows = sum(math.comb(N, r) * r for r in range(N - pmax + 1, N + 1))
+    # every DP row (L 16-bit entries, rounded up to even) is written once and has to be read at least once
+    row_bytes = 2 * ((w.L + 1) & ~1)
+    alg_bytes = 2 * rows * row_bytes * n_inst
+    achieved = alg_bytes / (wall / args.steps) / 1e9
     result = {
         "metric": f"clusters solved exactly/sec at n={N},L={w.L}, up to {pmax} segments (dynamic programming over sets of unused nodes)",
         "value": n_inst / (wall / args.steps), "unit": "instances/s", "n_gpus": 1, "steps": args.steps,
@@ -84,7 +88,10 @@ def bench_cluster(args, torch, ppo, workloads):
         "vs_baseline": None, "dtype": "u16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {n_inst} instances x (L={w.L}, n={N}), seed={w.seed}",
                    "dp_rows_per_instance": rows, "segments_found": [int(x) for x in out[1].cpu().numpy()[:8]]},
-        "roofline": None,
+        # against the whole call (tables, one launch per level, trace), not the level kernel alone
+        "roofline": {"bound": "hbm", "kernel": "cluster_level_kernel (all levels) + tables + trace",
+                     "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0, "traffic": None,
+                     "bytes_per_step": alg_bytes},
     }
     print(json.dumps(result), flush=True)
 

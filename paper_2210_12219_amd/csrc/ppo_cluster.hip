@@ -102,7 +102,8 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
 // grid.x slices of kClPreThreads quotients, grid.y = instance
 __global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
     constexpr int kTile = 4096;
-    __shared__ float tile[kTile];
+    __shared__ float4 tile4[kTile / 4];
+    float* tile = reinterpret_cast<float*>(tile4);
     const int L = y.L, nq = y.nq, inst = blockIdx.y, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
     uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
@@ -114,9 +115,12 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLay
     for (int first = 0; first < nq; first += kTile) {
         const int len = nq - first < kTile ? nq - first : kTile;
         __syncthreads();
-        for (int j = tid; j < len; j += kClPreThreads) tile[j] = qv[first + j];
+        for (int j = tid; j < kTile; j += kClPreThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
         __syncthreads();
-        for (int j = 0; j < len; ++j) below += (tile[j] < x) ? 1 : 0;
+        for (int j = 0; j < (len + 3) / 4; ++j) {   // the padding (+inf) is below nothing
+            const float4 v = tile4[j];
+            below += (v.x < x ? 1 : 0) + (v.y < x ? 1 : 0) + (v.z < x ? 1 : 0) + (v.w < x ? 1 : 0);
+        }
     }
     if (idx < nq) {
         const int p = idx / (L - 1), i = idx - p * (L - 1);
@@ -298,18 +302,26 @@ __global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLay
 }
 
 // ---------------------------------------------------------------------------------------------
-// The optimum, the smallest optimal sequence and its cuts: one wave per instance.
+// The optimum, the smallest optimal sequence and its cuts: one workgroup per instance.  At each position
+// the candidates for the next node are tried side by side, one wave each; the smallest node whose best
+// completion still equals the optimum is taken.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, const unsigned char* __restrict__ ws,
-                                                           const uint16_t* __restrict__ rows, int pmax,
-                                                           float* __restrict__ beta_out, int32_t* __restrict__ segs_out,
-                                                           int32_t* __restrict__ cuts_out,
-                                                           int32_t* __restrict__ order_out) {
+constexpr int kClTraceWaves = 16;
+
+__global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(ClusterLayout y,
+                                                                          const unsigned char* __restrict__ ws,
+                                                                          const uint16_t* __restrict__ rows, int pmax,
+                                                                          float* __restrict__ beta_out,
+                                                                          int32_t* __restrict__ segs_out,
+                                                                          int32_t* __restrict__ cuts_out,
+                                                                          int32_t* __restrict__ order_out) {
     __shared__ unsigned char hi_s[PPO_CLUSTER_MAX_N * (PPO_MAX_L + 1)];
-    __shared__ uint16_t D[PPO_CLUSTER_MAX_N][kClRow];   // forward rows of the chosen prefix
-    __shared__ uint16_t rest[kClRow];
+    __shared__ uint16_t D[PPO_CLUSTER_MAX_N][kClRow];      // forward rows of the chosen prefix
+    __shared__ uint16_t cand[PPO_CLUSTER_MAX_N][kClRow];   // forward row of the prefix extended by node j
+    __shared__ uint16_t rest_s[kClTraceWaves][kClRow];
+    __shared__ uint32_t comp[PPO_CLUSTER_MAX_N];           // least bottleneck over the completions of prefix + j
     __shared__ int seq[PPO_CLUSTER_MAX_N];
-    const int L = y.L, n = y.n, inst = blockIdx.x, lane = threadIdx.x;
+    const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
@@ -317,9 +329,9 @@ __global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, cons
     float* beta = beta_out + inst;
     int32_t* order = order_out + (size_t)inst * n;
     int32_t* cuts = cuts_out ? cuts_out + (size_t)inst * (n - 1) : nullptr;
-    for (int i = lane; i < n * (L + 1); i += 64) hi_s[i] = base[y.hi_off + i];
-    for (int i = lane; i < n; i += 64) order[i] = -1;
-    for (int i = lane; i < n - 1; i += 64) cuts[i] = -1;
+    for (int i = tid; i < n * (L + 1); i += kClTraceWaves * 64) hi_s[i] = base[y.hi_off + i];
+    for (int i = tid; i < n; i += kClTraceWaves * 64) order[i] = -1;
+    for (int i = tid; i < n - 1; i += kClTraceWaves * 64) cuts[i] = -1;
     __syncthreads();
     auto wave_min = [&](uint32_t v) -> uint32_t {
         for (int off = 32; off >= 1; off >>= 1) {
@@ -330,9 +342,10 @@ __global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, cons
     };
     auto hi = [&](int j, int e) -> int { return hi_s[j * (L + 1) + e]; };
     const uint32_t all = (1u << n) - 1u;
+    // every wave takes the minimum itself: the same value in all of them
     const uint32_t best = wave_min(lane < n ? (uint32_t)A[((size_t)all * n + lane) * y.rs] : kClInf);
     if (best >= kClInf) {
-        if (lane == 0) {
+        if (tid == 0) {
             *beta = __uint_as_float(kInfBits);
             segs_out[inst] = 0;
         }
@@ -341,10 +354,12 @@ __global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, cons
     uint32_t used = 0;
     int last = -1, p = 0;
     for (int s = 0; s < pmax; ++s) {
-        int chosen = -1;
-        uint16_t* f2 = D[s];
-        for (int j = 0; j < n && chosen < 0; ++j) {
-            if ((used >> j) & 1u) continue;
+        for (int j = wave; j < n; j += kClTraceWaves) {
+            if ((used >> j) & 1u) {
+                if (lane == 0) comp[j] = 0xFFFFFFFFu;
+                continue;
+            }
+            uint16_t* f2 = cand[j];
             if (s == 0) {
                 for (int e = lane; e <= L; e += 64) f2[e] = (uint16_t)((e >= 1 && e <= hi(j, 0)) ? kClZero : kClInf);
             } else {
@@ -361,6 +376,7 @@ __global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, cons
                     f2[e2] = (uint16_t)v;
                 }
             }
+            uint16_t* rest = rest_s[wave];
             cluster_rest_row(y, qc, A, all & ~used & ~(1u << j), j, s + 1 < pmax, lane, rest);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -370,18 +386,25 @@ __global__ __launch_bounds__(64) void cluster_trace_kernel(ClusterLayout y, cons
                 const uint32_t c = a > b ? a : b;
                 v = (e >= 1 && c < v) ? c : v;
             }
+            v = wave_min(v);
+            if (lane == 0) comp[j] = v;
             __builtin_amdgcn_wave_barrier();
-            if (wave_min(v) == best) chosen = j;
         }
+        __syncthreads();
+        int chosen = -1;
+        for (int j = n - 1; j >= 0; --j)
+            if (comp[j] == best) chosen = j;
         if (chosen < 0) break;   // cannot happen: some completion of the prefix reaches `best`
-        if (lane == 0) seq[s] = chosen;
+        for (int e = tid; e <= L; e += kClTraceWaves * 64) D[s][e] = cand[chosen][e];
+        if (tid == 0) seq[s] = chosen;
+        const bool complete = cand[chosen][L] <= best;   // the prefix itself is optimal: it sorts before its extensions
+        __syncthreads();
         used |= 1u << chosen;
         last = chosen;
         p = s + 1;
-        if (f2[L] <= best) break;   // the prefix itself is optimal: it sorts before all its extensions
+        if (complete) break;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    if (wave != 0) return;
     // cuts: latest segment first, each time the smallest cut that keeps the bottleneck at `best`
     int e = L;
     for (int s = p - 1; s >= 1; --s) {
@@ -435,7 +458,7 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, const void* 
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(64), 0, stream, y, w, r, pmax, beta_out, segs_out,
+    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(kClTraceWaves * 64), 0, stream, y, w, r, pmax, beta_out, segs_out,
                        cuts_out, order_out);
     return hipGetLastError();
 }
