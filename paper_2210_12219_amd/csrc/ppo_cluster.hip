@@ -158,7 +158,6 @@ __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const u
 // entry e holds q[e-1]), then a table of minima over runs of 1, 2, 4 .. 64 entries of it in LDS, from which
 // the minimum over the window (e, hi[j][e]] is two reads.  grid.x waves share the sets, grid.y = instance.
 // ---------------------------------------------------------------------------------------------
-constexpr int kClWaves = 8;        // waves per workgroup of the level kernel
 constexpr int kClRunLevels = 7;    // runs of 2^0 .. 2^6 entries
 constexpr int kClRunRow = 192;     // entries per run-minimum row: 128 computed per set, the rest constant
 constexpr int kClHiRow = 130;      // bytes per node of the window table in LDS (entries above L read 0)
@@ -197,26 +196,36 @@ __device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int
     return set;
 }
 
+// LDS of the level kernel: the quotient rows of every ORDERED pair of nodes, 64 dwords each (so that the row
+// of (j, j'') is a fixed distance j'' * 256 bytes from the row of (j, 0)), the window table, and the
+// run-minimum tables of each wave.
 struct ClusterLds {
-    uint32_t q_bytes, hi_off, run_off, total;
-    __host__ __device__ static ClusterLds make(const ClusterLayout& y) {
+    uint32_t hi_off, run_off, total;
+    int waves;
+    __host__ __device__ static ClusterLds make(const ClusterLayout& y, int waves) {
         ClusterLds s;
-        s.q_bytes = (uint32_t)align_up((size_t)y.npairs * y.rs * 2, 16);
-        s.hi_off = s.q_bytes;
+        s.waves = waves;
+        s.hi_off = (uint32_t)y.n * (uint32_t)y.n * 256u;
         s.run_off = (uint32_t)align_up((size_t)s.hi_off + (size_t)y.n * kClHiRow, 16);
-        s.total = s.run_off + kClWaves * kClRunLevels * kClRunRow * 2;
+        s.total = s.run_off + (uint32_t)waves * kClRunLevels * kClRunRow * 2;
         return s;
+    }
+    // 8 waves per workgroup while two workgroups fit a compute unit's 160 KB, else 16
+    __host__ static ClusterLds choose(const ClusterLayout& y) {
+        const ClusterLds s = make(y, 8);
+        return 2u * s.total <= 160u * 1024u ? s : make(y, 16);
     }
 };
 
-__global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLayout y,
+__global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                                                                      const unsigned char* __restrict__ ws,
                                                                      uint16_t* __restrict__ rows, int level,
                                                                      int pmax) {
     extern __shared__ __align__(16) unsigned char cl_smem[];
-    const int L = y.L, n = y.n, rs = y.rs, rd = y.rs / 2;
+    const int L = y.L, n = y.n, rd = y.rs / 2;
     const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const ClusterLds lds = ClusterLds::make(y);
+    const int threads = blockDim.x, waves = threads >> 6;
+    const ClusterLds lds = ClusterLds::make(y, waves);
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     uint16_t* q16 = reinterpret_cast<uint16_t*>(cl_smem);
@@ -224,12 +233,12 @@ __global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLay
     unsigned char* hi_s = cl_smem + lds.hi_off;
     uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
     uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (((size_t)n << n) * rd);
-    // entry e of a quotient row in LDS: q[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
-    for (int i = tid; i < y.npairs * rs; i += kClWaves * 64) {
-        const int p = i / rs, e = i - p * rs;
-        q16[i] = (uint16_t)((e >= 1 && e <= L - 1) ? qc[p * L + e - 1] : kClInf);
+    // entry e of the row of (j, j''): q_{j,j''}[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
+    for (int i = tid; i < n * n * 128; i += threads) {
+        const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
+        q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
     }
-    for (int i = tid; i < n * kClHiRow; i += kClWaves * 64) {
+    for (int i = tid; i < n * kClHiRow; i += threads) {
         const int j = i / kClHiRow, e = i - j * kClHiRow;
         hi_s[i] = e <= L ? base[y.hi_off + j * (L + 1) + e] : (unsigned char)0;
     }
@@ -245,11 +254,10 @@ __global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLay
     const int e0 = 2 * lane, e1 = e0 + 1;
     const uint32_t end_mask = (e0 == L ? 0u : 0xFFFFu) | (e1 == L ? 0u : 0xFFFF0000u);   // rest[L] = 0
     const uint32_t after_last = L == 128 ? kClZero : kClInf;                             // entry 128 of rest
-    const int lq = lane < rd ? lane : rd - 1;
     uint32_t* run32 = reinterpret_cast<uint32_t*>(run);
     const uint32_t nsets = kClBinomials.c[n][level - 1];
-    const uint32_t stride = gridDim.x * kClWaves;
-    for (uint32_t u = blockIdx.x * kClWaves + wave; u < nsets; u += stride) {
+    const uint32_t stride = gridDim.x * waves;
+    for (uint32_t u = blockIdx.x * waves + wave; u < nsets; u += stride) {
         const uint32_t mp = cluster_set_at(u, level - 1, n);
         uint32_t a[PPO_CLUSTER_MAX_N];
 #pragma unroll
@@ -261,9 +269,10 @@ __global__ __launch_bounds__(kClWaves * 64) void cluster_level_kernel(ClusterLay
             const int j = __ffs(jb) - 1;
             uint32_t v = inf2;
             if (more) {
+                const uint32_t* qj = q32 + (j * n) * 64 + lane;
 #pragma unroll
                 for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2)
-                    if (j2 < n && ((mp >> j2) & 1u)) v = cl_pk_min(v, cl_pk_max(q32[pair_index(j, j2, n) * rd + lq], a[j2]));
+                    if (j2 < n && ((mp >> j2) & 1u)) v = cl_pk_min(v, cl_pk_max(qj[j2 * 64], a[j2]));
             }
             v &= end_mask;
             // minima over runs of 2^k entries starting at each entry
@@ -446,14 +455,18 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, const void* 
     const ClusterLayout y = ClusterLayout::make(L, n);
     const unsigned char* w = static_cast<const unsigned char*>(ws);
     uint16_t* r = static_cast<uint16_t*>(rows);
-    const ClusterLds lds = ClusterLds::make(y);
+    const ClusterLds lds = ClusterLds::choose(y);
+    const uint32_t per_cu = (160u * 1024u) / lds.total;   // workgroups a compute unit holds: 1 or 2 (or more for small n)
+    const uint32_t resident = 256u * (per_cu < 1u ? 1u : per_cu > 4u ? 4u : per_cu);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_level_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds.total);
     if (e != hipSuccess) return e;
     for (int level = n - pmax + 1; level <= n; ++level) {
-        uint32_t blocks = (kClBinomialsHost.c[n][level - 1] + kClWaves - 1u) / kClWaves;   // a set per wave, at most
-        if (blocks > 2048u) blocks = 2048u;
-        hipLaunchKernelGGL(cluster_level_kernel, dim3(blocks, n_inst), dim3(kClWaves * 64), lds.total, stream, y, w, r,
+        // a set per wave at most; no more workgroups than stay resident (each stages the quotient table once)
+        uint32_t blocks = (kClBinomialsHost.c[n][level - 1] + (uint32_t)lds.waves - 1u) / (uint32_t)lds.waves;
+        const uint32_t cap = (resident + (uint32_t)n_inst - 1u) / (uint32_t)n_inst;
+        if (blocks > cap) blocks = cap;
+        hipLaunchKernelGGL(cluster_level_kernel, dim3(blocks, n_inst), dim3(lds.waves * 64), lds.total, stream, y, w, r,
                            level, pmax);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
