@@ -223,7 +223,8 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                                                                      int pmax) {
     extern __shared__ __align__(16) unsigned char cl_smem[];
     const int L = y.L, n = y.n, rd = y.rs / 2;
-    const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: keeps the set in scalar registers
     const int threads = blockDim.x, waves = threads >> 6;
     const ClusterLds lds = ClusterLds::make(y, waves);
     const unsigned char* base = ws + (size_t)inst * y.stride;
@@ -260,10 +261,11 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     for (uint32_t u = blockIdx.x * waves + wave; u < nsets; u += stride) {
         const uint32_t mp = cluster_set_at(u, level - 1, n);
         uint32_t a[PPO_CLUSTER_MAX_N];
+        const uint32_t* arow = A32 + (size_t)mp * n * rd + lane;
 #pragma unroll
         for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
             a[j2] = inf2;
-            if (more && j2 < n && ((mp >> j2) & 1u) && lane < rd) a[j2] = A32[((size_t)mp * n + j2) * rd + lane];
+            if (more && j2 < n && ((mp >> j2) & 1u) && lane < rd) a[j2] = arow[j2 * rd];
         }
         for (uint32_t jb = all & ~mp; jb; jb &= jb - 1u) {
             const int j = __ffs(jb) - 1;
@@ -330,7 +332,8 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     __shared__ uint16_t rest_s[kClTraceWaves][kClRow];
     __shared__ uint32_t comp[PPO_CLUSTER_MAX_N];           // least bottleneck over the completions of prefix + j
     __shared__ int seq[PPO_CLUSTER_MAX_N];
-    const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
