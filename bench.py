@@ -223,7 +223,7 @@ def main():
         from oracle import ppo_oracle
         threads = ppo_oracle.default_threads()
         n_s = min(n, 16)
-        span = min(kf, 100000 * threads // n_s + 1)
+        span = min(kf, 1600000 * threads // n_s + 1)   # about 15 s of the oracle on every host thread
         s = w.take(n_s)
         ppo_oracle.lib()
         c0 = time.perf_counter()
