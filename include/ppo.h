@@ -156,7 +156,7 @@ int ppo_eval_orderings(const float *t, const float *m, int L, const float *M, co
  * devices).  The exact counterpart: over every number of segments p, 1 <= p <= min(max_segments, L),
  * every sequence of p DISTINCT nodes out of the n of the cluster and every cut vector, the minimum of
  * beta (Eq. 2, Eq. 3; memory rule and arithmetic as stated at the top).  Found by dynamic programming over
- * the sets of nodes not yet used: n 2^n rows of L 16-bit entries per instance, level by level.
+ * the sets of nodes not yet used: n 2^(n-1) rows of L 16-bit entries per instance, level by level.
  *   t, m [n_inst][L]   M [n_inst][n]   B [n_inst][n][n]      1 <= n <= PPO_CLUSTER_MAX_N, L <= PPO_MAX_L;
  *                                                            n may exceed L
  *   max_segments       1..n
@@ -170,7 +170,7 @@ int ppo_eval_orderings(const float *t, const float *m, int L, const float *M, co
  * tables of all instances and the DP rows of as many instances as fit (they are solved that many at a
  * time), so a larger workspace runs more instances per launch.  ppo_cluster_workspace_bytes(L, n, n_inst)
  * is the size at which all n_inst run together, capped at 16 GiB of rows (but never below one instance's:
- * 4.2 GB at n = 20, L = 100).  Returns 0 on a bad shape. */
+ * 2.1 GB at n = 20, L = 100).  Returns 0 on a bad shape. */
 size_t ppo_cluster_workspace_bytes(int L, int n, int n_inst);
 int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, const float *B, int n, int n_inst,
                       int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,

@@ -34,6 +34,9 @@ def load() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2210_12219_amd.build` first")
+        # PyTorch ships its own HIP runtime; it has to be in the process before libppo.so is, so that both
+        # use the same one (tensors' device pointers mean nothing to a second runtime).
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
         inst = [vp, vp, i, vp, vp, i]

@@ -47,8 +47,35 @@ struct ClusterLayout {
         y.stride = (uint32_t)off;
         return y;
     }
-    __host__ __device__ size_t rows_bytes() const { return ((size_t)n << n) * (size_t)rs * sizeof(uint16_t); }
+    // rows A[R][j] exist for j in R only: n 2^(n-1) of them per instance
+    __host__ __device__ size_t rows_per_instance() const { return (size_t)n << (n - 1); }
+    __host__ __device__ size_t rows_bytes() const { return rows_per_instance() * (size_t)rs * sizeof(uint16_t); }
 };
+
+// Row number of A[R][j], j in R: the rows of the sets before R in numeric order (the sum of their sizes),
+// then the members of R in increasing order.  The sum of the sizes of all sets below R: a member b of R
+// with h members above it stands for the 2^b sets that agree with R above b and lack b; they have
+// h + (a free choice below b) members: h 2^b + b 2^(b-1) in all.
+__host__ __device__ inline uint32_t cluster_first_row(uint32_t R, int n) {
+    uint32_t rows = 0, above = 0;
+    for (int b = n - 1; b >= 0; --b) {
+        if (!((R >> b) & 1u)) continue;
+        rows += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+        ++above;
+    }
+    return rows;
+}
+// first row of R' + j from the first row of R' (j not in R'): the sets counted gain j's own term, and every
+// member of R' below j has one more member above it
+__host__ __device__ inline uint32_t cluster_first_row_with(uint32_t first_row, uint32_t Rp, int j) {
+    const uint32_t below = Rp & ((1u << j) - 1u);
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t above = (uint32_t)__popc(Rp >> (j + 1));
+#else
+    const uint32_t above = (uint32_t)__builtin_popcount(Rp >> (j + 1));
+#endif
+    return first_row + (above << j) + (j ? (uint32_t)j << (j - 1) : 0u) + below;
+}
 
 size_t cluster_tables_bytes(int L, int n) { return ClusterLayout::make(L, n).stride; }
 size_t cluster_rows_bytes(int L, int n) { return ClusterLayout::make(L, n).rows_bytes(); }
@@ -134,15 +161,17 @@ __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const u
                                                  const uint16_t* __restrict__ A, uint32_t rprime, int j, bool more,
                                                  int lane, uint16_t* out) {
     const int L = y.L, n = y.n;
+    const uint16_t* Ar = A + (size_t)cluster_first_row(rprime, n) * y.rs;   // the rows of R', members in order
     for (int e = lane; e <= L; e += 64) {
         uint32_t v = kClInf;
         if (e == L) {
             v = kClZero;
         } else if (e >= 1 && more) {
-            for (uint32_t b = rprime; b; b &= b - 1u) {
+            int r = 0;
+            for (uint32_t b = rprime; b; b &= b - 1u, ++r) {
                 const int j2 = __ffs(b) - 1;
                 const uint32_t q = qc[pair_index(j, j2, n) * L + (e - 1)];
-                const uint32_t a = A[((size_t)rprime * n + j2) * y.rs + e];
+                const uint32_t a = Ar[(size_t)r * y.rs + e];
                 const uint32_t c = q > a ? q : a;
                 v = c < v ? c : v;
             }
@@ -185,14 +214,18 @@ struct ClusterBinomials {
 constexpr ClusterBinomials kClBinomialsHost = ClusterBinomials();
 __constant__ ClusterBinomials kClBinomials = ClusterBinomials();
 
-__device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int n) {
-    uint32_t set = 0;
+// also gives the set's first row (cluster_first_row), gathered on the way: members come out highest first
+__device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int n, uint32_t& first_row) {
+    uint32_t set = 0, rows = 0, above = 0;
     int b = n;
     for (int i = size; i >= 1; --i) {
         do { --b; } while (kClBinomials.c[b][i] > index);
         set |= 1u << b;
         index -= kClBinomials.c[b][i];
+        rows += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+        ++above;
     }
+    first_row = rows;
     return set;
 }
 
@@ -233,7 +266,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     const uint32_t* q32 = reinterpret_cast<const uint32_t*>(cl_smem);
     unsigned char* hi_s = cl_smem + lds.hi_off;
     uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
-    uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (((size_t)n << n) * rd);
+    uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (y.rows_per_instance() * rd);
     // entry e of the row of (j, j''): q_{j,j''}[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
     for (int i = tid; i < n * n * 128; i += threads) {
         const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
@@ -259,13 +292,18 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     const uint32_t nsets = kClBinomials.c[n][level - 1];
     const uint32_t stride = gridDim.x * waves;
     for (uint32_t u = blockIdx.x * waves + wave; u < nsets; u += stride) {
-        const uint32_t mp = cluster_set_at(u, level - 1, n);
+        uint32_t first_row;
+        const uint32_t mp = cluster_set_at(u, level - 1, n, first_row);
         uint32_t a[PPO_CLUSTER_MAX_N];
-        const uint32_t* arow = A32 + (size_t)mp * n * rd + lane;
+        const uint32_t* arow = A32 + (size_t)first_row * rd + lane;
+        int member = 0;   // rows of R' in the order of its members
 #pragma unroll
         for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
             a[j2] = inf2;
-            if (more && j2 < n && ((mp >> j2) & 1u) && lane < rd) a[j2] = arow[j2 * rd];
+            if (j2 < n && ((mp >> j2) & 1u)) {
+                if (more && lane < rd) a[j2] = arow[member * rd];
+                ++member;
+            }
         }
         for (uint32_t jb = all & ~mp; jb; jb &= jb - 1u) {
             const int j = __ffs(jb) - 1;
@@ -306,7 +344,9 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                 }
                 res[h] = r;
             }
-            if (lane < rd) A32[((size_t)(mp | (1u << j)) * n + j) * rd + lane] = res[0] | (res[1] << 16);
+            // row of j within R' + j: after the members below it
+            const uint32_t out_row = cluster_first_row_with(first_row, mp, j) + (uint32_t)__popc(mp & ((1u << j) - 1u));
+            if (lane < rd) A32[(size_t)out_row * rd + lane] = res[0] | (res[1] << 16);
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -337,7 +377,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
-    const uint16_t* A = rows + (size_t)inst * (((size_t)n << n) * y.rs);
+    const uint16_t* A = rows + (size_t)inst * (y.rows_per_instance() * y.rs);
     float* beta = beta_out + inst;
     int32_t* order = order_out + (size_t)inst * n;
     int32_t* cuts = cuts_out ? cuts_out + (size_t)inst * (n - 1) : nullptr;
@@ -355,7 +395,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     auto hi = [&](int j, int e) -> int { return hi_s[j * (L + 1) + e]; };
     const uint32_t all = (1u << n) - 1u;
     // every wave takes the minimum itself: the same value in all of them
-    const uint32_t best = wave_min(lane < n ? (uint32_t)A[((size_t)all * n + lane) * y.rs] : kClInf);
+    const uint32_t best = wave_min(lane < n ? (uint32_t)A[((size_t)cluster_first_row(all, n) + lane) * y.rs] : kClInf);
     if (best >= kClInf) {
         if (tid == 0) {
             *beta = __uint_as_float(kInfBits);

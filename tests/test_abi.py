@@ -100,7 +100,8 @@ def test_cluster_entry_point_without_a_gpu(lib):
     p, null, s = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0)
     lib.ppo_cluster_workspace_bytes.restype = C.c_size_t
     one = lib.ppo_cluster_workspace_bytes(100, 20, 1)
-    assert one >= 20 * (1 << 20) * 100 * 2 and one % 256 == 0           # n 2^n rows of L 16-bit entries
+    rows = 20 * (1 << 19) * 100 * 2                                     # n 2^(n-1) rows of L 16-bit entries
+    assert rows <= one < rows + (1 << 20) and one % 256 == 0
     assert lib.ppo_cluster_workspace_bytes(100, 21, 1) == 0 and lib.ppo_cluster_workspace_bytes(129, 5, 1) == 0
     assert lib.ppo_cluster_workspace_bytes(100, 20, 64) < 64 * one      # rows capped, tables for all
     assert lib.ppo_cluster_workspace_bytes(4, 9, 3) > 0                 # more nodes than layers is allowed
