@@ -134,8 +134,9 @@ int ppo_solve_range_bounded(int L, int k, int n_inst, const void *workspace, siz
  * replace k! DPs.  Sets best_key [n_inst] to exactly what ppo_solve_range leaves after the whole range
  * [0, k!): the optimum's beta and, among the orderings that reach it, the lowest rank (found position by
  * position as the smallest node that can still reach the optimum).  best_key is overwritten, not folded.
- * Allocates (k 2^k)(L+2) 16-bit entries of scratch per instance, for at most 1 GiB of instances at a
- * time, with the stream-ordered allocator. */
+ * Runs the kernels of ppo_solve_cluster (below) with every node required to host a segment.  Allocates
+ * k 2^(k-1) rows of L 16-bit entries of scratch per instance (and a small copy of the tables), for at most
+ * 1 GiB of instances at a time, with the stream-ordered allocator. */
 int ppo_solve_subsets(int L, int k, int n_inst, const void *workspace, size_t workspace_bytes, uint64_t *best_key,
                       void *stream);
 

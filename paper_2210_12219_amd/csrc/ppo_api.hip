@@ -12,14 +12,13 @@ hipError_t launch_enumerate(const Layout&, int, const void*, uint32_t, uint32_t,
 hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, float*, int32_t*, int32_t*,
                             hipStream_t);
 void set_enumeration_variant(int);
-size_t subset_scratch_bytes_per_instance(int L, int k);
-hipError_t launch_subset(const Layout&, int, const void*, void*, uint64_t*, hipStream_t);
 size_t cluster_tables_bytes(int L, int n);
 size_t cluster_rows_bytes(int L, int n);
 hipError_t launch_cluster_tables(const float*, const float*, const float*, const float*, int, int, int, void*,
                                  hipStream_t);
-hipError_t launch_cluster_solve(int, int, int, int, const void*, void*, float*, int32_t*, int32_t*, int32_t*,
-                                hipStream_t);
+hipError_t launch_cluster_solve(int, int, int, int, bool, const void*, void*, uint64_t*, float*, int32_t*, int32_t*,
+                                int32_t*, hipStream_t);
+hipError_t launch_cluster_tables_from_prepared(const Layout&, const void*, int, void*, hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -175,18 +174,23 @@ int ppo_solve_subsets(int L, int k, int n_inst, const void* workspace, size_t wo
     if (workspace_bytes < ppo_workspace_bytes(L, k, n_inst)) return PPO_ENOSPC;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const ppo::Layout y = ppo::Layout::make(L, k);
-    // rows of the subset DP: scratch for as many instances at a time as fit in 1 GiB
-    const size_t per = ppo::subset_scratch_bytes_per_instance(L, k);
-    size_t batch = ((size_t)1 << 30) / per;
+    // the engine of the cluster form with every node to be used: its own copy of the tables and the DP rows,
+    // for as many instances at a time as fit in 1 GiB
+    const size_t tables = ppo::cluster_tables_bytes(L, k), rows = ppo::cluster_rows_bytes(L, k);
+    size_t batch = ((size_t)1 << 30) / (tables + rows);
     if (batch < 1) batch = 1;
     if (batch > (size_t)n_inst) batch = (size_t)n_inst;
-    void* scratch = nullptr;
-    PPO_HIP(hipMallocAsync(&scratch, per * batch, s), "hipMallocAsync (subset DP rows)");
+    if (batch > (size_t)kInstPerLaunch) batch = (size_t)kInstPerLaunch;
+    unsigned char* scratch = nullptr;
+    PPO_HIP(hipMallocAsync(reinterpret_cast<void**>(&scratch), (tables + rows) * batch, s), "hipMallocAsync (subset DP rows)");
     hipError_t e = hipSuccess;
     for (size_t first = 0; first < (size_t)n_inst && e == hipSuccess; first += batch) {
         const int n = (int)(((size_t)n_inst - first < batch) ? (size_t)n_inst - first : batch);
-        e = ppo::launch_subset(y, n, static_cast<const unsigned char*>(workspace) + first * y.stride, scratch,
-                               best_key + first, s);
+        e = ppo::launch_cluster_tables_from_prepared(y, static_cast<const unsigned char*>(workspace) + first * y.stride, n,
+                                                     scratch, s);
+        if (e == hipSuccess)
+            e = ppo::launch_cluster_solve(L, k, n, k, true, scratch, scratch + tables * batch, best_key + first, nullptr,
+                                          nullptr, nullptr, nullptr, s);
     }
     const hipError_t e2 = hipFreeAsync(scratch, s);
     PPO_HIP(e, "subset DP launch");
@@ -235,7 +239,7 @@ int ppo_solve_cluster(const float* t, const float* m, int L, const float* M, con
     }
     for (size_t first = 0; first < (size_t)n_inst; first += together) {
         const int cnt = (int)(((size_t)n_inst - first < together) ? (size_t)n_inst - first : together);
-        PPO_HIP(ppo::launch_cluster_solve(L, n, cnt, pmax, ws + tables * first, row_area, beta_out + first,
+        PPO_HIP(ppo::launch_cluster_solve(L, n, cnt, pmax, false, ws + tables * first, row_area, nullptr, beta_out + first,
                                           segs_out + first, cuts_out ? cuts_out + first * (size_t)(n - 1) : nullptr,
                                           order_out + first * (size_t)n, s),
                 "cluster DP launch");

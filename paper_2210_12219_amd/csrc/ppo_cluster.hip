@@ -159,13 +159,13 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLay
 // rest[R'][j][e'] for e' = lane, lane + 64, ... <= L into `out` (one wave).  A: rows of the instance.
 __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const uint16_t* __restrict__ qc,
                                                  const uint16_t* __restrict__ A, uint32_t rprime, int j, bool more,
-                                                 int lane, uint16_t* out) {
+                                                 bool exact, int lane, uint16_t* out) {
     const int L = y.L, n = y.n;
     const uint16_t* Ar = A + (size_t)cluster_first_row(rprime, n) * y.rs;   // the rows of R', members in order
     for (int e = lane; e <= L; e += 64) {
         uint32_t v = kClInf;
         if (e == L) {
-            v = kClZero;
+            v = (exact && rprime != 0u) ? kClInf : kClZero;   // every node has to be used: the chain may end only then
         } else if (e >= 1 && more) {
             int r = 0;
             for (uint32_t b = rprime; b; b &= b - 1u, ++r) {
@@ -253,7 +253,7 @@ struct ClusterLds {
 __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                                                                      const unsigned char* __restrict__ ws,
                                                                      uint16_t* __restrict__ rows, int level,
-                                                                     int pmax) {
+                                                                     int pmax, int exact) {
     extern __shared__ __align__(16) unsigned char cl_smem[];
     const int L = y.L, n = y.n, rd = y.rs / 2;
     const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
@@ -305,6 +305,15 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                 ++member;
             }
         }
+        // with every node to be used (exact), the chain may end (rest[L] = 0) only after the last node
+        const bool may_end = !exact || mp == 0u;
+        const uint32_t end_here = may_end ? end_mask : 0xFFFFFFFFu;
+        const uint32_t after_here = may_end ? after_last : kClInf;
+        if (exact && L == 128) {   // rest[L] sits in the constant part of the run-minimum rows
+            if (lane < kClRunLevels) run[lane * kClRunRow + 128] = (uint16_t)after_here;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
         for (uint32_t jb = all & ~mp; jb; jb &= jb - 1u) {
             const int j = __ffs(jb) - 1;
             uint32_t v = inf2;
@@ -314,11 +323,11 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                 for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2)
                     if (j2 < n && ((mp >> j2) & 1u)) v = cl_pk_min(v, cl_pk_max(qj[j2 * 64], a[j2]));
             }
-            v &= end_mask;
+            v &= end_here;
             // minima over runs of 2^k entries starting at each entry
             run32[lane] = v;
             uint32_t next = (uint32_t)__shfl_down((int)v, 1, 64);
-            if (lane == 63) next = after_last;
+            if (lane == 63) next = after_here;
             uint32_t cur = cl_pk_min(v, (v >> 16) | (next << 16));
             run32[(kClRunRow / 2) + lane] = cur;
 #pragma unroll
@@ -362,6 +371,8 @@ constexpr int kClTraceWaves = 16;
 __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(ClusterLayout y,
                                                                           const unsigned char* __restrict__ ws,
                                                                           const uint16_t* __restrict__ rows, int pmax,
+                                                                          int exact,
+                                                                          unsigned long long* __restrict__ key_out,
                                                                           float* __restrict__ beta_out,
                                                                           int32_t* __restrict__ segs_out,
                                                                           int32_t* __restrict__ cuts_out,
@@ -378,12 +389,15 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
     const uint16_t* A = rows + (size_t)inst * (y.rows_per_instance() * y.rs);
-    float* beta = beta_out + inst;
-    int32_t* order = order_out + (size_t)inst * n;
+    // either the key alone (exact: bits of beta, rank of the permutation) or beta, segments, cuts, order
+    float* beta = beta_out ? beta_out + inst : nullptr;
+    int32_t* order = order_out ? order_out + (size_t)inst * n : nullptr;
     int32_t* cuts = cuts_out ? cuts_out + (size_t)inst * (n - 1) : nullptr;
     for (int i = tid; i < n * (L + 1); i += kClTraceWaves * 64) hi_s[i] = base[y.hi_off + i];
-    for (int i = tid; i < n; i += kClTraceWaves * 64) order[i] = -1;
-    for (int i = tid; i < n - 1; i += kClTraceWaves * 64) cuts[i] = -1;
+    if (order)
+        for (int i = tid; i < n; i += kClTraceWaves * 64) order[i] = -1;
+    if (cuts)
+        for (int i = tid; i < n - 1; i += kClTraceWaves * 64) cuts[i] = -1;
     __syncthreads();
     auto wave_min = [&](uint32_t v) -> uint32_t {
         for (int off = 32; off >= 1; off >>= 1) {
@@ -398,8 +412,9 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     const uint32_t best = wave_min(lane < n ? (uint32_t)A[((size_t)cluster_first_row(all, n) + lane) * y.rs] : kClInf);
     if (best >= kClInf) {
         if (tid == 0) {
-            *beta = __uint_as_float(kInfBits);
-            segs_out[inst] = 0;
+            if (key_out) key_out[inst] = (unsigned long long)kInfBits << 32;
+            if (beta) *beta = __uint_as_float(kInfBits);
+            if (segs_out) segs_out[inst] = 0;
         }
         return;
     }
@@ -429,7 +444,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
                 }
             }
             uint16_t* rest = rest_s[wave];
-            cluster_rest_row(y, qc, A, all & ~used & ~(1u << j), j, s + 1 < pmax, lane, rest);
+            cluster_rest_row(y, qc, A, all & ~used & ~(1u << j), j, s + 1 < pmax, exact != 0, lane, rest);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             uint32_t v = kClInf;
@@ -449,7 +464,8 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         if (chosen < 0) break;   // cannot happen: some completion of the prefix reaches `best`
         for (int e = tid; e <= L; e += kClTraceWaves * 64) D[s][e] = cand[chosen][e];
         if (tid == 0) seq[s] = chosen;
-        const bool complete = cand[chosen][L] <= best;   // the prefix itself is optimal: it sorts before its extensions
+        // the prefix itself is optimal: it sorts before its extensions (exact: only a full permutation ends)
+        const bool complete = exact ? s == n - 1 : cand[chosen][L] <= best;
         __syncthreads();
         used |= 1u << chosen;
         last = chosen;
@@ -457,9 +473,19 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         if (complete) break;
     }
     if (wave != 0) return;
+    if (key_out && lane == 0) {
+        // lexicographic rank of the permutation: digit s counts the smaller nodes not used before position s
+        uint32_t rank = 0, seen = 0;
+        for (int s = 0; s < p; ++s) {
+            rank += (uint32_t)__popc(~seen & ((1u << seq[s]) - 1u)) * factorial_u32(n - 1 - s);
+            seen |= 1u << seq[s];
+        }
+        key_out[inst] = ((unsigned long long)__float_as_uint(dec[best]) << 32) | rank;
+    }
+    if (!cuts && !beta) return;
     // cuts: latest segment first, each time the smallest cut that keeps the bottleneck at `best`
     int e = L;
-    for (int s = p - 1; s >= 1; --s) {
+    for (int s = p - 1; s >= 1 && cuts; --s) {
         const int js = seq[s], jl = seq[s - 1];
         const uint16_t* f = D[s - 1];
         const uint16_t* q = qc + pair_index(jl, js, n) * L;
@@ -474,10 +500,38 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         e = (int)first;
     }
     if (lane == 0) {
-        *beta = dec[best];
-        segs_out[inst] = p;
-        for (int s = 0; s < p; ++s) order[s] = seq[s];
+        if (beta) *beta = dec[best];
+        if (segs_out) segs_out[inst] = p;
+        if (order)
+            for (int s = 0; s < p; ++s) order[s] = seq[s];
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The tables of this file from those of the fixed-k precompute kernel (window starts lo, quotient codes from
+// kCodeZero + 1 up): hi[j][e] = last e' with lo[j][e'] <= e; the codes lose their offset; dec is the same.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layout f, const unsigned char* __restrict__ fixed_ws,
+                                                                           ClusterLayout y, unsigned char* __restrict__ ws) {
+    const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
+    const unsigned char* src = fixed_ws + (size_t)inst * f.stride;
+    unsigned char* dst = ws + (size_t)inst * y.stride;
+    const unsigned char* lo = src + f.lo_off;
+    for (int idx = tid; idx < n * (L + 1); idx += 256) {
+        const int j = idx / (L + 1), e = idx - j * (L + 1);
+        int e2 = e;
+        while (e2 < L && lo[j * (L + 1) + e2 + 1] <= e) ++e2;
+        dst[y.hi_off + idx] = (unsigned char)e2;
+    }
+    const uint16_t* qsrc = reinterpret_cast<const uint16_t*>(src + f.qc_off);
+    uint16_t* qdst = reinterpret_cast<uint16_t*>(dst + y.qc_off);
+    for (int idx = tid; idx < y.npairs * L; idx += 256) {
+        const int i = idx % L;
+        qdst[idx] = (uint16_t)(i < L - 1 ? qsrc[idx] - kCodeZero : kClInf);
+    }
+    const float* dsrc = reinterpret_cast<const float*>(src + f.dec_off);
+    float* ddst = reinterpret_cast<float*>(dst + y.dec_off);
+    for (int idx = tid; idx <= y.nq; idx += 256) ddst[idx] = dsrc[idx];
 }
 
 hipError_t launch_cluster_tables(const float* t, const float* m, const float* M, const float* B, int L, int n,
@@ -493,8 +547,10 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
 }
 
 // rows of `n_inst` instances (tables at ws, rows at `rows`), levels n - pmax + 1 .. n, then the trace
-hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, const void* ws, void* rows, float* beta_out,
-                                int32_t* segs_out, int32_t* cuts_out, int32_t* order_out, hipStream_t stream) {
+// exact: every node has to be used (pmax = n); key_out (may be null): bits of beta and rank of the permutation
+hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, bool exact, const void* ws, void* rows,
+                                uint64_t* key_out, float* beta_out, int32_t* segs_out, int32_t* cuts_out,
+                                int32_t* order_out, hipStream_t stream) {
     const ClusterLayout y = ClusterLayout::make(L, n);
     const unsigned char* w = static_cast<const unsigned char*>(ws);
     uint16_t* r = static_cast<uint16_t*>(rows);
@@ -510,12 +566,21 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, const void* 
         const uint32_t cap = (resident + (uint32_t)n_inst - 1u) / (uint32_t)n_inst;
         if (blocks > cap) blocks = cap;
         hipLaunchKernelGGL(cluster_level_kernel, dim3(blocks, n_inst), dim3(lds.waves * 64), lds.total, stream, y, w, r,
-                           level, pmax);
+                           level, pmax, exact ? 1 : 0);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(kClTraceWaves * 64), 0, stream, y, w, r, pmax, beta_out, segs_out,
-                       cuts_out, order_out);
+    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(kClTraceWaves * 64), 0, stream, y, w, r, pmax,
+                       exact ? 1 : 0, reinterpret_cast<unsigned long long*>(key_out), beta_out, segs_out, cuts_out,
+                       order_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_cluster_tables_from_prepared(const Layout& f, const void* fixed_ws, int n_inst, void* ws,
+                                               hipStream_t stream) {
+    const ClusterLayout y = ClusterLayout::make(f.L, f.k);
+    hipLaunchKernelGGL(cluster_tables_from_prepared_kernel, dim3(n_inst), dim3(256), 0, stream, f,
+                       static_cast<const unsigned char*>(fixed_ws), y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
 
