@@ -174,6 +174,16 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&kLaneSlot[par][0][0]);
         for (int i = tid; i < 42 * 64 / 2; i += kGrpThreads) lds[gs.slot_off + i] = src[i];
         for (int i = tid; i < (int)gs.buf_off; i += kGrpThreads) lds[i] = kInf2;
+        // Every dword a chain can read has to hold two valid codes, wanted or not: an unwanted entry is dropped
+        // by a maximum with +inf, and the three-input minimum that follows is a binary16 one, which a stray
+        // pattern above +inf (a NaN) or with the sign bit set would win.  Below a row's first dword lie the
+        // margin just filled and, for the first slot of the second buffer, the end of the first buffer.  When
+        // every ordering starts at row 0, that buffer has been written by then; with shared prefix rows the
+        // first row computed may read the second buffer while the first has never been written.
+        if (MODE == kGrpShared) {
+            const int tail = (int)gs.buf_dwords < kDeep * 32 ? (int)gs.buf_dwords : kDeep * 32;
+            for (int i = tid; i < tail; i += kGrpThreads) buf0[(int)gs.buf_dwords - tail + i] = kInf2;
+        }
         // the first rows of all nodes (two codes per dword), the same for every group of the instance
         const uint32_t* d0src = reinterpret_cast<const uint32_t*>(base + y.d0_off);
         for (int i = tid; i < k * y.wt_cols; i += kGrpThreads) lds[gs.d0_off + i] = d0src[i];

@@ -16,7 +16,6 @@ namespace ppo {
 //   code     = kCodeZero + 1 + #{quotients of the instance strictly below q}.
 // ---------------------------------------------------------------------------------------------
 constexpr int kPreThreads = 1024;
-constexpr int kMaxQuot = (PPO_MAX_K * (PPO_MAX_K - 1) / 2) * (PPO_MAX_L - 1);
 
 __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __restrict__ t,
                                                                  const float* __restrict__ m,
@@ -24,7 +23,6 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
                                                                  const float* __restrict__ B, Layout y,
                                                                  unsigned char* __restrict__ ws) {
     __shared__ double P[PPO_MAX_L + 1];
-    __shared__ float qv[kMaxQuot];
     const int L = y.L, k = y.k, inst = blockIdx.x, tid = threadIdx.x;
     const float* ti = t + (size_t)inst * L;
     const float* mi = m + (size_t)inst * L;
@@ -32,8 +30,8 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
     const float* Bi = B + (size_t)inst * k * k;
     unsigned char* base = ws + (size_t)inst * y.stride;
     unsigned char* lo = base + y.lo_off;
-    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
     float* dec = reinterpret_cast<float*>(base + y.dec_off);
+    float* qv = reinterpret_cast<float*>(base + y.qv_off);
     uint32_t* low = reinterpret_cast<uint32_t*>(base + y.low_off);
 
     if (tid == 0) {
@@ -105,27 +103,55 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
         int b = a + 1 + rem;
         qv[idx] = __fdiv_rn(ti[i], Bi[a * k + b]);
     }
-    __syncthreads();
-    for (int idx = tid; idx < nq; idx += kPreThreads) {
-        int p = idx / (L - 1), i = idx - p * (L - 1);
-        float x = qv[idx];
-        int below = 0;
-        for (int j = 0; j < nq; ++j) below += (qv[j] < x) ? 1 : 0;
-        qc[p * L + i] = (uint16_t)(kCodeZero + 1 + below);
+    if (tid == 0) dec[0] = 0.0f;
+}
+
+// Order codes of the quotients (needs L >= 2): grid.x slices of whole node pairs, grid.y = instance.  A
+// thread ranks one quotient against all of the instance (tiles staged in LDS, four comparisons per read);
+// the block then writes the aligned quotient rows `qa` of its pairs.
+__global__ __launch_bounds__(kPreThreads) void codes_kernel(Layout y, unsigned char* __restrict__ ws) {
+    constexpr int kTile = 4096;
+    __shared__ float4 tile4[kTile / 4];
+    __shared__ uint16_t code_s[kPreThreads];
+    float* tile = reinterpret_cast<float*>(tile4);
+    const int L = y.L, inst = blockIdx.y, tid = threadIdx.x;
+    const int ppb = kPreThreads / (L - 1);   // pairs per block
+    const int nq = y.npairs * (L - 1);
+    unsigned char* base = ws + (size_t)inst * y.stride;
+    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
+    float* dec = reinterpret_cast<float*>(base + y.dec_off);
+    const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
+    const int pl = tid / (L - 1), i = tid - pl * (L - 1), p = blockIdx.x * ppb + pl;
+    const bool mine = pl < ppb && p < y.npairs;
+    const float x = mine ? qv[p * (L - 1) + i] : 0.0f;
+    int below = 0;
+    for (int first = 0; first < nq; first += kTile) {
+        const int len = nq - first < kTile ? nq - first : kTile;
+        __syncthreads();
+        for (int j = tid; j < kTile; j += kPreThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
+        __syncthreads();
+        for (int j = 0; j < (len + 3) / 4; ++j) {   // the padding (+inf) is below nothing
+            const float4 v = tile4[j];
+            below += (v.x < x ? 1 : 0) + (v.y < x ? 1 : 0) + (v.z < x ? 1 : 0) + (v.w < x ? 1 : 0);
+        }
+    }
+    if (mine) {
+        const uint16_t code = (uint16_t)(kCodeZero + 1 + below);
+        qc[p * L + i] = code;
+        code_s[tid] = code;
         dec[1 + below] = x;
     }
-    if (tid == 0) dec[0] = 0.0f;
     __syncthreads();
-    {
-        uint32_t* qa = reinterpret_cast<uint32_t*>(base + y.qa_off);
-        const int cols = y.qa_cols, QD = L / 2 + 1;
-        for (int idx = tid; idx < y.npairs * cols; idx += kPreThreads) {
-            const int p = idx / cols, col = idx - p * cols;
-            const int i0 = col < QD ? 2 * col : 2 * (col - QD - 1) + 1;
-            const uint32_t v0 = (i0 >= 0 && i0 <= L - 2) ? qc[p * L + i0] : kCodeInf;
-            const uint32_t v1 = (i0 + 1 >= 0 && i0 + 1 <= L - 2) ? qc[p * L + i0 + 1] : kCodeInf;
-            qa[idx] = v0 | (v1 << 16);
-        }
+    uint32_t* qa = reinterpret_cast<uint32_t*>(base + y.qa_off);
+    const int cols = y.qa_cols, QD = L / 2 + 1;
+    const int first_pair = blockIdx.x * ppb;
+    const int pairs_here = y.npairs - first_pair < ppb ? y.npairs - first_pair : ppb;
+    for (int idx = tid; idx < pairs_here * cols; idx += kPreThreads) {
+        const int q = idx / cols, col = idx - q * cols;
+        const int i0 = col < QD ? 2 * col : 2 * (col - QD - 1) + 1;
+        const uint32_t v0 = (i0 >= 0 && i0 <= L - 2) ? code_s[q * (L - 1) + i0] : kCodeInf;
+        const uint32_t v1 = (i0 + 1 >= 0 && i0 + 1 <= L - 2) ? code_s[q * (L - 1) + i0 + 1] : kCodeInf;
+        qa[(first_pair + q) * cols + col] = v0 | (v1 << 16);
     }
 }
 
@@ -300,6 +326,11 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
 hipError_t launch_precompute(const float* t, const float* m, const float* M, const float* B, const Layout& y,
                              int n_inst, void* ws, hipStream_t stream) {
     hipLaunchKernelGGL(precompute_kernel, dim3(n_inst), dim3(kPreThreads), 0, stream, t, m, M, B, y,
+                       static_cast<unsigned char*>(ws));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || y.L < 2 || y.npairs == 0) return e;   // no link, no quotient
+    const int ppb = kPreThreads / (y.L - 1);
+    hipLaunchKernelGGL(codes_kernel, dim3((y.npairs + ppb - 1) / ppb, n_inst), dim3(kPreThreads), 0, stream, y,
                        static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
