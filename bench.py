@@ -120,7 +120,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
-                 "(the rank range shards trivially, see DESIGN.md, but no multi-GPU path is built)")
+                 "(rank ranges and instances are independent, so the search shards trivially, but no multi-GPU path is built)")
 
     import torch
     from paper_2210_12219_amd import binding as ppo
