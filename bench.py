@@ -56,7 +56,18 @@ def algorithmic_ops_per_ordering(w):
 # (FETCH_SIZE, then WRITE_SIZE) of `bench.py --steps 1 --warmup 0 --no-cpu-baseline --copy-probe`, each counter
 # scaled by what it reads for the probe's 256 MiB (see profiles/).  Keyed by ppo_version(): a library whose
 # kernel has changed since reports no traffic.
-MEASURED_TRAFFIC_BYTES = {("headline", 104): 4.853e7}   # re-measure when the kernel changes
+MEASURED_TRAFFIC_BYTES = {("headline", 104): 4.853e7,
+                          ("cluster_mixed_n20", 104): 4.526e9}   # the 20 level launches of one n = 20 solve   # re-measure when the kernel changes
+
+
+def copy_probe(torch):
+    """One plain elementwise kernel of known traffic, for scaling the HBM counters of a rocprofv3 --pmc run."""
+    src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    torch.add(src, 1.0, out=dst)   # one dispatch: 256 MiB read, 256 MiB written
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def bench_cluster(args, torch, ppo, workloads):
@@ -68,6 +79,8 @@ def bench_cluster(args, torch, ppo, workloads):
     dev = ppo.to_device(w)
     ws = torch.empty(ppo.ppo_cluster_workspace_bytes(w.L, N, n_inst), dtype=torch.uint8, device="cuda:0")
     out = None
+    if args.copy_probe:
+        copy_probe(torch)
     for _ in range(args.warmup):
         out = ppo.ppo_solve_cluster(*dev, max_segments=pmax, workspace=ws, out=out)
     torch.cuda.synchronize()
@@ -90,7 +103,9 @@ def bench_cluster(args, torch, ppo, workloads):
                    "dp_rows_per_instance": rows, "segments_found": [int(x) for x in out[1].cpu().numpy()[:8]]},
         # against the whole call (tables, one launch per level, trace), not the level kernel alone
         "roofline": {"bound": "hbm", "kernel": "cluster_level_kernel (all levels) + tables + trace",
-                     "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0, "traffic": None,
+                     "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, ppo.load().ppo_version()))
+                     if (n_inst == 1 and pmax == N) else None,
                      "bytes_per_step": alg_bytes},
     }
     print(json.dumps(result), flush=True)
@@ -161,12 +176,7 @@ def main():
             events[3].record(stream)
 
     if args.copy_probe:
-        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.add(src, 1.0, out=dst)   # one dispatch: 256 MiB read, 256 MiB written
-        torch.cuda.synchronize()
-        del src, dst
+        copy_probe(torch)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
