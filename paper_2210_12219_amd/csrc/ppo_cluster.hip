@@ -14,14 +14,21 @@
 // level in |R|, one launch per level, one wave per row, on 16-bit order codes of the quotients.  The
 // lexicographically smallest optimal sequence (a sequence before its extensions) is rebuilt position by
 // position from forward rows of the prefix combined with `rest`, then the cuts by the fixed-k cut rule.
+#include <array>
+#include <utility>
+
 #include "ppo_common.h"
 
 namespace ppo {
 
-constexpr uint32_t kClZero = 0u, kClInf = 0xFFFFu;   // codes: 0 = value 0, 1 + #smaller quotients, 0xFFFF = +inf
+// Codes as in the fixed-k kernels: kCodeZero for the value 0, kCodeZero + 1 + #{smaller quotients}, kCodeInf for
+// +inf: positive normal binary16 patterns, so the three-input binary16 minimum acts as an integer minimum.
+// Everything these kernels read as a code is written by them as one (a stray pattern could win that minimum).
+constexpr uint32_t kClZero = kCodeZero, kClInf = kCodeInf;
 constexpr int kClPreThreads = 1024;
 constexpr int kClRow = PPO_MAX_L + 2;
-static_assert((PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) + 1 < (int)kClInf, "codes fit 16 bits");
+static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) + 1 < (int)kClInf,
+              "codes stay below +inf");
 
 struct ClusterLayout {
     int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
@@ -151,7 +158,7 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLay
     }
     if (idx < nq) {
         const int p = idx / (L - 1), i = idx - p * (L - 1);
-        qc[p * L + i] = (uint16_t)(1 + below);
+        qc[p * L + i] = (uint16_t)(kClZero + 1 + below);
         dec[1 + below] = x;
     }
 }
@@ -250,11 +257,19 @@ struct ClusterLds {
     }
 };
 
+__device__ __forceinline__ uint32_t cl_pk_min3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_pk_minimum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// C = |R'| = level - 1: the rows of the set's members sit in C registers, in the order of the members
+template <int C>
 __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
-                                                                     const unsigned char* __restrict__ ws,
-                                                                     uint16_t* __restrict__ rows, int level,
-                                                                     int pmax, int exact) {
+                                                             const unsigned char* __restrict__ ws,
+                                                             uint16_t* __restrict__ rows, int pmax, int exact) {
     extern __shared__ __align__(16) unsigned char cl_smem[];
+    constexpr int level = C + 1, CA = C > 0 ? C : 1;
     const int L = y.L, n = y.n, rd = y.rs / 2;
     const int inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: keeps the set in scalar registers
@@ -267,11 +282,13 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     unsigned char* hi_s = cl_smem + lds.hi_off;
     uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
     uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (y.rows_per_instance() * rd);
+    const bool more = n - level + 1 < pmax;   // segments up to and including this row's: n - level + 1
     // entry e of the row of (j, j''): q_{j,j''}[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
-    for (int i = tid; i < n * n * 128; i += threads) {
-        const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
-        q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
-    }
+    if (more)
+        for (int i = tid; i < n * n * 128; i += threads) {
+            const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
+            q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
+        }
     for (int i = tid; i < n * kClHiRow; i += threads) {
         const int j = i / kClHiRow, e = i - j * kClHiRow;
         hi_s[i] = e <= L ? base[y.hi_off + j * (L + 1) + e] : (unsigned char)0;
@@ -282,32 +299,34 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
         run[k * kClRunRow + e] = (uint16_t)(e == L ? kClZero : kClInf);
     }
     __syncthreads();
-    const bool more = n - level + 1 < pmax;   // segments up to and including this row's: n - level + 1
     const uint32_t inf2 = kClInf | (kClInf << 16);
     const uint32_t all = (1u << n) - 1u;
     const int e0 = 2 * lane, e1 = e0 + 1;
-    const uint32_t end_mask = (e0 == L ? 0u : 0xFFFFu) | (e1 == L ? 0u : 0xFFFF0000u);   // rest[L] = 0
-    const uint32_t after_last = L == 128 ? kClZero : kClInf;                             // entry 128 of rest
+    // rest[L] = 0: the half of entry L is cleared and set to the code of 0
+    const uint32_t end_keep = (e0 == L ? 0u : 0xFFFFu) | (e1 == L ? 0u : 0xFFFF0000u);
+    const uint32_t end_set = (e0 == L ? kClZero : 0u) | (e1 == L ? kClZero << 16 : 0u);
+    const uint32_t after_last = L == 128 ? kClZero : kClInf;   // entry 128 of rest
     uint32_t* run32 = reinterpret_cast<uint32_t*>(run);
-    const uint32_t nsets = kClBinomials.c[n][level - 1];
+    const uint32_t nsets = kClBinomials.c[n][C];
     const uint32_t stride = gridDim.x * waves;
     for (uint32_t u = blockIdx.x * waves + wave; u < nsets; u += stride) {
         uint32_t first_row;
-        const uint32_t mp = cluster_set_at(u, level - 1, n, first_row);
-        uint32_t a[PPO_CLUSTER_MAX_N];
-        const uint32_t* arow = A32 + (size_t)first_row * rd + lane;
-        int member = 0;   // rows of R' in the order of its members
+        const uint32_t mp = cluster_set_at(u, C, n, first_row);
+        uint32_t a[CA];      // row A[R'][member m], two entries per lane
+        uint32_t moff[CA];   // dword offset of member m's quotient row from the row of (j, 0)
+        {
+            const uint32_t* arow = A32 + (size_t)first_row * rd + lane;
+            uint32_t bits = mp;
 #pragma unroll
-        for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
-            a[j2] = inf2;
-            if (j2 < n && ((mp >> j2) & 1u)) {
-                if (more && lane < rd) a[j2] = arow[member * rd];
-                ++member;
+            for (int m = 0; m < C; ++m) {
+                moff[m] = (uint32_t)(__ffs(bits) - 1) * 64u;
+                bits &= bits - 1u;
+                a[m] = (more && lane < rd) ? arow[m * rd] : inf2;
             }
         }
         // with every node to be used (exact), the chain may end (rest[L] = 0) only after the last node
         const bool may_end = !exact || mp == 0u;
-        const uint32_t end_here = may_end ? end_mask : 0xFFFFFFFFu;
+        const uint32_t keep_here = may_end ? end_keep : 0xFFFFFFFFu, set_here = may_end ? end_set : 0u;
         const uint32_t after_here = may_end ? after_last : kClInf;
         if (exact && L == 128) {   // rest[L] sits in the constant part of the run-minimum rows
             if (lane < kClRunLevels) run[lane * kClRunRow + 128] = (uint16_t)after_here;
@@ -319,11 +338,14 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             uint32_t v = inf2;
             if (more) {
                 const uint32_t* qj = q32 + (j * n) * 64 + lane;
+                uint32_t x[CA];
 #pragma unroll
-                for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2)
-                    if (j2 < n && ((mp >> j2) & 1u)) v = cl_pk_min(v, cl_pk_max(qj[j2 * 64], a[j2]));
+                for (int m = 0; m < C; ++m) x[m] = cl_pk_max(qj[moff[m]], a[m]);
+#pragma unroll
+                for (int m = 0; m + 1 < C; m += 2) v = cl_pk_min3(v, x[m], x[m + 1]);
+                if (C & 1) v = cl_pk_min(v, x[C - 1]);
             }
-            v &= end_here;
+            v = (v & keep_here) | set_here;
             // minima over runs of 2^k entries starting at each entry
             run32[lane] = v;
             uint32_t next = (uint32_t)__shfl_down((int)v, 1, 64);
@@ -480,7 +502,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
             rank += (uint32_t)__popc(~seen & ((1u << seq[s]) - 1u)) * factorial_u32(n - 1 - s);
             seen |= 1u << seq[s];
         }
-        key_out[inst] = ((unsigned long long)__float_as_uint(dec[best]) << 32) | rank;
+        key_out[inst] = ((unsigned long long)__float_as_uint(dec[best - kClZero]) << 32) | rank;
     }
     if (!cuts && !beta) return;
     // cuts: latest segment first, each time the smallest cut that keeps the bottleneck at `best`
@@ -500,7 +522,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         e = (int)first;
     }
     if (lane == 0) {
-        if (beta) *beta = dec[best];
+        if (beta) *beta = dec[best - kClZero];
         if (segs_out) segs_out[inst] = p;
         if (order)
             for (int s = 0; s < p; ++s) order[s] = seq[s];
@@ -509,7 +531,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
 
 // ---------------------------------------------------------------------------------------------
 // The tables of this file from those of the fixed-k precompute kernel (window starts lo, quotient codes from
-// kCodeZero + 1 up): hi[j][e] = last e' with lo[j][e'] <= e; the codes lose their offset; dec is the same.
+// kCodeZero + 1 up): hi[j][e] = last e' with lo[j][e'] <= e; codes and dec are the same.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layout f, const unsigned char* __restrict__ fixed_ws,
                                                                            ClusterLayout y, unsigned char* __restrict__ ws) {
@@ -527,7 +549,7 @@ __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layou
     uint16_t* qdst = reinterpret_cast<uint16_t*>(dst + y.qc_off);
     for (int idx = tid; idx < y.npairs * L; idx += 256) {
         const int i = idx % L;
-        qdst[idx] = (uint16_t)(i < L - 1 ? qsrc[idx] - kCodeZero : kClInf);
+        qdst[idx] = (uint16_t)(i < L - 1 ? qsrc[idx] : kClInf);
     }
     const float* dsrc = reinterpret_cast<const float*>(src + f.dec_off);
     float* ddst = reinterpret_cast<float*>(dst + y.dec_off);
@@ -547,6 +569,25 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
 }
 
 // rows of `n_inst` instances (tables at ws, rows at `rows`), levels n - pmax + 1 .. n, then the trace
+// one instantiation of the level kernel per set size
+using ClLevelLaunch = hipError_t (*)(dim3, dim3, uint32_t, hipStream_t, const ClusterLayout&, const unsigned char*,
+                                     uint16_t*, int, int);
+template <int C>
+static hipError_t cluster_launch_level(dim3 grid, dim3 block, uint32_t lds_bytes, hipStream_t stream, const ClusterLayout& y,
+                                       const unsigned char* ws, uint16_t* rows, int pmax, int exact) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_level_kernel<C>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cluster_level_kernel<C>, grid, block, lds_bytes, stream, y, ws, rows, pmax, exact);
+    return hipGetLastError();
+}
+template <int... Cs>
+static constexpr std::array<ClLevelLaunch, sizeof...(Cs)> cluster_level_table(std::integer_sequence<int, Cs...>) {
+    return {{&cluster_launch_level<Cs>...}};
+}
+static const std::array<ClLevelLaunch, PPO_CLUSTER_MAX_N> kClLevelLaunch =
+    cluster_level_table(std::make_integer_sequence<int, PPO_CLUSTER_MAX_N>{});
+
 // exact: every node has to be used (pmax = n); key_out (may be null): bits of beta and rank of the permutation
 hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, bool exact, const void* ws, void* rows,
                                 uint64_t* key_out, float* beta_out, int32_t* segs_out, int32_t* cuts_out,
@@ -557,17 +598,14 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, bool exact, 
     const ClusterLds lds = ClusterLds::choose(y);
     const uint32_t per_cu = (160u * 1024u) / lds.total;   // workgroups a compute unit holds: 1 or 2 (or more for small n)
     const uint32_t resident = 256u * (per_cu < 1u ? 1u : per_cu > 4u ? 4u : per_cu);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_level_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds.total);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
     for (int level = n - pmax + 1; level <= n; ++level) {
         // a set per wave at most; no more workgroups than stay resident (each stages the quotient table once)
         uint32_t blocks = (kClBinomialsHost.c[n][level - 1] + (uint32_t)lds.waves - 1u) / (uint32_t)lds.waves;
         const uint32_t cap = (resident + (uint32_t)n_inst - 1u) / (uint32_t)n_inst;
         if (blocks > cap) blocks = cap;
-        hipLaunchKernelGGL(cluster_level_kernel, dim3(blocks, n_inst), dim3(lds.waves * 64), lds.total, stream, y, w, r,
-                           level, pmax, exact ? 1 : 0);
-        e = hipGetLastError();
+        e = kClLevelLaunch[level - 1](dim3(blocks, n_inst), dim3(lds.waves * 64), lds.total, stream, y, w, r, pmax,
+                                      exact ? 1 : 0);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(kClTraceWaves * 64), 0, stream, y, w, r, pmax,
