@@ -196,7 +196,7 @@ __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const u
 // ---------------------------------------------------------------------------------------------
 constexpr int kClRunLevels = 7;    // runs of 2^0 .. 2^6 entries
 constexpr int kClRunRow = 192;     // entries per run-minimum row: 128 computed per set, the rest constant
-constexpr int kClHiRow = 130;      // bytes per node of the window table in LDS (entries above L read 0)
+constexpr int kClQueryRow = 128;   // window queries per node in LDS: one dword per entry e
 
 typedef unsigned short cl_ushort2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t cl_pk_min(uint32_t a, uint32_t b) {
@@ -237,8 +237,8 @@ __device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int
 }
 
 // LDS of the level kernel: the quotient rows of every ORDERED pair of nodes, 64 dwords each (so that the row
-// of (j, j'') is a fixed distance j'' * 256 bytes from the row of (j, 0)), the window table, and the
-// run-minimum tables of each wave.
+// of (j, j'') is a fixed distance j'' * 256 bytes from the row of (j, 0)), the window queries of every
+// (node, entry), and the run-minimum tables of each wave.
 struct ClusterLds {
     uint32_t hi_off, run_off, total;
     int waves;
@@ -246,7 +246,7 @@ struct ClusterLds {
         ClusterLds s;
         s.waves = waves;
         s.hi_off = (uint32_t)y.n * (uint32_t)y.n * 256u;
-        s.run_off = (uint32_t)align_up((size_t)s.hi_off + (size_t)y.n * kClHiRow, 16);
+        s.run_off = (uint32_t)align_up((size_t)s.hi_off + (size_t)y.n * kClQueryRow * 4, 16);
         s.total = s.run_off + (uint32_t)waves * kClRunLevels * kClRunRow * 2;
         return s;
     }
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     uint16_t* q16 = reinterpret_cast<uint16_t*>(cl_smem);
     const uint32_t* q32 = reinterpret_cast<const uint32_t*>(cl_smem);
-    unsigned char* hi_s = cl_smem + lds.hi_off;
+    uint32_t* query = reinterpret_cast<uint32_t*>(cl_smem + lds.hi_off);
     uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
     uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (y.rows_per_instance() * rd);
     const bool more = n - level + 1 < pmax;   // segments up to and including this row's: n - level + 1
@@ -289,9 +289,20 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
             q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
         }
-    for (int i = tid; i < n * kClHiRow; i += threads) {
-        const int j = i / kClHiRow, e = i - j * kClHiRow;
-        hi_s[i] = e <= L ? base[y.hi_off + j * (L + 1) + e] : (unsigned char)0;
+    // The window (e, hi[j][e]] of node j at entry e is covered by two runs of 2^k entries, k the largest with
+    // 2^k <= its length: the one starting at e + 1 and the one ending at hi.  The table holds the byte offsets
+    // of their minima within a wave's run-minimum rows, 16 bits each; no window: twice an entry that is +inf.
+    for (int i = tid; i < n * kClQueryRow; i += threads) {
+        const int j = i / kClQueryRow, e = i - j * kClQueryRow;
+        const int top = e < L ? (int)base[y.hi_off + j * (L + 1) + e] : 0;
+        uint32_t o1 = kClRunRow - 2, o2 = kClRunRow - 2;   // run row 0, beyond the chain
+        if (top > e) {
+            int k = 31 - __clz(top - e);
+            k = k > kClRunLevels - 1 ? kClRunLevels - 1 : k;
+            o1 = (uint32_t)(k * kClRunRow + e + 1);
+            o2 = (uint32_t)(k * kClRunRow + top - (1 << k) + 1);
+        }
+        query[i] = (o1 * 2u) | ((o2 * 2u) << 16);
     }
     // entries 128.. of the run-minimum rows never change: rest[L] = 0 if L = 128, +inf beyond the chain
     for (int i = lane; i < kClRunLevels * (kClRunRow - 128); i += 64) {
@@ -361,19 +372,15 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            const uint32_t hh = *reinterpret_cast<const uint16_t*>(hi_s + j * kClHiRow + e0);
+            const uint2 qd = *reinterpret_cast<const uint2*>(query + j * kClQueryRow + e0);
+            const unsigned char* runb = reinterpret_cast<const unsigned char*>(run);
             uint32_t res[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int e = e0 + h, top = (int)((hh >> (8 * h)) & 0xFFu);
-                uint32_t r = kClInf;
-                if (top > e) {   // entries at and above L have top = 0
-                    int k = 31 - __clz(top - e);
-                    k = k > kClRunLevels - 1 ? kClRunLevels - 1 : k;
-                    const uint32_t r1 = run[k * kClRunRow + e + 1], r2 = run[k * kClRunRow + top - (1 << k) + 1];
-                    r = r1 < r2 ? r1 : r2;
-                }
-                res[h] = r;
+                const uint32_t d = h ? qd.y : qd.x;
+                const uint32_t r1 = *reinterpret_cast<const uint16_t*>(runb + (d & 0xFFFFu));
+                const uint32_t r2 = *reinterpret_cast<const uint16_t*>(runb + (d >> 16));
+                res[h] = r1 < r2 ? r1 : r2;
             }
             // row of j within R' + j: after the members below it
             const uint32_t out_row = cluster_first_row_with(first_row, mp, j) + (uint32_t)__popc(mp & ((1u << j) - 1u));
