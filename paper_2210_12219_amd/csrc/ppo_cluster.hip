@@ -318,11 +318,16 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     const uint32_t end_set = (e0 == L ? kClZero : 0u) | (e1 == L ? kClZero << 16 : 0u);
     const uint32_t after_last = L == 128 ? kClZero : kClInf;   // entry 128 of rest
     uint32_t* run32 = reinterpret_cast<uint32_t*>(run);
+    // A wave takes a run of consecutive sets: the first from its index (binomial table, a chain of dependent
+    // scalar loads), each further one from the one before (the next larger number with as many bits set).
     const uint32_t nsets = kClBinomials.c[n][C];
-    const uint32_t stride = gridDim.x * waves;
-    for (uint32_t u = blockIdx.x * waves + wave; u < nsets; u += stride) {
-        uint32_t first_row;
-        const uint32_t mp = cluster_set_at(u, C, n, first_row);
+    const uint32_t total_waves = gridDim.x * waves;
+    const uint32_t per_wave = (nsets + total_waves - 1u) / total_waves;
+    uint32_t u = (blockIdx.x * waves + wave) * per_wave;
+    const uint32_t u_end = u + per_wave < nsets ? u + per_wave : nsets;
+    uint32_t mp = 0, first_row = 0;
+    if (u < u_end) mp = cluster_set_at(u, C, n, first_row);
+    for (; u < u_end; ++u) {
         uint32_t a[CA];      // row A[R'][member m], two entries per lane
         uint32_t moff[CA];   // dword offset of member m's quotient row from the row of (j, 0)
         {
@@ -386,6 +391,17 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             const uint32_t out_row = cluster_first_row_with(first_row, mp, j) + (uint32_t)__popc(mp & ((1u << j) - 1u));
             if (lane < rd) A32[(size_t)out_row * rd + lane] = res[0] | (res[1] << 16);
             __builtin_amdgcn_wave_barrier();
+        }
+        if (C > 0 && u + 1u < u_end) {
+            const uint32_t low = mp & (0u - mp), up = mp + low;
+            mp = (((up ^ mp) >> 2) >> (__ffs(mp) - 1)) | up;
+            first_row = 0;
+            uint32_t above = 0;
+            for (uint32_t bits = mp; bits; ++above) {
+                const int b = 31 - __clz(bits);
+                bits ^= 1u << b;
+                first_row += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+            }
         }
     }
 }
