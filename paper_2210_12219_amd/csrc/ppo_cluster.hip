@@ -364,8 +364,9 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             v = (v & keep_here) | set_here;
             // minima over runs of 2^k entries starting at each entry
             run32[lane] = v;
-            uint32_t next = (uint32_t)__shfl_down((int)v, 1, 64);
-            if (lane == 63) next = after_here;
+            // the dword of the next lane (wave shift left by one: lane i reads lane i + 1; lane 63 keeps the
+            // first operand, the entry after the last one)
+            const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp((int)after_here, (int)v, 0x130, 0xF, 0xF, false);
             uint32_t cur = cl_pk_min(v, (v >> 16) | (next << 16));
             run32[(kClRunRow / 2) + lane] = cur;
 #pragma unroll
