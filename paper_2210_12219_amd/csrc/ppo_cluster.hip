@@ -33,7 +33,7 @@ static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) *
 struct ClusterLayout {
     int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
                                                     // and not stored), rounded up to even
-    uint32_t hi_off, qc_off, dec_off, qv_off, stride;   // bytes within one instance's tables
+    uint32_t hi_off, qc_off, dec_off, qv_off, img_off, stride;   // bytes within one instance's tables
 
     __host__ __device__ static ClusterLayout make(int L, int n) {
         ClusterLayout y;
@@ -51,6 +51,10 @@ struct ClusterLayout {
         off = align_up(off + ((size_t)y.nq + 1) * 4, 16);
         y.qv_off = (uint32_t)off;
         off = align_up(off + (size_t)y.nq * 4, 256);
+        // what the level kernel keeps in LDS, ready to be copied: quotient rows of every ordered pair (64 dwords
+        // each), then the window queries of every (node, entry) (128 dwords per node)
+        y.img_off = (uint32_t)off;
+        off = align_up(off + (size_t)n * n * 256 + (size_t)n * 512, 256);
         y.stride = (uint32_t)off;
         return y;
     }
@@ -276,33 +280,17 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     const int threads = blockDim.x, waves = threads >> 6;
     const ClusterLds lds = ClusterLds::make(y, waves);
     const unsigned char* base = ws + (size_t)inst * y.stride;
-    const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
-    uint16_t* q16 = reinterpret_cast<uint16_t*>(cl_smem);
     const uint32_t* q32 = reinterpret_cast<const uint32_t*>(cl_smem);
-    uint32_t* query = reinterpret_cast<uint32_t*>(cl_smem + lds.hi_off);
+    const uint32_t* query = reinterpret_cast<const uint32_t*>(cl_smem + lds.hi_off);
     uint16_t* run = reinterpret_cast<uint16_t*>(cl_smem + lds.run_off) + wave * (kClRunLevels * kClRunRow);
     uint32_t* A32 = reinterpret_cast<uint32_t*>(rows) + (size_t)inst * (y.rows_per_instance() * rd);
     const bool more = n - level + 1 < pmax;   // segments up to and including this row's: n - level + 1
-    // entry e of the row of (j, j''): q_{j,j''}[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf
-    if (more)
-        for (int i = tid; i < n * n * 128; i += threads) {
-            const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
-            q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
-        }
-    // The window (e, hi[j][e]] of node j at entry e is covered by two runs of 2^k entries, k the largest with
-    // 2^k <= its length: the one starting at e + 1 and the one ending at hi.  The table holds the byte offsets
-    // of their minima within a wave's run-minimum rows, 16 bits each; no window: twice an entry that is +inf.
-    for (int i = tid; i < n * kClQueryRow; i += threads) {
-        const int j = i / kClQueryRow, e = i - j * kClQueryRow;
-        const int top = e < L ? (int)base[y.hi_off + j * (L + 1) + e] : 0;
-        uint32_t o1 = kClRunRow - 2, o2 = kClRunRow - 2;   // run row 0, beyond the chain
-        if (top > e) {
-            int k = 31 - __clz(top - e);
-            k = k > kClRunLevels - 1 ? kClRunLevels - 1 : k;
-            o1 = (uint32_t)(k * kClRunRow + e + 1);
-            o2 = (uint32_t)(k * kClRunRow + top - (1 << k) + 1);
-        }
-        query[i] = (o1 * 2u) | ((o2 * 2u) << 16);
+    // quotient rows and window queries: a straight copy of the image the tables kernels left (16 bytes a thread)
+    {
+        const uint4* img = reinterpret_cast<const uint4*>(base + y.img_off);
+        uint4* dst = reinterpret_cast<uint4*>(cl_smem);
+        const int first = more ? 0 : n * n * 16, count = n * n * 16 + n * 32;   // the quotient rows only if used
+        for (int i = first + tid; i < count; i += threads) dst[i] = img[i];
     }
     // entries 128.. of the run-minimum rows never change: rest[L] = 0 if L = 128, +inf beyond the chain
     for (int i = lane; i < kClRunLevels * (kClRunRow - 128); i += 64) {
@@ -580,15 +568,49 @@ __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layou
     for (int idx = tid; idx <= y.nq; idx += 256) ddst[idx] = dsrc[idx];
 }
 
+// The image of the level kernel's LDS tables (needs hi and the codes): one workgroup per instance.
+//   quotient rows: entry e of the row of (j, j''): q_{j,j''}[e-1] for 1 <= e <= L-1 (the cuts with a link), else +inf;
+//   window queries: the window (e, hi[j][e]] of node j at entry e is covered by two runs of 2^k entries, k the
+//   largest with 2^k <= its length: the one starting at e + 1 and the one ending at hi.  The table holds the byte
+//   offsets of their minima within a wave's run-minimum rows, 16 bits each; no window: twice an entry that is +inf.
+__global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
+    const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
+    unsigned char* base = ws + (size_t)inst * y.stride;
+    const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
+    uint16_t* q16 = reinterpret_cast<uint16_t*>(base + y.img_off);
+    uint32_t* query = reinterpret_cast<uint32_t*>(base + y.img_off) + n * n * 64;
+    for (int i = tid; i < n * n * 128; i += kClPreThreads) {
+        const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
+        q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
+    }
+    for (int i = tid; i < n * kClQueryRow; i += kClPreThreads) {
+        const int j = i / kClQueryRow, e = i - j * kClQueryRow;
+        const int top = e < L ? (int)base[y.hi_off + j * (L + 1) + e] : 0;
+        uint32_t o1 = kClRunRow - 2, o2 = kClRunRow - 2;   // run row 0, beyond the chain
+        if (top > e) {
+            int k = 31 - __clz(top - e);
+            k = k > kClRunLevels - 1 ? kClRunLevels - 1 : k;
+            o1 = (uint32_t)(k * kClRunRow + e + 1);
+            o2 = (uint32_t)(k * kClRunRow + top - (1 << k) + 1);
+        }
+        query[i] = (o1 * 2u) | ((o2 * 2u) << 16);
+    }
+}
+
 hipError_t launch_cluster_tables(const float* t, const float* m, const float* M, const float* B, int L, int n,
                                  int n_inst, void* ws, hipStream_t stream) {
     const ClusterLayout y = ClusterLayout::make(L, n);
     unsigned char* w = static_cast<unsigned char*>(ws);
     hipLaunchKernelGGL(cluster_tables_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, t, m, M, B, y, w);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || y.nq == 0) return e;
-    hipLaunchKernelGGL(cluster_codes_kernel, dim3((y.nq + kClPreThreads - 1) / kClPreThreads, n_inst), dim3(kClPreThreads),
-                       0, stream, y, w);
+    if (e != hipSuccess) return e;
+    if (y.nq > 0) {
+        hipLaunchKernelGGL(cluster_codes_kernel, dim3((y.nq + kClPreThreads - 1) / kClPreThreads, n_inst),
+                           dim3(kClPreThreads), 0, stream, y, w);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, w);
     return hipGetLastError();
 }
 
@@ -643,6 +665,9 @@ hipError_t launch_cluster_tables_from_prepared(const Layout& f, const void* fixe
     const ClusterLayout y = ClusterLayout::make(f.L, f.k);
     hipLaunchKernelGGL(cluster_tables_from_prepared_kernel, dim3(n_inst), dim3(256), 0, stream, f,
                        static_cast<const unsigned char*>(fixed_ws), y, static_cast<unsigned char*>(ws));
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
 
