@@ -33,7 +33,7 @@ static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) *
 struct ClusterLayout {
     int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
                                                     // and not stored), rounded up to even
-    uint32_t hi_off, qc_off, dec_off, qv_off, img_off, stride;   // bytes within one instance's tables
+    uint32_t hi_off, qc_off, dec_off, qv_off, cnt_off, img_off, stride;   // bytes within one instance's tables
 
     __host__ __device__ static ClusterLayout make(int L, int n) {
         ClusterLayout y;
@@ -50,6 +50,8 @@ struct ClusterLayout {
         y.dec_off = (uint32_t)off;
         off = align_up(off + ((size_t)y.nq + 1) * 4, 16);
         y.qv_off = (uint32_t)off;
+        off = align_up(off + (size_t)y.nq * 4, 16);
+        y.cnt_off = (uint32_t)off;   // per quotient: how many quotients of the instance are strictly smaller
         off = align_up(off + (size_t)y.nq * 4, 256);
         // what the level kernel keeps in LDS, ready to be copied: quotient rows of every ordered pair (64 dwords
         // each), then the window queries of every (node, entry) (128 dwords per node)
@@ -134,37 +136,39 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
         while (rem >= n - 1 - a) { rem -= n - 1 - a; ++a; }
         const int b = a + 1 + rem;
         qv[idx] = __fdiv_rn(ti[i], Bi[a * n + b]);
+        reinterpret_cast<uint32_t*>(base + y.cnt_off)[idx] = 0u;
     }
 }
 
-// grid.x slices of kClPreThreads quotients, grid.y = instance
-__global__ __launch_bounds__(kClPreThreads) void cluster_codes_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
+// Counting: grid.x slices of 256 quotients, grid.y parts of the quotients they are compared with, grid.z =
+// instance; the parts' counts are added up in the workspace.  (The image kernel turns them into codes.)
+constexpr int kClCountThreads = 256;
+__global__ __launch_bounds__(kClCountThreads) void cluster_count_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
     constexpr int kTile = 4096;
     __shared__ float4 tile4[kTile / 4];
     float* tile = reinterpret_cast<float*>(tile4);
-    const int L = y.L, nq = y.nq, inst = blockIdx.y, tid = threadIdx.x;
+    const int nq = y.nq, inst = blockIdx.z, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
-    uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
-    float* dec = reinterpret_cast<float*>(base + y.dec_off);
     const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
-    const int idx = blockIdx.x * kClPreThreads + tid;
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(base + y.cnt_off);
+    const int idx = blockIdx.x * kClCountThreads + tid;
     const float x = idx < nq ? qv[idx] : 0.0f;
+    // this block's part of the quotients to compare with, in whole tiles
+    const int tiles = (nq + kTile - 1) / kTile, tiles_per_part = (tiles + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int part_begin = (int)blockIdx.y * tiles_per_part * kTile;
+    const int part_end = part_begin + tiles_per_part * kTile < nq ? part_begin + tiles_per_part * kTile : nq;
     int below = 0;
-    for (int first = 0; first < nq; first += kTile) {
-        const int len = nq - first < kTile ? nq - first : kTile;
+    for (int first = part_begin; first < part_end; first += kTile) {
+        const int len = part_end - first < kTile ? part_end - first : kTile;
         __syncthreads();
-        for (int j = tid; j < kTile; j += kClPreThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
+        for (int j = tid; j < kTile; j += kClCountThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
         __syncthreads();
         for (int j = 0; j < (len + 3) / 4; ++j) {   // the padding (+inf) is below nothing
             const float4 v = tile4[j];
             below += (v.x < x ? 1 : 0) + (v.y < x ? 1 : 0) + (v.z < x ? 1 : 0) + (v.w < x ? 1 : 0);
         }
     }
-    if (idx < nq) {
-        const int p = idx / (L - 1), i = idx - p * (L - 1);
-        qc[p * L + i] = (uint16_t)(kClZero + 1 + below);
-        dec[1 + below] = x;
-    }
+    if (idx < nq && below) atomicAdd(cnt + idx, (uint32_t)below);
 }
 
 // rest[R'][j][e'] for e' = lane, lane + 64, ... <= L into `out` (one wave).  A: rows of the instance.
@@ -573,12 +577,27 @@ __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layou
 //   window queries: the window (e, hi[j][e]] of node j at entry e is covered by two runs of 2^k entries, k the
 //   largest with 2^k <= its length: the one starting at e + 1 and the one ending at hi.  The table holds the byte
 //   offsets of their minima within a wave's run-minimum rows, 16 bits each; no window: twice an entry that is +inf.
-__global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
+__global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLayout y, unsigned char* __restrict__ ws,
+                                                                     int codes_from_counts) {
     const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     uint16_t* q16 = reinterpret_cast<uint16_t*>(base + y.img_off);
     uint32_t* query = reinterpret_cast<uint32_t*>(base + y.img_off) + n * n * 64;
+    if (codes_from_counts) {
+        // order codes from the counts, and the value of each code
+        uint16_t* qcw = reinterpret_cast<uint16_t*>(base + y.qc_off);
+        float* dec = reinterpret_cast<float*>(base + y.dec_off);
+        const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
+        const uint32_t* __restrict__ cnt = reinterpret_cast<const uint32_t*>(base + y.cnt_off);
+        for (int idx = tid; idx < y.nq; idx += kClPreThreads) {
+            const int p = idx / (L - 1), i = idx - p * (L - 1);
+            const uint32_t below = cnt[idx];
+            qcw[p * L + i] = (uint16_t)(kClZero + 1 + below);
+            dec[1 + below] = qv[idx];
+        }
+        __syncthreads();   // the codes are read back below by other threads of this workgroup
+    }
     for (int i = tid; i < n * n * 128; i += kClPreThreads) {
         const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
         q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
@@ -605,12 +624,15 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (y.nq > 0) {
-        hipLaunchKernelGGL(cluster_codes_kernel, dim3((y.nq + kClPreThreads - 1) / kClPreThreads, n_inst),
-                           dim3(kClPreThreads), 0, stream, y, w);
+        // enough workgroups to fill the chip: split the quotients compared with into parts when instances are few
+        const int slices = (y.nq + kClCountThreads - 1) / kClCountThreads, tiles = (y.nq + 4095) / 4096;
+        int parts = (1024 + slices * n_inst - 1) / (slices * n_inst);
+        parts = parts < 1 ? 1 : parts > tiles ? tiles : parts;
+        hipLaunchKernelGGL(cluster_count_kernel, dim3(slices, parts, n_inst), dim3(kClCountThreads), 0, stream, y, w);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, w);
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, w, 1);
     return hipGetLastError();
 }
 
@@ -667,7 +689,7 @@ hipError_t launch_cluster_tables_from_prepared(const Layout& f, const void* fixe
                        static_cast<const unsigned char*>(fixed_ws), y, static_cast<unsigned char*>(ws));
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, static_cast<unsigned char*>(ws));
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, static_cast<unsigned char*>(ws), 0);
     return hipGetLastError();
 }
 
