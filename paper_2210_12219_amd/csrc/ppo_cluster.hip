@@ -182,12 +182,22 @@ __device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const u
         if (e == L) {
             v = (exact && rprime != 0u) ? kClInf : kClZero;   // every node has to be used: the chain may end only then
         } else if (e >= 1 && more) {
+            // all loads first (the set is the same for every lane, so the branches are scalar), then the folding
+            uint32_t a[PPO_CLUSTER_MAX_N], q[PPO_CLUSTER_MAX_N];
             int r = 0;
-            for (uint32_t b = rprime; b; b &= b - 1u, ++r) {
-                const int j2 = __ffs(b) - 1;
-                const uint32_t q = qc[pair_index(j, j2, n) * L + (e - 1)];
-                const uint32_t a = Ar[(size_t)r * y.rs + e];
-                const uint32_t c = q > a ? q : a;
+#pragma unroll
+            for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
+                a[j2] = kClInf;
+                q[j2] = kClInf;
+                if ((rprime >> j2) & 1u) {
+                    q[j2] = qc[pair_index(j, j2, n) * L + (e - 1)];
+                    a[j2] = Ar[(size_t)r * y.rs + e];
+                    ++r;
+                }
+            }
+#pragma unroll
+            for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
+                const uint32_t c = q[j2] > a[j2] ? q[j2] : a[j2];
                 v = c < v ? c : v;
             }
         }
@@ -468,18 +478,30 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
             if (s == 0) {
                 for (int e = lane; e <= L; e += 64) f2[e] = (uint16_t)((e >= 1 && e <= hi(j, 0)) ? kClZero : kClInf);
             } else {
-                // f2[e2] = min over cuts i in [s, e2) with layers [i, e2) fitting j of max(D[s-1][i], q[i-1])
+                // f2[e2] = min over cuts i in [s, e2) with layers [i, e2) fitting j of max(D[s-1][i], q[i-1]):
+                // the maxima first, side by side, into the wave's row; then every lane walks its window in LDS
                 const uint16_t* f = D[s - 1];
                 const uint16_t* q = qc + pair_index(last, j, n) * L;
+                uint16_t* g = rest_s[wave];
+                for (int i = lane; i <= L; i += 64) {
+                    uint32_t c = kClInf;
+                    if (i >= 1 && i <= L - 1) {
+                        const uint32_t a = f[i], b = q[i - 1];
+                        c = a > b ? a : b;
+                    }
+                    g[i] = (uint16_t)c;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
                 for (int e2 = lane; e2 <= L; e2 += 64) {
                     uint32_t v = kClInf;
                     for (int i = e2 - 1; i >= s && hi(j, i) >= e2; --i) {
-                        const uint32_t a = f[i], b = q[i - 1];
-                        const uint32_t c = a > b ? a : b;
+                        const uint32_t c = g[i];
                         v = c < v ? c : v;
                     }
                     f2[e2] = (uint16_t)v;
                 }
+                __builtin_amdgcn_wave_barrier();   // g is the row `rest` is written to next
             }
             uint16_t* rest = rest_s[wave];
             cluster_rest_row(y, qc, A, all & ~used & ~(1u << j), j, s + 1 < pmax, exact != 0, lane, rest);
