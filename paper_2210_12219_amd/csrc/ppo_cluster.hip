@@ -33,7 +33,7 @@ static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) *
 struct ClusterLayout {
     int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
                                                     // and not stored), rounded up to even
-    uint32_t hi_off, qc_off, dec_off, qv_off, cnt_off, img_off, stride;   // bytes within one instance's tables
+    uint32_t hi_off, qc_off, dec_off, qv_off, ord_off, img_off, stride;   // bytes within one instance's tables
 
     __host__ __device__ static ClusterLayout make(int L, int n) {
         ClusterLayout y;
@@ -51,8 +51,8 @@ struct ClusterLayout {
         off = align_up(off + ((size_t)y.nq + 1) * 4, 16);
         y.qv_off = (uint32_t)off;
         off = align_up(off + (size_t)y.nq * 4, 16);
-        y.cnt_off = (uint32_t)off;   // per quotient: how many quotients of the instance are strictly smaller
-        off = align_up(off + (size_t)y.nq * 4, 256);
+        y.ord_off = (uint32_t)off;   // the layers 0 .. L-2 in increasing order of t (one byte each)
+        off = align_up(off + (size_t)L, 256);
         // what the level kernel keeps in LDS, ready to be copied: quotient rows of every ordered pair (64 dwords
         // each), then the window queries of every (node, entry) (128 dwords per node)
         y.img_off = (uint32_t)off;
@@ -130,45 +130,72 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
         while (e2 < L && (P[e2 + 1] - P[e]) <= cap) ++e2;
         hi[idx] = (unsigned char)e2;
     }
+    // The quotients of one link, t[i] / B, are in the order of the t[i] (a correctly rounded division by a
+    // positive number is monotone), so each link's row is written sorted: position r holds the quotient of the
+    // layer with the r-th smallest t (ties by index).  Ranking a quotient among all of them is then a binary
+    // search per link instead of a comparison with every quotient.
+    __shared__ float t_s[PPO_MAX_L];
+    __shared__ unsigned char ord_s[PPO_MAX_L];
+    for (int i = tid; i < L - 1; i += kClPreThreads) t_s[i] = ti[i];
+    __syncthreads();
+    for (int i = tid; i < L - 1; i += kClPreThreads) {
+        const float x = t_s[i];
+        int pos = 0;
+        for (int i2 = 0; i2 < L - 1; ++i2) pos += (t_s[i2] < x || (t_s[i2] == x && i2 < i)) ? 1 : 0;
+        ord_s[pos] = (unsigned char)i;
+        base[y.ord_off + pos] = (unsigned char)i;
+    }
+    __syncthreads();
     for (int idx = tid; idx < y.nq; idx += kClPreThreads) {
-        const int p = idx / (L - 1), i = idx - p * (L - 1);
+        const int p = idx / (L - 1), r = idx - p * (L - 1);
         int a = 0, rem = p;
         while (rem >= n - 1 - a) { rem -= n - 1 - a; ++a; }
         const int b = a + 1 + rem;
-        qv[idx] = __fdiv_rn(ti[i], Bi[a * n + b]);
-        reinterpret_cast<uint32_t*>(base + y.cnt_off)[idx] = 0u;
+        qv[idx] = __fdiv_rn(t_s[ord_s[r]], Bi[a * n + b]);
     }
 }
 
-// Counting: grid.x slices of 256 quotients, grid.y parts of the quotients they are compared with, grid.z =
-// instance; the parts' counts are added up in the workspace.  (The image kernel turns them into codes.)
+// Order codes: grid.x slices of 256 quotients, grid.y = instance.  All sorted rows are staged in LDS; a thread
+// adds up, over the links, how many of a link's quotients are strictly below its own (a binary search each).
 constexpr int kClCountThreads = 256;
 __global__ __launch_bounds__(kClCountThreads) void cluster_count_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
-    constexpr int kTile = 4096;
-    __shared__ float4 tile4[kTile / 4];
-    float* tile = reinterpret_cast<float*>(tile4);
-    const int nq = y.nq, inst = blockIdx.z, tid = threadIdx.x;
+    extern __shared__ __align__(16) float cl_rows[];   // [npairs][L-1]
+    const int L = y.L, nq = y.nq, len = L - 1, inst = blockIdx.y, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
     const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
-    uint32_t* cnt = reinterpret_cast<uint32_t*>(base + y.cnt_off);
+    for (int i = tid; i < nq; i += kClCountThreads) cl_rows[i] = qv[i];
+    __syncthreads();
     const int idx = blockIdx.x * kClCountThreads + tid;
-    const float x = idx < nq ? qv[idx] : 0.0f;
-    // this block's part of the quotients to compare with, in whole tiles
-    const int tiles = (nq + kTile - 1) / kTile, tiles_per_part = (tiles + (int)gridDim.y - 1) / (int)gridDim.y;
-    const int part_begin = (int)blockIdx.y * tiles_per_part * kTile;
-    const int part_end = part_begin + tiles_per_part * kTile < nq ? part_begin + tiles_per_part * kTile : nq;
+    if (idx >= nq) return;
+    const float x = cl_rows[idx];
     int below = 0;
-    for (int first = part_begin; first < part_end; first += kTile) {
-        const int len = part_end - first < kTile ? part_end - first : kTile;
-        __syncthreads();
-        for (int j = tid; j < kTile; j += kClCountThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
-        __syncthreads();
-        for (int j = 0; j < (len + 3) / 4; ++j) {   // the padding (+inf) is below nothing
-            const float4 v = tile4[j];
-            below += (v.x < x ? 1 : 0) + (v.y < x ? 1 : 0) + (v.z < x ? 1 : 0) + (v.w < x ? 1 : 0);
+    // four links at a time, so that four reads are in flight at every step of the searches
+    for (int p0 = 0; p0 < y.npairs; p0 += 4) {
+        int pos[4] = {0, 0, 0, 0};   // number of entries of each row below x
+        const float* row[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) row[u] = cl_rows + (p0 + u < y.npairs ? p0 + u : p0) * len;
+#pragma unroll
+        for (int step = 64; step >= 1; step >>= 1) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int np = pos[u] + step;
+                v[u] = row[u][(np <= len ? np : len) - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int np = pos[u] + step;
+                if (np <= len && v[u] < x) pos[u] = np;
+            }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) below += p0 + u < y.npairs ? pos[u] : 0;
     }
-    if (idx < nq && below) atomicAdd(cnt + idx, (uint32_t)below);
+    const int p = idx / len, r = idx - p * len;
+    const int i = base[y.ord_off + r];
+    reinterpret_cast<uint16_t*>(base + y.qc_off)[p * L + i] = (uint16_t)(kClZero + 1 + below);
+    reinterpret_cast<float*>(base + y.dec_off)[1 + below] = x;
 }
 
 // rest[R'][j][e'] for e' = lane, lane + 64, ... <= L into `out` (one wave).  A: rows of the instance.
@@ -599,27 +626,12 @@ __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layou
 //   window queries: the window (e, hi[j][e]] of node j at entry e is covered by two runs of 2^k entries, k the
 //   largest with 2^k <= its length: the one starting at e + 1 and the one ending at hi.  The table holds the byte
 //   offsets of their minima within a wave's run-minimum rows, 16 bits each; no window: twice an entry that is +inf.
-__global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLayout y, unsigned char* __restrict__ ws,
-                                                                     int codes_from_counts) {
+__global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLayout y, unsigned char* __restrict__ ws) {
     const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     uint16_t* q16 = reinterpret_cast<uint16_t*>(base + y.img_off);
     uint32_t* query = reinterpret_cast<uint32_t*>(base + y.img_off) + n * n * 64;
-    if (codes_from_counts) {
-        // order codes from the counts, and the value of each code
-        uint16_t* qcw = reinterpret_cast<uint16_t*>(base + y.qc_off);
-        float* dec = reinterpret_cast<float*>(base + y.dec_off);
-        const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
-        const uint32_t* __restrict__ cnt = reinterpret_cast<const uint32_t*>(base + y.cnt_off);
-        for (int idx = tid; idx < y.nq; idx += kClPreThreads) {
-            const int p = idx / (L - 1), i = idx - p * (L - 1);
-            const uint32_t below = cnt[idx];
-            qcw[p * L + i] = (uint16_t)(kClZero + 1 + below);
-            dec[1 + below] = qv[idx];
-        }
-        __syncthreads();   // the codes are read back below by other threads of this workgroup
-    }
     for (int i = tid; i < n * n * 128; i += kClPreThreads) {
         const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
         q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
@@ -646,15 +658,16 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (y.nq > 0) {
-        // enough workgroups to fill the chip: split the quotients compared with into parts when instances are few
-        const int slices = (y.nq + kClCountThreads - 1) / kClCountThreads, tiles = (y.nq + 4095) / 4096;
-        int parts = (1024 + slices * n_inst - 1) / (slices * n_inst);
-        parts = parts < 1 ? 1 : parts > tiles ? tiles : parts;
-        hipLaunchKernelGGL(cluster_count_kernel, dim3(slices, parts, n_inst), dim3(kClCountThreads), 0, stream, y, w);
+        const int slices = (y.nq + kClCountThreads - 1) / kClCountThreads;
+        const uint32_t lds_bytes = (uint32_t)y.nq * 4u;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_count_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(cluster_count_kernel, dim3(slices, n_inst), dim3(kClCountThreads), lds_bytes, stream, y, w);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, w, 1);
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, w);
     return hipGetLastError();
 }
 
@@ -711,7 +724,7 @@ hipError_t launch_cluster_tables_from_prepared(const Layout& f, const void* fixe
                        static_cast<const unsigned char*>(fixed_ws), y, static_cast<unsigned char*>(ws));
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, static_cast<unsigned char*>(ws), 0);
+    hipLaunchKernelGGL(cluster_image_kernel, dim3(n_inst), dim3(kClPreThreads), 0, stream, y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
 
