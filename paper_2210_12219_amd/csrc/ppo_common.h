@@ -34,7 +34,9 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
 //   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
 //       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
-//   qv  [npairs][L-1] f32   the quotients themselves (between the two kernels that make the tables)
+//   qv  [npairs][L-1] f32   the quotients themselves, each link's row in increasing order (between the two
+//       kernels that make the tables);  ord [L-1] u8  the layers in increasing order of t: entry r of a row
+//       of qv belongs to layer ord[r]
 // Chain descriptor of one output dword (positions x = e and y = e+1) of the grouped kernel, four words.
 // The kernel works on chunks of kChunkPairs output dwords and holds the input dword at an output's own
 // index and the kChainDepth dwords below it in registers.  The entries of the row below are counted
@@ -97,7 +99,7 @@ struct WinDesc {
 
 struct Layout {
     int L, k, npairs, wt_cols, qa_cols;
-    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, d0_off, qv_off, stride;  // bytes within one instance's slice
+    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, d0_off, qv_off, ord_off, stride;  // bytes within one instance's slice
 
     __host__ __device__ static Layout make(int L, int k) {
         Layout y;
@@ -123,7 +125,9 @@ struct Layout {
         y.d0_off = (uint32_t)off;
         off = align_up(off + (size_t)k * y.wt_cols * 4, 16);
         y.qv_off = (uint32_t)off;
-        off = align_up(off + (size_t)y.npairs * (L > 1 ? L - 1 : 0) * 4, 256);
+        off = align_up(off + (size_t)y.npairs * (L > 1 ? L - 1 : 0) * 4, 16);
+        y.ord_off = (uint32_t)off;
+        off = align_up(off + (size_t)L, 256);
         y.stride = (uint32_t)off;
         return y;
     }

@@ -95,50 +95,84 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
             d0[idx] = v[0] | (v[1] << 16);
         }
     }
+    // The quotients of one link, t[i] / B, are in the order of the t[i] (a correctly rounded division by a
+    // positive number is monotone), so each link's row is written sorted: position r holds the quotient of the
+    // layer with the r-th smallest t (ties by index).  Ranking a quotient among all of them is then a binary
+    // search per link instead of a comparison with every quotient.
+    __shared__ float t_s[PPO_MAX_L];
+    __shared__ unsigned char ord_s[PPO_MAX_L];
+    __syncthreads();
+    for (int i = tid; i < L - 1; i += kPreThreads) t_s[i] = ti[i];
+    __syncthreads();
+    for (int i = tid; i < L - 1; i += kPreThreads) {
+        const float x = t_s[i];
+        int pos = 0;
+        for (int i2 = 0; i2 < L - 1; ++i2) pos += (t_s[i2] < x || (t_s[i2] == x && i2 < i)) ? 1 : 0;
+        ord_s[pos] = (unsigned char)i;
+        base[y.ord_off + pos] = (unsigned char)i;
+    }
+    __syncthreads();
     const int nq = y.npairs * (L - 1);
     for (int idx = tid; idx < nq; idx += kPreThreads) {
-        int p = idx / (L - 1), i = idx - p * (L - 1);
+        int p = idx / (L - 1), r = idx - p * (L - 1);
         int a = 0, rem = p;
         while (rem >= k - 1 - a) { rem -= k - 1 - a; ++a; }
         int b = a + 1 + rem;
-        qv[idx] = __fdiv_rn(ti[i], Bi[a * k + b]);
+        qv[idx] = __fdiv_rn(t_s[ord_s[r]], Bi[a * k + b]);
     }
     if (tid == 0) dec[0] = 0.0f;
 }
 
-// Order codes of the quotients (needs L >= 2): grid.x slices of whole node pairs, grid.y = instance.  A
-// thread ranks one quotient against all of the instance (tiles staged in LDS, four comparisons per read);
-// the block then writes the aligned quotient rows `qa` of its pairs.
+// Order codes of the quotients (needs L >= 2): grid.x slices of whole node pairs, grid.y = instance.  All
+// sorted rows are staged in LDS; a thread adds up, over the links, how many of a link's quotients are strictly
+// below its own (a binary search each, four links at a time); the block then writes the aligned quotient
+// rows `qa` of its pairs.
+constexpr int kMaxQuot = (PPO_MAX_K * (PPO_MAX_K - 1) / 2) * (PPO_MAX_L - 1);
 __global__ __launch_bounds__(kPreThreads) void codes_kernel(Layout y, unsigned char* __restrict__ ws) {
-    constexpr int kTile = 4096;
-    __shared__ float4 tile4[kTile / 4];
-    __shared__ uint16_t code_s[kPreThreads];
-    float* tile = reinterpret_cast<float*>(tile4);
-    const int L = y.L, inst = blockIdx.y, tid = threadIdx.x;
-    const int ppb = kPreThreads / (L - 1);   // pairs per block
-    const int nq = y.npairs * (L - 1);
+    __shared__ float rows_s[kMaxQuot];           // [npairs][L-1], each row in increasing order
+    __shared__ uint16_t code_s[kPreThreads];     // codes of this block's pairs, by layer
+    const int L = y.L, len = L - 1, inst = blockIdx.y, tid = threadIdx.x;
+    const int ppb = kPreThreads / len;   // pairs per block
+    const int nq = y.npairs * len;
     unsigned char* base = ws + (size_t)inst * y.stride;
     uint16_t* qc = reinterpret_cast<uint16_t*>(base + y.qc_off);
     float* dec = reinterpret_cast<float*>(base + y.dec_off);
     const float* __restrict__ qv = reinterpret_cast<const float*>(base + y.qv_off);
-    const int pl = tid / (L - 1), i = tid - pl * (L - 1), p = blockIdx.x * ppb + pl;
+    for (int j = tid; j < nq; j += kPreThreads) rows_s[j] = qv[j];
+    __syncthreads();
+    const int pl = tid / len, r = tid - pl * len, p = blockIdx.x * ppb + pl;
     const bool mine = pl < ppb && p < y.npairs;
-    const float x = mine ? qv[p * (L - 1) + i] : 0.0f;
+    const float x = mine ? rows_s[p * len + r] : 0.0f;
+    const int i = mine ? (int)base[y.ord_off + r] : 0;   // the layer whose quotient this is
     int below = 0;
-    for (int first = 0; first < nq; first += kTile) {
-        const int len = nq - first < kTile ? nq - first : kTile;
-        __syncthreads();
-        for (int j = tid; j < kTile; j += kPreThreads) tile[j] = j < len ? qv[first + j] : __uint_as_float(kInfBits);
-        __syncthreads();
-        for (int j = 0; j < (len + 3) / 4; ++j) {   // the padding (+inf) is below nothing
-            const float4 v = tile4[j];
-            below += (v.x < x ? 1 : 0) + (v.y < x ? 1 : 0) + (v.z < x ? 1 : 0) + (v.w < x ? 1 : 0);
+    if (mine) {
+        for (int p0 = 0; p0 < y.npairs; p0 += 4) {
+            int pos[4] = {0, 0, 0, 0};   // number of entries of each row below x
+            const float* row[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) row[u] = rows_s + (p0 + u < y.npairs ? p0 + u : p0) * len;
+#pragma unroll
+            for (int step = 64; step >= 1; step >>= 1) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int np = pos[u] + step;
+                    v[u] = row[u][(np <= len ? np : len) - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int np = pos[u] + step;
+                    if (np <= len && v[u] < x) pos[u] = np;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) below += p0 + u < y.npairs ? pos[u] : 0;
         }
     }
     if (mine) {
         const uint16_t code = (uint16_t)(kCodeZero + 1 + below);
         qc[p * L + i] = code;
-        code_s[tid] = code;
+        code_s[pl * len + i] = code;
         dec[1 + below] = x;
     }
     __syncthreads();
