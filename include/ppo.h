@@ -177,6 +177,25 @@ int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, con
                       int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* From a model's layer graph to the chain (paper Sec. III-A).  HOST routine: every pointer is a host pointer,
+ * nothing is enqueued on the GPU.
+ *   n_vertices layers, n_edges data dependencies edge_src[e] -> edge_dst[e] (a DAG with exactly one vertex
+ *   without predecessors, the source); weight[v] the weight size of layer v, out_size[v] the size of the
+ *   tensor it emits (already divided by whatever compression ratio the caller assumes).
+ * Topological depth LP(v) = length of the longest path from the source to v.  Candidate partition points:
+ * p_0 = the source; going through the vertices in order of depth, u is the next point after p iff no other
+ * vertex has u's depth and every path that leaves p reaches u before any vertex deeper than u (a path that
+ * ends first does not reach it).  Layer i of the chain = the vertices deeper than point i-1 and not deeper
+ * than point i; vertices deeper than the last point form one more layer.
+ *   t [max_layers], m [max_layers]   t[i] = out_size of point i (0 for the layer after the last point),
+ *                                    m[i] = sum of the weights of layer i (added in binary64, in vertex order)
+ *   point [max_layers]               vertex of point i (-1 for the layer after the last point)
+ *   n_layers                         L, also set when PPO_ENOSPC says that max_layers is too small
+ * PPO_EINVAL: null pointer, vertex index out of range, self loop, no or several sources, a cycle. */
+int ppo_chain_from_dag(int n_vertices, int n_edges, const int32_t *edge_src, const int32_t *edge_dst,
+                       const float *weight, const float *out_size, int max_layers, float *t, float *m,
+                       int32_t *point, int32_t *n_layers);
+
 #ifdef __cplusplus
 }
 #endif

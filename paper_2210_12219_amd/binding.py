@@ -55,6 +55,7 @@ def load() -> C.CDLL:
         lib.ppo_solve_subsets.argtypes = [i, i, i, vp, sz, vp, vp]
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
+        lib.ppo_chain_from_dag.argtypes = [i, i, vp, vp, vp, vp, i, vp, vp, vp, vp]
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_cluster_workspace_bytes.restype = sz
         lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
@@ -212,6 +213,23 @@ def ppo_eval_orderings(t, m, M, B, rank_begin, rank_end, stream=None):
     _check(load().ppo_eval_orderings(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, int(rank_begin),
                                      int(rank_end), C.c_void_p(out.data_ptr()), _stream(stream)))
     return out
+
+
+def ppo_chain_from_dag(n_vertices, edges, weight, out_size):
+    """Host routine: (t [L], m [L], point [L]) of the chain of a layer graph; edges is a sequence of (src, dst)."""
+    import numpy as np
+    e = np.ascontiguousarray(np.asarray(edges, dtype=np.int32).reshape(-1, 2))
+    src, dst = np.ascontiguousarray(e[:, 0]), np.ascontiguousarray(e[:, 1])
+    w = np.ascontiguousarray(weight, dtype=np.float32)
+    o = np.ascontiguousarray(out_size, dtype=np.float32)
+    assert w.shape == (n_vertices,) and o.shape == (n_vertices,)
+    cap = n_vertices + 1
+    t, m = np.zeros(cap, np.float32), np.zeros(cap, np.float32)
+    point, L = np.zeros(cap, np.int32), C.c_int32(0)
+    ptr = lambda a: C.c_void_p(a.ctypes.data)
+    _check(load().ppo_chain_from_dag(n_vertices, len(src), ptr(src), ptr(dst), ptr(w), ptr(o), cap, ptr(t), ptr(m),
+                                     ptr(point), C.cast(C.byref(L), C.c_void_p)))
+    return t[:L.value].copy(), m[:L.value].copy(), point[:L.value].copy()
 
 
 def ppo_cluster_workspace_bytes(L: int, n: int, n_inst: int) -> int:

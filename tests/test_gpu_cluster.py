@@ -172,3 +172,30 @@ def test_cluster_sixteen_against_the_oracle(ppo):
     w = W.cluster_mixed(16, L=100, n_inst=1, seed=12)
     print("cluster n=16 L=100", flush=True)
     assert_same(solve(ppo, w), oracle(w, 16, CO.subset_dp), "mixed n=16")
+
+
+def test_layer_graph_to_placement(ppo):
+    """End to end as in the paper: a layer graph with shortcuts (Sec. III-A) -> chain -> exact partition and
+    placement on a cluster.  The chain comes from the library's host front-end; the search from the GPU."""
+    import torch
+    rng = np.random.default_rng(3)
+    edges, v = [], 0
+    for _ in range(12):              # twelve residual blocks: in -> a -> b -> add, in -> add
+        a, b, add = v + 1, v + 2, v + 3
+        edges += [(v, a), (a, b), (b, add), (v, add)]
+        v = add
+    n_vertices = v + 1
+    weight = rng.uniform(0.5, 12.0, n_vertices).astype(np.float32)
+    out = rng.uniform(1.0, 30.0, n_vertices).astype(np.float32)
+    t, m, point = ppo.ppo_chain_from_dag(n_vertices, edges, weight, out)
+    assert list(point) == [3 * i for i in range(13)] and len(t) == 13      # the block boundaries, nothing inside
+    n = 7
+    M = np.full(n, 0.3 * float(m.sum()), np.float32)
+    w = W.cluster_geometric(n, 1.0, n_inst=1, seed=11)                      # for its bandwidth matrix
+    dev = [torch.tensor(x[None], device="cuda:0") for x in (t, m, M)] + [torch.tensor(w.B, device="cuda:0")]
+    print("layer graph -> chain -> cluster", flush=True)
+    got = tuple(x.cpu().numpy() for x in ppo.ppo_solve_cluster(*dev))
+    torch.cuda.synchronize()
+    beta, p, cuts, order = CO.exhaustive(t, m, M, w.B[0])
+    assert bits(got[0][0]) == bits(beta) and got[1][0] == p >= 4
+    assert np.array_equal(got[2][0], cuts) and np.array_equal(got[3][0], order)
