@@ -177,6 +177,20 @@ int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, con
                       int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* The paper's own partitioning step (Sec. III-B1, Alg. 1), for comparison with the joint optimum: cut the chain
+ * into segments that each fit a node of capacity kappa so that the SUM of the transfer sizes at the cuts,
+ * t[c_1 - 1] + ... + t[c_{p-1} - 1], is least (the cheapest root-to-leaf path of the partition graph).
+ * Memory rule as stated at the top; sums of transfer sizes in binary64, added from the chain's end.
+ * Among partitions of equal sum: the fewest segments, then the smallest first cut, second cut, ...
+ *   t, m [n_inst][L], kappa [n_inst]      device
+ *   segs_out [n_inst]        p; 0 if some layer does not fit
+ *   cuts_out [n_inst][L-1]   c_1..c_{p-1}, then -1 (may be NULL when L = 1)
+ *   sum_out  [n_inst]        binary64; +inf if infeasible
+ * The placement the paper then looks for (Alg. 2, 3) is, for these fixed cuts, what ppo_solve_cluster finds
+ * exactly on the chain of the merged segments. */
+int ppo_min_sum_partition(const float *t, const float *m, int L, const float *kappa, int n_inst, int32_t *segs_out,
+                          int32_t *cuts_out, double *sum_out, void *stream);
+
 /* From a model's layer graph to the chain (paper Sec. III-A).  HOST routine: every pointer is a host pointer,
  * nothing is enqueued on the GPU.
  *   n_vertices layers, n_edges data dependencies edge_src[e] -> edge_dst[e] (a DAG with exactly one vertex

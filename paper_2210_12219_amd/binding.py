@@ -56,6 +56,7 @@ def load() -> C.CDLL:
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
         lib.ppo_chain_from_dag.argtypes = [i, i, vp, vp, vp, vp, i, vp, vp, vp, vp]
+        lib.ppo_min_sum_partition.argtypes = [vp, vp, i, vp, i, vp, vp, vp, vp]
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_cluster_workspace_bytes.restype = sz
         lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
@@ -213,6 +214,20 @@ def ppo_eval_orderings(t, m, M, B, rank_begin, rank_end, stream=None):
     _check(load().ppo_eval_orderings(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, int(rank_begin),
                                      int(rank_end), C.c_void_p(out.data_ptr()), _stream(stream)))
     return out
+
+
+def ppo_min_sum_partition(t, m, kappa, stream=None):
+    """The paper's partitioning step (least sum of transfer sizes): (segs [n], cuts [n, L-1], sum [n] float64)."""
+    torch = _torch()
+    n_inst, L = t.shape
+    f32 = torch.float32
+    segs = torch.empty(n_inst, dtype=torch.int32, device=t.device)
+    cuts = torch.empty((n_inst, max(L - 1, 0)), dtype=torch.int32, device=t.device)
+    total = torch.empty(n_inst, dtype=torch.float64, device=t.device)
+    _check(load().ppo_min_sum_partition(_dev(t, f32), _dev(m, f32), L, _dev(kappa, f32), n_inst,
+                                        C.c_void_p(segs.data_ptr()), C.c_void_p(cuts.data_ptr()),
+                                        C.c_void_p(total.data_ptr()), _stream(stream)))
+    return segs, cuts, total
 
 
 def ppo_chain_from_dag(n_vertices, edges, weight, out_size):

@@ -19,6 +19,8 @@ hipError_t launch_cluster_tables(const float*, const float*, const float*, const
 hipError_t launch_cluster_solve(int, int, int, int, bool, const void*, void*, uint64_t*, float*, int32_t*, int32_t*,
                                 int32_t*, hipStream_t);
 hipError_t launch_cluster_tables_from_prepared(const Layout&, const void*, int, void*, hipStream_t);
+hipError_t launch_min_sum_partition(const float*, const float*, int, const float*, int, int32_t*, int32_t*, double*,
+                                    hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -243,6 +245,22 @@ int ppo_solve_cluster(const float* t, const float* m, int L, const float* M, con
                                           segs_out + first, cuts_out ? cuts_out + first * (size_t)(n - 1) : nullptr,
                                           order_out + first * (size_t)n, s),
                 "cluster DP launch");
+    }
+    return PPO_OK;
+}
+
+int ppo_min_sum_partition(const float* t, const float* m, int L, const float* kappa, int n_inst, int32_t* segs_out,
+                          int32_t* cuts_out, double* sum_out, void* stream) {
+    if (L < 1 || n_inst < 0) return PPO_EINVAL;
+    if (L > PPO_MAX_L) return PPO_ETOOBIG;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !kappa || !segs_out || !sum_out || (L > 1 && !cuts_out) || misaligned(sum_out, 8)) return PPO_EINVAL;
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int cnt = n_inst - first < kInstPerLaunch ? n_inst - first : kInstPerLaunch;
+        PPO_HIP(ppo::launch_min_sum_partition(t + (size_t)first * L, m + (size_t)first * L, L, kappa + first, cnt,
+                                              segs_out + first, cuts_out ? cuts_out + (size_t)first * (L - 1) : nullptr,
+                                              sum_out + first, static_cast<hipStream_t>(stream)),
+                "min-sum partition launch");
     }
     return PPO_OK;
 }

@@ -118,3 +118,16 @@ def test_cluster_entry_point_without_a_gpu(lib):
     assert lib.ppo_solve_cluster(*args(10, 3, 1, 2, C.c_void_p(0x1010))) == binding.PPO_EINVAL
     assert lib.ppo_solve_cluster(*args(10, 3, 1, 2, p, 64)) == binding.PPO_ENOSPC
     assert lib.ppo_solve_cluster(p, p, 10, p, p, 3, 1, 2, null, p, p, p, p, 1 << 30, s) == binding.PPO_EINVAL
+
+
+def test_partition_and_front_end_refuse_bad_arguments(lib):
+    p, null, s = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0)
+    assert lib.ppo_min_sum_partition(p, p, 0, p, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_min_sum_partition(p, p, 129, p, 1, p, p, p, s) == binding.PPO_ETOOBIG
+    assert lib.ppo_min_sum_partition(p, p, 10, p, -1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_min_sum_partition(p, p, 10, p, 0, null, null, null, s) == binding.PPO_OK
+    assert lib.ppo_min_sum_partition(p, p, 10, null, 1, p, p, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_min_sum_partition(p, p, 10, p, 1, p, null, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_min_sum_partition(p, p, 10, p, 1, p, p, C.c_void_p(0x1004), s) == binding.PPO_EINVAL
+    assert lib.ppo_chain_from_dag(0, 0, null, null, p, p, 4, p, p, p, p) == binding.PPO_EINVAL
+    assert lib.ppo_chain_from_dag(3, 2, null, p, p, p, 4, p, p, p, p) == binding.PPO_EINVAL
