@@ -199,3 +199,35 @@ def test_layer_graph_to_placement(ppo):
     beta, p, cuts, order = CO.exhaustive(t, m, M, w.B[0])
     assert bits(got[0][0]) == bits(beta) and got[1][0] == p >= 4
     assert np.array_equal(got[2][0], cuts) and np.array_equal(got[3][0], order)
+
+
+def test_more_instances_than_one_launch_takes(ppo):
+    """40,000 instances: the tables, the level launches and the trace all go in several pieces (a launch
+    covers 32,768 instances at most); sampled instances against the oracle."""
+    import torch
+    w = W.random_instances(77, 40000, 10, 4, capacity_factor=2.0)
+    print("cluster, 40000 instances", flush=True)
+    out = solve(ppo, w)
+    rng = np.random.default_rng(0)
+    for i in list(rng.choice(w.n_inst, 200, replace=False)) + [0, 32767, 32768, w.n_inst - 1]:
+        b, p, cu, o = CO.subset_dp(w.t[i], w.m[i], w.M[i], w.B[i])
+        assert bits(out[0][i]) == bits(b) and out[1][i] == p, i
+        assert np.array_equal(out[2][i], cu) and np.array_equal(out[3][i], o), i
+    # the fixed-k routes on as many
+    w3 = W.random_instances(78, 40000, 8, 3, capacity_factor=1.6)
+    dev = ppo.to_device(w3)
+    print("fixed k, 40000 instances", flush=True)
+    full = tuple(x.cpu().numpy() for x in ppo.ppo_solve(*dev))
+    ws = ppo.alloc_workspace(8, 3, w3.n_inst)
+    keys = torch.empty(w3.n_inst, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_prepare(*dev, ws)
+    ppo.ppo_init_keys(keys)
+    ppo.ppo_solve_subsets(8, 3, w3.n_inst, ws, keys)
+    sub = tuple(x.cpu().numpy() for x in ppo.ppo_finalize(8, 3, w3.n_inst, ws, keys))
+    torch.cuda.synchronize()
+    for a, b in zip(full, sub):
+        assert np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a, b.view(np.uint32) if b.dtype == np.float32 else b)
+    for sl in (slice(0, 150), slice(32700, 32850), slice(-150, None)):
+        ref = O.bruteforce(w3.t[sl], w3.m[sl], w3.M[sl], w3.B[sl])
+        assert np.array_equal(bits(full[0][sl]), bits(ref[0])) and np.array_equal(full[2][sl], ref[2])
+        assert np.array_equal(full[1][sl], ref[1])
