@@ -398,8 +398,20 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp((int)after_here, (int)v, 0x130, 0xF, 0xF, false);
             uint32_t cur = cl_pk_min(v, (v >> 16) | (next << 16));
             run32[(kClRunRow / 2) + lane] = cur;
+            {
+                // runs of 4 and of 8: the dwords one and two lanes up come by wave shifts too; what enters at
+                // lane 63 are the entries 128 .. 131 of the row before, known beforehand
+                const uint32_t tail = after_here | (kClInf << 16);
+                const uint32_t up1 = (uint32_t)__builtin_amdgcn_update_dpp((int)tail, (int)cur, 0x130, 0xF, 0xF, false);
+                cur = cl_pk_min(cur, up1);
+                run32[2 * (kClRunRow / 2) + lane] = cur;
+                const uint32_t s1 = (uint32_t)__builtin_amdgcn_update_dpp((int)tail, (int)cur, 0x130, 0xF, 0xF, false);
+                const uint32_t up2 = (uint32_t)__builtin_amdgcn_update_dpp((int)inf2, (int)s1, 0x130, 0xF, 0xF, false);
+                cur = cl_pk_min(cur, up2);
+                run32[3 * (kClRunRow / 2) + lane] = cur;
+            }
 #pragma unroll
-            for (int k = 2; k < kClRunLevels; ++k) {
+            for (int k = 4; k < kClRunLevels; ++k) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 cur = cl_pk_min(cur, run32[(k - 1) * (kClRunRow / 2) + lane + (1 << (k - 2))]);
