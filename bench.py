@@ -70,6 +70,30 @@ def copy_probe(torch):
     del src, dst
 
 
+def bench_partition(args, torch, ppo, workloads):
+    """Not the headline: the paper's partitioning step (least sum of transfer sizes), instances per second."""
+    w = workloads.transformer_encoder()
+    t, m, _, _ = ppo.to_device(w)
+    kappa = torch.full((w.n_inst,), 0.2 * float(w.m[0].sum()), dtype=torch.float32, device="cuda:0")
+    out = None
+    for _ in range(args.warmup):
+        out = ppo.ppo_min_sum_partition(t, m, kappa)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = ppo.ppo_min_sum_partition(t, m, kappa)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    print(json.dumps({
+        "metric": f"chains partitioned/sec at L={w.L} (least sum of transfer sizes, the paper's Alg. 1)",
+        "value": w.n_inst / (wall / args.steps), "unit": "instances/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_inst} chains of L={w.L}, capacity 0.2 of the model",
+                   "segments_found": [int(x) for x in out[0].cpu().numpy()[:8]]},
+        "roofline": None}), flush=True)
+
+
 def bench_cluster(args, torch, ppo, workloads):
     """Not the headline: whole exact solves per second of the cluster form (ppo_solve_cluster)."""
     N = args.cluster
@@ -129,6 +153,9 @@ def main():
                          "free; L=100, mixed capacities): a separate figure in instances per second")
     ap.add_argument("--cluster-instances", type=int, default=0, help="instances per step with --cluster")
     ap.add_argument("--max-segments", type=int, default=0, help="with --cluster: most segments allowed (default N)")
+    ap.add_argument("--partition", action="store_true",
+                    help="time ppo_min_sum_partition (the paper's own partitioning step) on 4096 chains of L=96: "
+                         "a separate figure in instances per second")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes 256 MiB: the known "
                          "traffic the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -146,6 +173,8 @@ def main():
     ppo.load()
     if args.cluster:
         return bench_cluster(args, torch, ppo, workloads)
+    if args.partition:
+        return bench_partition(args, torch, ppo, workloads)
     w = workloads.WORKLOADS[args.workload]()
     L, k, n = w.L, w.k, w.n_inst
     kf = math.factorial(k)
