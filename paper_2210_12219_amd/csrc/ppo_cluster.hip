@@ -453,7 +453,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
 // the candidates for the next node are tried side by side, one wave each; the smallest node whose best
 // completion still equals the optimum is taken.
 // ---------------------------------------------------------------------------------------------
-constexpr int kClTraceWaves = 16;
+constexpr int kClTraceWaves = 16;   // at most; a launch uses min(n, 16) waves per workgroup
 
 __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(ClusterLayout y,
                                                                           const unsigned char* __restrict__ ws,
@@ -480,11 +480,12 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     float* beta = beta_out ? beta_out + inst : nullptr;
     int32_t* order = order_out ? order_out + (size_t)inst * n : nullptr;
     int32_t* cuts = cuts_out ? cuts_out + (size_t)inst * (n - 1) : nullptr;
-    for (int i = tid; i < n * (L + 1); i += kClTraceWaves * 64) hi_s[i] = base[y.hi_off + i];
+    const int threads = blockDim.x, waves = threads >> 6;
+    for (int i = tid; i < n * (L + 1); i += threads) hi_s[i] = base[y.hi_off + i];
     if (order)
-        for (int i = tid; i < n; i += kClTraceWaves * 64) order[i] = -1;
+        for (int i = tid; i < n; i += threads) order[i] = -1;
     if (cuts)
-        for (int i = tid; i < n - 1; i += kClTraceWaves * 64) cuts[i] = -1;
+        for (int i = tid; i < n - 1; i += threads) cuts[i] = -1;
     __syncthreads();
     auto wave_min = [&](uint32_t v) -> uint32_t {
         for (int off = 32; off >= 1; off >>= 1) {
@@ -508,7 +509,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
     uint32_t used = 0;
     int last = -1, p = 0;
     for (int s = 0; s < pmax; ++s) {
-        for (int j = wave; j < n; j += kClTraceWaves) {
+        for (int j = wave; j < n; j += waves) {
             if ((used >> j) & 1u) {
                 if (lane == 0) comp[j] = 0xFFFFFFFFu;
                 continue;
@@ -561,7 +562,7 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         for (int j = n - 1; j >= 0; --j)
             if (comp[j] == best) chosen = j;
         if (chosen < 0) break;   // cannot happen: some completion of the prefix reaches `best`
-        for (int e = tid; e <= L; e += kClTraceWaves * 64) D[s][e] = cand[chosen][e];
+        for (int e = tid; e <= L; e += threads) D[s][e] = cand[chosen][e];
         if (tid == 0) seq[s] = chosen;
         // the prefix itself is optimal: it sorts before its extensions (exact: only a full permutation ends)
         const bool complete = exact ? s == n - 1 : cand[chosen][L] <= best;
@@ -723,7 +724,8 @@ hipError_t launch_cluster_solve(int L, int n, int n_inst, int pmax, bool exact, 
                                       exact ? 1 : 0);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(kClTraceWaves * 64), 0, stream, y, w, r, pmax,
+    const int trace_waves = n < kClTraceWaves ? n : kClTraceWaves;   // one wave per candidate node
+    hipLaunchKernelGGL(cluster_trace_kernel, dim3(n_inst), dim3(trace_waves * 64), 0, stream, y, w, r, pmax,
                        exact ? 1 : 0, reinterpret_cast<unsigned long long*>(key_out), beta_out, segs_out, cuts_out,
                        order_out);
     return hipGetLastError();
