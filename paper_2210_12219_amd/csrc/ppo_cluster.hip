@@ -13,7 +13,7 @@
 // (q_{a,b}[i] = t[i] / B[a][b], Eq. 3) and beta* = min over j of A[All][j][0].  Rows are computed level by
 // level in |R|, one launch per level, one wave per row, on 16-bit order codes of the quotients.  The
 // lexicographically smallest optimal sequence (a sequence before its extensions) is rebuilt position by
-// position from forward rows of the prefix combined with `rest`, then the cuts by the fixed-k cut rule.
+// position from the cuts the prefix reaches within beta* and the rows of A, then the cuts by the fixed-k cut rule.
 #include <array>
 #include <utility>
 
@@ -26,7 +26,6 @@ namespace ppo {
 // Everything these kernels read as a code is written by them as one (a stray pattern could win that minimum).
 constexpr uint32_t kClZero = kCodeZero, kClInf = kCodeInf;
 constexpr int kClPreThreads = 1024;
-constexpr int kClRow = PPO_MAX_L + 2;
 static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) + 1 < (int)kClInf,
               "codes stay below +inf");
 
@@ -196,40 +195,6 @@ __global__ __launch_bounds__(kClCountThreads) void cluster_count_kernel(ClusterL
     const int i = base[y.ord_off + r];
     reinterpret_cast<uint16_t*>(base + y.qc_off)[p * L + i] = (uint16_t)(kClZero + 1 + below);
     reinterpret_cast<float*>(base + y.dec_off)[1 + below] = x;
-}
-
-// rest[R'][j][e'] for e' = lane, lane + 64, ... <= L into `out` (one wave).  A: rows of the instance.
-__device__ __forceinline__ void cluster_rest_row(const ClusterLayout& y, const uint16_t* __restrict__ qc,
-                                                 const uint16_t* __restrict__ A, uint32_t rprime, int j, bool more,
-                                                 bool exact, int lane, uint16_t* out) {
-    const int L = y.L, n = y.n;
-    const uint16_t* Ar = A + (size_t)cluster_first_row(rprime, n) * y.rs;   // the rows of R', members in order
-    for (int e = lane; e <= L; e += 64) {
-        uint32_t v = kClInf;
-        if (e == L) {
-            v = (exact && rprime != 0u) ? kClInf : kClZero;   // every node has to be used: the chain may end only then
-        } else if (e >= 1 && more) {
-            // all loads first (the set is the same for every lane, so the branches are scalar), then the folding
-            uint32_t a[PPO_CLUSTER_MAX_N], q[PPO_CLUSTER_MAX_N];
-            int r = 0;
-#pragma unroll
-            for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
-                a[j2] = kClInf;
-                q[j2] = kClInf;
-                if ((rprime >> j2) & 1u) {
-                    q[j2] = qc[pair_index(j, j2, n) * L + (e - 1)];
-                    a[j2] = Ar[(size_t)r * y.rs + e];
-                    ++r;
-                }
-            }
-#pragma unroll
-            for (int j2 = 0; j2 < PPO_CLUSTER_MAX_N; ++j2) {
-                const uint32_t c = q[j2] > a[j2] ? q[j2] : a[j2];
-                v = c < v ? c : v;
-            }
-        }
-        out[e] = (uint16_t)v;
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -449,9 +414,13 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
 }
 
 // ---------------------------------------------------------------------------------------------
-// The optimum, the smallest optimal sequence and its cuts: one workgroup per instance.  At each position
-// the candidates for the next node are tried side by side, one wave each; the smallest node whose best
-// completion still equals the optimum is taken.
+// The optimum, the smallest optimal sequence and its cuts: one workgroup per instance.  With beta* known
+// (the least A[All][j][0]) every further question is a yes or no, "can this be done with all links at most
+// beta*", so the walk keeps sets of cuts as bit masks: F = cuts that the chosen prefix reaches (all its links
+// at most beta*), G_j = those of F whose link into candidate j is at most beta*.  Candidate j at a position
+// completes to an optimum iff A[unused][j][e] <= beta* for some e in G_j (one row of A, one wave per
+// candidate); the smallest such node is taken, and F for the next position is the set of cuts that a window
+// of that node starting in G_j covers.  hi[j][.] does not decrease, so the latest start below a cut decides.
 // ---------------------------------------------------------------------------------------------
 constexpr int kClTraceWaves = 16;   // at most; a launch uses min(n, 16) waves per workgroup
 
@@ -465,10 +434,9 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
                                                                           int32_t* __restrict__ cuts_out,
                                                                           int32_t* __restrict__ order_out) {
     __shared__ unsigned char hi_s[PPO_CLUSTER_MAX_N * (PPO_MAX_L + 1)];
-    __shared__ uint16_t D[PPO_CLUSTER_MAX_N][kClRow];      // forward rows of the chosen prefix
-    __shared__ uint16_t cand[PPO_CLUSTER_MAX_N][kClRow];   // forward row of the prefix extended by node j
-    __shared__ uint16_t rest_s[kClTraceWaves][kClRow];
-    __shared__ uint32_t comp[PPO_CLUSTER_MAX_N];           // least bottleneck over the completions of prefix + j
+    __shared__ unsigned long long cand_s[PPO_CLUSTER_MAX_N][2];    // G_j of every candidate of this position
+    __shared__ unsigned long long start_s[PPO_CLUSTER_MAX_N][2];   // G of the node chosen at every position
+    __shared__ uint32_t ok_s[PPO_CLUSTER_MAX_N];
     __shared__ int seq[PPO_CLUSTER_MAX_N];
     const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -506,66 +474,62 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         }
         return;
     }
+    // is cut e2 (1 <= e2 <= L) inside the window of node j that starts at the latest cut of (g0, g1) below e2?
+    auto covered = [&](unsigned long long g0, unsigned long long g1, int j, int e2) -> bool {
+        unsigned long long m0 = g0, m1 = 0;
+        if (e2 < 64)
+            m0 = g0 & ((1ull << e2) - 1ull);
+        else
+            m1 = e2 >= 128 ? g1 : g1 & ((1ull << (e2 - 64)) - 1ull);
+        const int from = m1 ? 127 - __clzll((long long)m1) : m0 ? 63 - __clzll((long long)m0) : -1;
+        return from >= 0 && hi(j, from) >= e2;
+    };
+    unsigned long long F0 = 1ull, F1 = 0ull;   // the first segment starts at 0
     uint32_t used = 0;
     int last = -1, p = 0;
     for (int s = 0; s < pmax; ++s) {
+        const uint32_t unused = all & ~used;
+        const uint32_t first_row = cluster_first_row(unused, n);
         for (int j = wave; j < n; j += waves) {
             if ((used >> j) & 1u) {
-                if (lane == 0) comp[j] = 0xFFFFFFFFu;
+                if (lane == 0) ok_s[j] = 0u;
                 continue;
             }
-            uint16_t* f2 = cand[j];
-            if (s == 0) {
-                for (int e = lane; e <= L; e += 64) f2[e] = (uint16_t)((e >= 1 && e <= hi(j, 0)) ? kClZero : kClInf);
-            } else {
-                // f2[e2] = min over cuts i in [s, e2) with layers [i, e2) fitting j of max(D[s-1][i], q[i-1]):
-                // the maxima first, side by side, into the wave's row; then every lane walks its window in LDS
-                const uint16_t* f = D[s - 1];
-                const uint16_t* q = qc + pair_index(last, j, n) * L;
-                uint16_t* g = rest_s[wave];
-                for (int i = lane; i <= L; i += 64) {
-                    uint32_t c = kClInf;
-                    if (i >= 1 && i <= L - 1) {
-                        const uint32_t a = f[i], b = q[i - 1];
-                        c = a > b ? a : b;
-                    }
-                    g[i] = (uint16_t)c;
+            const uint16_t* __restrict__ a = A + (size_t)(first_row + (uint32_t)__popc(unused & ((1u << j) - 1u))) * y.rs;
+            const uint16_t* __restrict__ q = qc + (s ? pair_index(last, j, n) * L : 0);
+            unsigned long long g[2], ok[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e = lane + 64 * h;
+                bool in_g = false, in_ok = false;
+                if ((((h ? F1 : F0) >> lane) & 1ull) && e < L) {
+                    in_g = s == 0 || (uint32_t)q[e - 1] <= best;   // beyond the first position F holds no cut 0
+                    in_ok = in_g && (uint32_t)a[e] <= best;
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                for (int e2 = lane; e2 <= L; e2 += 64) {
-                    uint32_t v = kClInf;
-                    for (int i = e2 - 1; i >= s && hi(j, i) >= e2; --i) {
-                        const uint32_t c = g[i];
-                        v = c < v ? c : v;
-                    }
-                    f2[e2] = (uint16_t)v;
-                }
-                __builtin_amdgcn_wave_barrier();   // g is the row `rest` is written to next
+                g[h] = __ballot(in_g);
+                ok[h] = __ballot(in_ok);
             }
-            uint16_t* rest = rest_s[wave];
-            cluster_rest_row(y, qc, A, all & ~used & ~(1u << j), j, s + 1 < pmax, exact != 0, lane, rest);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            uint32_t v = kClInf;
-            for (int e = lane; e <= L; e += 64) {
-                const uint32_t a = f2[e], b = rest[e];
-                const uint32_t c = a > b ? a : b;
-                v = (e >= 1 && c < v) ? c : v;
+            if (lane == 0) {
+                cand_s[j][0] = g[0];
+                cand_s[j][1] = g[1];
+                ok_s[j] = (ok[0] | ok[1]) != 0ull ? 1u : 0u;
             }
-            v = wave_min(v);
-            if (lane == 0) comp[j] = v;
-            __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
         int chosen = -1;
         for (int j = n - 1; j >= 0; --j)
-            if (comp[j] == best) chosen = j;
+            if (ok_s[j]) chosen = j;
         if (chosen < 0) break;   // cannot happen: some completion of the prefix reaches `best`
-        for (int e = tid; e <= L; e += threads) D[s][e] = cand[chosen][e];
-        if (tid == 0) seq[s] = chosen;
+        const unsigned long long G0 = cand_s[chosen][0], G1 = cand_s[chosen][1];
+        if (tid == 0) {
+            seq[s] = chosen;
+            start_s[s][0] = G0;
+            start_s[s][1] = G1;
+        }
         // the prefix itself is optimal: it sorts before its extensions (exact: only a full permutation ends)
-        const bool complete = exact ? s == n - 1 : cand[chosen][L] <= best;
+        const bool complete = exact ? s == n - 1 : covered(G0, G1, chosen, L);
+        F0 = __ballot(lane >= 1 && lane < L && covered(G0, G1, chosen, lane));
+        F1 = __ballot(lane + 64 < L && covered(G0, G1, chosen, lane + 64));
         __syncthreads();
         used |= 1u << chosen;
         last = chosen;
@@ -583,21 +547,18 @@ __global__ __launch_bounds__(kClTraceWaves * 64) void cluster_trace_kernel(Clust
         key_out[inst] = ((unsigned long long)__float_as_uint(dec[best - kClZero]) << 32) | rank;
     }
     if (!cuts && !beta) return;
-    // cuts: latest segment first, each time the smallest cut that keeps the bottleneck at `best`
+    // cuts: latest segment first, each time the smallest start (reached by the prefix, link at most beta*)
+    // whose window covers the end
     int e = L;
     for (int s = p - 1; s >= 1 && cuts; --s) {
-        const int js = seq[s], jl = seq[s - 1];
-        const uint16_t* f = D[s - 1];
-        const uint16_t* q = qc + pair_index(jl, js, n) * L;
-        uint32_t first = 0xFFFFFFFFu;
-        for (int i = s + lane; i < e; i += 64) {
-            const uint32_t a = f[i], b = q[i - 1];
-            const uint32_t c = a > b ? a : b;
-            if (hi(js, i) >= e && c <= best && (uint32_t)i < first) first = (uint32_t)i;
-        }
-        first = wave_min(first);
+        const int js = seq[s];
+        const unsigned long long m0 = __ballot(((start_s[s][0] >> lane) & 1ull) && lane < e && hi(js, lane) >= e);
+        const unsigned long long m1 =
+            __ballot(((start_s[s][1] >> lane) & 1ull) && lane + 64 < e && hi(js, lane + 64 < L ? lane + 64 : L) >= e);
+        if (!(m0 | m1)) break;   // cannot happen: e was reached from such a start
+        const int first = m0 ? __ffsll((long long)m0) - 1 : 63 + __ffsll((long long)m1);
         if (lane == 0) cuts[s - 1] = (int32_t)first;
-        e = (int)first;
+        e = first;
     }
     if (lane == 0) {
         if (beta) *beta = dec[best - kClZero];
