@@ -577,7 +577,9 @@ __global__ __launch_bounds__(256) void cluster_tables_from_prepared_kernel(Layou
     const int L = y.L, n = y.n, inst = blockIdx.x, tid = threadIdx.x;
     const unsigned char* src = fixed_ws + (size_t)inst * f.stride;
     unsigned char* dst = ws + (size_t)inst * y.stride;
-    const unsigned char* lo = src + f.lo_off;
+    __shared__ unsigned char lo[PPO_MAX_K * (PPO_MAX_L + 1)];
+    for (int idx = tid; idx < n * (L + 1); idx += 256) lo[idx] = src[f.lo_off + idx];
+    __syncthreads();
     for (int idx = tid; idx < n * (L + 1); idx += 256) {
         const int j = idx / (L + 1), e = idx - j * (L + 1);
         int e2 = e;

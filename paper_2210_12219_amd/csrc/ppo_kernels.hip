@@ -289,6 +289,8 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
                                                        float* __restrict__ beta_out, int32_t* __restrict__ cuts_out,
                                                        int32_t* __restrict__ order_out) {
     __shared__ uint16_t rows[PPO_MAX_K][PPO_MAX_L + 1];
+    __shared__ uint16_t q_s[PPO_MAX_K][PPO_MAX_L];              // [s]: link into the node at position s
+    __shared__ unsigned char lo_s[PPO_MAX_K][PPO_MAX_L + 1];   // [s]: window starts of the node at position s
     const int L = y.L, k = y.k, inst = blockIdx.x, lane = threadIdx.x;
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const unsigned char* lo_t = base + y.lo_off;
@@ -306,18 +308,23 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
         }
         return;
     }
-    // the rows of the winner's DP: one wave, lanes over the segment end
+    // the rows of the winner's DP: one wave, lanes over the segment end; the quotient codes of its links and
+    // the window starts of its nodes are staged first (loads that do not depend on each other)
     const uint64_t perm = unrank_packed(r, k);
-    {
-        const unsigned char* lo0 = lo_t + perm_at(perm, 0) * (L + 1);
-        for (int e = lane; e <= L; e += 64)
-            rows[0][e] = (uint16_t)((e >= 1 && e <= L - (k - 1) && lo0[e] == 0) ? kCodeZero : kCodeInf);
+    for (int s = 0; s < k; ++s) {
+        const unsigned char* lo = lo_t + perm_at(perm, s) * (L + 1);
+        for (int e = lane; e <= L; e += 64) lo_s[s][e] = lo[e];
+        if (s == 0) continue;
+        const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), perm_at(perm, s), k) * L;
+        for (int i = lane; i < L; i += 64) q_s[s][i] = q[i];
     }
     __syncthreads();
+    for (int e = lane; e <= L; e += 64)
+        rows[0][e] = (uint16_t)((e >= 1 && e <= L - (k - 1) && lo_s[0][e] == 0) ? kCodeZero : kCodeInf);
+    __syncthreads();
     for (int s = 1; s < k; ++s) {
-        const int node = perm_at(perm, s);
-        const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), node, k) * L;
-        const unsigned char* lo = lo_t + node * (L + 1);
+        const uint16_t* q = q_s[s];
+        const unsigned char* lo = lo_s[s];
         for (int e = lane; e <= L; e += 64) {
             uint32_t acc = kCodeInf;
             if (e >= s + 1 && e <= L - (k - 1 - s)) {
@@ -332,31 +339,33 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
         }
         __syncthreads();
     }
-    if (lane != 0) return;
     const uint32_t beta_code = rows[k - 1][L];
-    beta_out[inst] = (beta_code >= kCodeInf) ? __uint_as_float(kInfBits) : dec[beta_code - kCodeZero];
-    for (int s = 0; s < k; ++s) order[s] = perm_at(perm, s);
+    if (lane == 0) {
+        beta_out[inst] = (beta_code >= kCodeInf) ? __uint_as_float(kInfBits) : dec[beta_code - kCodeZero];
+        for (int s = 0; s < k; ++s) order[s] = perm_at(perm, s);
+    }
+    // rule T2, latest segment first: the smallest cut of the window that keeps the bottleneck (lanes over the cuts)
     int e = L;
     for (int s = k - 1; s >= 1; --s) {
-        const int node = perm_at(perm, s);
-        const uint16_t* q = qc + pair_index(perm_at(perm, s - 1), node, k) * L;
-        const unsigned char* lo = lo_t + node * (L + 1);
-        int first = lo[e] > s ? lo[e] : s;
+        const uint16_t* q = q_s[s];
+        const int first = lo_s[s][e] > s ? lo_s[s][e] : s;
         int chosen = -1;
-        for (int i = first; i < e; ++i) {
-            uint32_t d = rows[s - 1][i], g = q[i - 1];
-            uint32_t c = d > g ? d : g;
-            if (c <= beta_code) { chosen = i; break; }
+        for (int i0 = first; i0 < e && chosen < 0; i0 += 64) {
+            const int i = i0 + lane;
+            bool keeps = false;
+            if (i < e) {
+                const uint32_t d = rows[s - 1][i], g = q[i - 1];
+                keeps = (d > g ? d : g) <= beta_code;
+            }
+            const unsigned long long found = __ballot(keeps);
+            if (found) chosen = i0 + __ffsll((long long)found) - 1;
         }
-        cuts[s - 1] = chosen;
+        if (lane == 0) cuts[s - 1] = chosen;
         if (chosen < 0) break;  // cannot happen for a key produced by the enumeration
         e = chosen;
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// host-side launchers (called from the C ABI)
-// ---------------------------------------------------------------------------------------------
 hipError_t launch_precompute(const float* t, const float* m, const float* M, const float* B, const Layout& y,
                              int n_inst, void* ws, hipStream_t stream) {
     hipLaunchKernelGGL(precompute_kernel, dim3(n_inst), dim3(kPreThreads), 0, stream, t, m, M, B, y,
