@@ -15,6 +15,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ppo_oracle.c")
 _LIB = os.path.join(_HERE, "libppo_oracle.so")
+# The mutation tests (tests/test_oracle_mutants.py) point this at an altered copy of the source to show that the
+# pins notice; the library is then built beside that copy.
+if os.environ.get("PPO_ORACLE_SOURCE"):
+    _SRC = os.path.abspath(os.environ["PPO_ORACLE_SOURCE"])
+    _LIB = os.path.join(os.path.dirname(_SRC), "libppo_oracle_mutant.so")
 
 ERRORS = {0: "ok", -1: "invalid argument", -2: "too big", -3: "data precondition violated", -4: "out of memory"}
 

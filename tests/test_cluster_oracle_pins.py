@@ -108,6 +108,29 @@ def test_closed_forms(route):
 
 
 @pytest.mark.parametrize("route", ROUTES)
+def test_memory_rule_is_taken_in_binary64(route):
+    """2^24 + 1 does not fit a node of capacity 2^24 (it would after rounding the sum to binary32)."""
+    f = ROUTES[route]
+    big = np.float32(2.0 ** 24)
+    t = np.array([3, 5, 7], np.float32)
+    m = np.array([1, big, 1], np.float32)
+    B = np.array([[0, 1, 1], [1, 0, 1], [1, 1, 0]], np.float32)
+    # three nodes of 2^24: only [1 | 2^24 | 1] fits, link times 3 and 5
+    beta, p, cuts, order = f(t, m, np.array([big, big, big], np.float32), B)
+    assert (float(beta), p, list(order), list(cuts)) == (5.0, 3, [0, 1, 2], [1, 2])
+    # two segments at most: no cut leaves both parts within 2^24
+    beta, p, _, _ = f(t, m, np.array([big, big, big], np.float32), B, 2)
+    assert np.isinf(beta) and p == 0
+    # a node of 2^24 + 2 holds the whole model exactly
+    beta, p, _, order = f(t, m, np.array([big, big + np.float32(2), big], np.float32), B, 2)
+    assert (float(beta), p, int(order[0])) == (0.0, 1, 1)
+    # one more layer of weight 1: [1 | 2^24, 1, 1] with the larger node second is the only cut at t[0] = 3
+    beta, p, cuts, order = f(np.array([3, 5, 7, 9], np.float32), np.array([1, big, 1, 1], np.float32),
+                             np.array([big, big + np.float32(2), big], np.float32), B, 2)
+    assert (float(beta), p, list(order[:2]), list(cuts[:1])) == (3.0, 2, [0, 1], [1])
+
+
+@pytest.mark.parametrize("route", ROUTES)
 def test_more_segments_can_beat_fewer(route):
     """Capacities force the only two-segment cut onto the largest tensor; a third node lets the chain
     be cut at the two small tensors instead."""

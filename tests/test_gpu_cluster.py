@@ -68,6 +68,22 @@ def test_cluster_small_shapes_ties_and_infeasible(ppo):
             assert_same(solve(ppo, w, pmax), ref, f"cluster L={L} n={n} pmax={pmax} seed={seed}")
 
 
+def test_cluster_memory_rule_in_binary64(ppo):
+    """Weights near 2^24: a segment of 2^24 + 1 does not fit a node of 2^24 (binary64 sums and comparison)."""
+    big = np.float32(2.0 ** 24)
+    rng = np.random.default_rng(78)
+    L, n, cnt = 6, 4, 48
+    t = rng.integers(1, 9, (cnt, L)).astype(np.float32)
+    m = rng.choice(np.array([1, 2, 3, big, big + np.float32(2)], np.float32), (cnt, L), p=[0.3, 0.2, 0.2, 0.2, 0.1])
+    M = rng.choice(np.array([big, big + np.float32(2), big + np.float32(4), 4], np.float32), (cnt, n))
+    B = np.ones((cnt, n, n), np.float32)
+    w = W.Workload("near 2^24", L, n, cnt, 78, t, m, M, B)
+    for pmax in (2, 4):
+        ref = oracle(w, pmax, CO.bruteforce)
+        assert np.isfinite(ref[0]).sum() >= 6 and np.isinf(ref[0]).sum() >= 6
+        assert_same(solve(ppo, w, pmax), ref, f"cluster near 2^24, pmax={pmax}")
+
+
 def test_cluster_brute_force_definition(ppo):
     w = W.random_instances(11, 16, 9, 5, capacity_factor=2.0, quantised=True)
     print("cluster brute force L=9 n=5", flush=True)

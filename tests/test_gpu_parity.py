@@ -147,6 +147,36 @@ def test_degenerate_shapes(ppo):
     assert_same(got, O.bruteforce(w.t, w.m, w.M, w.B), "t=0")
 
 
+def test_memory_rule_in_binary64(ppo):
+    """Sums of weights near 2^24, where binary32 sums or a binary32 comparison would let a segment of
+    2^24 + 1 into a node of 2^24: every stage-2 route against the oracle's definition route."""
+    import torch
+    big = np.float32(2.0 ** 24)
+    rng = np.random.default_rng(77)
+    L, k, n = 6, 3, 64
+    t = rng.integers(1, 9, (n, L)).astype(np.float32)
+    m = rng.choice(np.array([1, 2, 3, big, big + np.float32(2)], np.float32), (n, L), p=[0.3, 0.2, 0.2, 0.2, 0.1])
+    M = rng.choice(np.array([big, big + np.float32(2), big + np.float32(4), 4], np.float32), (n, k))
+    B = np.ones((n, k, k), np.float32)
+    w = W.Workload("near 2^24", L, k, n, 77, t, m, M, B)
+    ref = O.bruteforce(w.t, w.m, w.M, w.B)
+    assert np.isfinite(ref[0]).sum() >= 8 and np.isinf(ref[0]).sum() >= 8
+    assert_same(gpu_solve(ppo, w), ref, "near 2^24")
+    dev = ppo.to_device(w)
+    ws = ppo.alloc_workspace(L, k, n)
+    for route in ("bounded", "subsets"):
+        keys = torch.empty(n, dtype=torch.int64, device="cuda:0")
+        ppo.ppo_prepare(*dev, ws)
+        ppo.ppo_init_keys(keys)
+        if route == "bounded":
+            ppo.ppo_solve_range_bounded(L, k, n, ws, 0, math.factorial(k), keys, None)
+        else:
+            ppo.ppo_solve_subsets(L, k, n, ws, keys)
+        out = tuple(x.cpu().numpy() for x in ppo.ppo_finalize(L, k, n, ws, keys))
+        torch.cuda.synchronize()
+        assert_same(out, ref, f"near 2^24, {route}")
+
+
 def test_empty_batch(ppo):
     import torch
     z = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda:0")

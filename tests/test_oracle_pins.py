@@ -189,6 +189,30 @@ def test_capacity_hit_exactly_counts_as_fitting():
         assert np.isinf(beta[0])
 
 
+def test_memory_rule_is_taken_in_binary64():
+    """Segment sizes are sums of binary32 weights taken in binary64 and compared there with the capacity:
+    2^24 + 1 exceeds a capacity of 2^24, although it rounds to 2^24 in binary32 (by hand, both ways)."""
+    big = np.float32(2.0 ** 24)
+    for route in ROUTES.values():
+        # one node: the whole model must fit it
+        beta, _, order = route(np.array([1, 1], np.float32), np.array([big, 1], np.float32),
+                               np.array([big], np.float32), const_bandwidth(1, 1.0))
+        assert np.isinf(beta[0]) and order.tolist() == [[-1]]
+        beta, _, _ = route(np.array([1, 1, 1], np.float32), np.array([big, 1, 1], np.float32),
+                           np.array([big], np.float32), const_bandwidth(1, 1.0))   # 2^24 + 1 + 1, summed in order
+        assert np.isinf(beta[0])
+        beta, _, _ = route(np.array([1, 1], np.float32), np.array([big, 1], np.float32),
+                           np.array([big + np.float32(2)], np.float32), const_bandwidth(1, 1.0))
+        assert float(beta[0]) == 0.0
+        # two nodes: neither cut leaves both segments within 2^24
+        t = np.array([3, 5, 7], np.float32)
+        m = np.array([1, big, 1], np.float32)
+        beta, cuts, _ = route(t, m, np.array([big, big], np.float32), const_bandwidth(2, 1.0))
+        assert np.isinf(beta[0]) and cuts.tolist() == [[-1]]
+        beta, cuts, _ = route(t, m, np.array([big, big + np.float32(2)], np.float32), const_bandwidth(2, 1.0))
+        assert float(beta[0]) == 3.0 and cuts.tolist() == [[1]]   # [1 | 2^24, 1] with the larger node second
+
+
 def test_monotone_in_capacity_and_bandwidth_and_exact_scaling():
     rng = np.random.default_rng(3)
     for seed in range(40):
