@@ -50,6 +50,59 @@ MUTANTS = [
 ]
 
 
+# The Python oracles: (file, pin tests, pytest -k expression, [(text, replacement), ...], what the mistake is).
+# The altered file shadows the real one in a copy of the package placed first on the import path.
+PY_MUTANTS = [
+    ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
+     [("P[e] - P[s] <= float(kappa)", "P[e] - P[s] < float(kappa)"), ("P[e] - P[i] <= float(kappa)", "P[e] - P[i] < float(kappa)")],
+     "both routes: a segment that fills the node exactly no longer fits"),
+    ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
+     [("float(t[c - 1]) + total", "float(t[c]) + total"), ("float(t[e - 1]) if e < L", "float(t[e]) if e < L")],
+     "both routes: tensor of the layer after the cut"),
+    ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
+     [("P.append(P[-1] + float(x))", "P.append(float(x))")], "segment sizes are not cumulative"),
+    ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
+     [("cand = (total, p, cuts)", "cand = (total, -p, cuts)"), ("f[e][0], f[e][1] + 1, e)", "f[e][0], -(f[e][1] + 1), e)")],
+     "both routes: ties go to the most segments"),
+    ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
+     [("if cand < best:\n                best = cand\n        f[i] = best", "if cand[0] < best[0]:\n                best = cand\n        f[i] = best")],
+     "recurrence: ties keep the first end found"),
+    ("oracle/ppo_dag_oracle.py", "tests/test_dag_frontend.py", "hand_worked and oracle",
+     [("1 + max(lp(u) for u in pred[v])", "1 + min(lp(u) for u in pred[v])")], "depth by the shortest path"),
+    ("oracle/ppo_dag_oracle.py", "tests/test_dag_frontend.py", "hand_worked and oracle",
+     [("if len(here) == 1 and every_path_reaches(points[-1], here[0]):", "if len(here) == 1:")],
+     "a vertex of unique depth that some path goes round"),
+    ("oracle/ppo_dag_oracle.py", "tests/test_dag_frontend.py", "hand_worked and oracle",
+     [("if lower < depth[v] <= depth[p]]", "if lower <= depth[v] <= depth[p]]")],
+     "the previous partition point is counted into the next layer as well"),
+    ("oracle/ppo_dag_oracle.py", "tests/test_dag_frontend.py", "hand_worked and oracle",
+     [("t.append(float(out_size[p]))", "t.append(float(weight[p]))")], "transfer size taken from the weights"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(PY_MUTANTS)), ids=[m[4] for m in PY_MUTANTS])
+def test_pins_notice_a_planted_mistake_in_a_python_oracle(case, tmp_path):
+    source, pin_file, select, edits, what = PY_MUTANTS[case]
+    shadow = tmp_path / "oracle"
+    shadow.mkdir()
+    (shadow / "__init__.py").write_text("")
+    text = open(os.path.join(ROOT, source)).read()
+    for old, new in edits:
+        assert text.count(old) >= 1, f"the source no longer holds the text this case alters: {old!r}"
+        text = text.replace(old, new)
+    (shadow / os.path.basename(source)).write_text(text)
+    env = dict(os.environ, PYTHONPATH=os.pathsep.join([str(tmp_path), ROOT, os.environ.get("PYTHONPATH", "")]))
+    cmd = [sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider", "--rootdir", ROOT,
+           os.path.join(ROOT, pin_file)]
+    if select:
+        cmd += ["-k", select]
+    # run from the directory that holds the shadow package: the interpreter puts it first on the import path
+    run = subprocess.run(cmd, cwd=tmp_path, env=env, capture_output=True, text=True, timeout=600)
+    assert "Error while" not in run.stdout and "ModuleNotFoundError" not in run.stdout, run.stdout[-2000:]
+    assert run.returncode == 1, f"the pins passed with this mistake planted: {what}\n{run.stdout[-2000:]}\n{run.stderr[-1000:]}"
+    assert " failed" in run.stdout, run.stdout[-2000:]
+
+
 @pytest.mark.parametrize("case", range(len(MUTANTS)), ids=[m[3] for m in MUTANTS])
 def test_pins_notice_a_planted_mistake(case, tmp_path):
     (source, variable, pin_files), old, new, what = MUTANTS[case]
