@@ -94,6 +94,36 @@ def bench_partition(args, torch, ppo, workloads):
         "roofline": None}), flush=True)
 
 
+def bench_valu_probe(args, torch, ppo):
+    """Not the headline: the measured issue rate of packed 16-bit vector instructions, 1 to 4 waves per SIMD."""
+    iters = 100000
+    rates = {}
+    for wps in (1, 2, 3, 4):
+        sink = ppo.ppo_probe_valu(wps, 1000)
+        for _ in range(30):   # a few hundred milliseconds of the same work first, so that the clocks have settled
+            ppo.ppo_probe_valu(wps, iters, sink)
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(5):
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record()
+            ppo.ppo_probe_valu(wps, iters, sink)
+            t1.record()
+            torch.cuda.synchronize()
+            ms.append(t0.elapsed_time(t1))
+        ns_per_instr = sorted(ms)[len(ms) // 2] * 1e6 / (16.0 * iters * wps)
+        rates[wps] = {"ns_per_simd_instruction": ns_per_instr, "clocks_at_2.4GHz": ns_per_instr * 2.4,
+                      "Tlane_op_per_s": 256 * 4 * 64 / ns_per_instr / 1e3}
+    best = max(r["Tlane_op_per_s"] for r in rates.values())
+    print(json.dumps({
+        "metric": "measured issue rate of packed 16-bit vector instructions (four independent accumulators per wave)",
+        "value": best, "unit": "Tlane-op/s", "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": None,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": "valu probe: 256 workgroups, 1..4 waves per SIMD", "by_waves_per_simd": rates},
+        "roofline": {"bound": "alu", "achieved": best, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
+                     "frac": best / VALU_PEAK_TOPS, "traffic": None}}), flush=True)
+
+
 def bench_cluster(args, torch, ppo, workloads):
     """Not the headline: whole exact solves per second of the cluster form (ppo_solve_cluster)."""
     N = args.cluster
@@ -156,6 +186,9 @@ def main():
     ap.add_argument("--partition", action="store_true",
                     help="time ppo_min_sum_partition (the paper's own partitioning step) on 4096 chains of L=96: "
                          "a separate figure in instances per second")
+    ap.add_argument("--valu-probe", action="store_true",
+                    help="measure the issue rate of packed 16-bit vector instructions (ppo_probe_valu): the measured "
+                         "peak to set beside the nominal one")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes 256 MiB: the known "
                          "traffic the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -175,6 +208,8 @@ def main():
         return bench_cluster(args, torch, ppo, workloads)
     if args.partition:
         return bench_partition(args, torch, ppo, workloads)
+    if args.valu_probe:
+        return bench_valu_probe(args, torch, ppo)
     w = workloads.WORKLOADS[args.workload]()
     L, k, n = w.L, w.k, w.n_inst
     kf = math.factorial(k)

@@ -60,6 +60,7 @@ def load() -> C.CDLL:
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_cluster_workspace_bytes.restype = sz
         lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
+        lib.ppo_probe_valu.argtypes = [i, i, vp, vp]
         _lib = lib
     return _lib
 
@@ -274,3 +275,12 @@ def ppo_solve_cluster(t, m, M, B, max_segments=None, workspace=None, out=None, s
 
 def orderings_per_instance(k: int) -> int:
     return math.factorial(k)
+
+
+def ppo_probe_valu(waves_per_simd, iters, sink=None, stream=None):
+    """Enqueue the vector-ALU issue probe (a measurement aid); returns the sink tensor."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.empty(256 * 256 * waves_per_simd, dtype=torch.int32, device="cuda:0")
+    _check(load().ppo_probe_valu(waves_per_simd, iters, sink.data_ptr(), _stream(stream)))
+    return sink

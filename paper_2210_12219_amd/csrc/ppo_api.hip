@@ -21,6 +21,7 @@ hipError_t launch_cluster_solve(int, int, int, int, bool, const void*, void*, ui
 hipError_t launch_cluster_tables_from_prepared(const Layout&, const void*, int, void*, hipStream_t);
 hipError_t launch_min_sum_partition(const float*, const float*, int, const float*, int, int32_t*, int32_t*, double*,
                                     hipStream_t);
+hipError_t launch_valu_probe(int, int, uint32_t*, hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -330,6 +331,12 @@ int ppo_eval_orderings(const float* t, const float* m, int L, const float* M, co
     hipError_t e2 = hipFreeAsync(ws, s);
     if (rc == PPO_OK && e2 != hipSuccess) rc = hip_fail(e2, "hipFreeAsync");
     return rc;
+}
+
+int ppo_probe_valu(int waves_per_simd, int iters, uint32_t* sink, void* stream) {
+    if (waves_per_simd < 1 || waves_per_simd > 4 || iters < 1 || sink == nullptr) return PPO_EINVAL;
+    PPO_HIP(ppo::launch_valu_probe(waves_per_simd, iters, sink, static_cast<hipStream_t>(stream)), "valu probe launch");
+    return PPO_OK;
 }
 
 }  // extern "C"

@@ -128,6 +128,10 @@ def test_partition_and_front_end_refuse_bad_arguments(lib):
     assert lib.ppo_min_sum_partition(p, p, 10, p, 0, null, null, null, s) == binding.PPO_OK
     assert lib.ppo_min_sum_partition(p, p, 10, null, 1, p, p, p, s) == binding.PPO_EINVAL
     assert lib.ppo_min_sum_partition(p, p, 10, p, 1, p, null, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_probe_valu(0, 10, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_probe_valu(5, 10, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_probe_valu(2, 0, p, s) == binding.PPO_EINVAL
+    assert lib.ppo_probe_valu(2, 10, null, s) == binding.PPO_EINVAL
     assert lib.ppo_min_sum_partition(p, p, 10, p, 1, p, p, C.c_void_p(0x1004), s) == binding.PPO_EINVAL
     assert lib.ppo_chain_from_dag(0, 0, null, null, p, p, 4, p, p, p, p) == binding.PPO_EINVAL
     assert lib.ppo_chain_from_dag(3, 2, null, p, p, p, 4, p, p, p, p) == binding.PPO_EINVAL
