@@ -637,6 +637,9 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 #pragma unroll
                 for (int t = 0; t < kChunkPairs; ++t)
                     if (t < np) lds_store(obase + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
+                // keeps the compiler from sinking "the last store" of both branches into one block behind a
+                // chain of selects (which the full chunk, the common case, would then pay for as well)
+                asm volatile("" ::: "memory");
             }
         };
 #undef PPO_B
