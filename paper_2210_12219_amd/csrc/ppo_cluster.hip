@@ -28,6 +28,8 @@ constexpr uint32_t kClZero = kCodeZero, kClInf = kCodeInf;
 constexpr int kClPreThreads = 1024;
 static_assert((int)kClZero + (PPO_CLUSTER_MAX_N * (PPO_CLUSTER_MAX_N - 1) / 2) * (PPO_MAX_L - 1) + 1 < (int)kClInf,
               "codes stay below +inf");
+static_assert(((unsigned long long)PPO_CLUSTER_MAX_N << (PPO_CLUSTER_MAX_N - 1)) * ((PPO_MAX_L + 1) / 2) < (1ull << 32),
+              "the dwords of one instance's rows are counted in 32 bits");
 
 struct ClusterLayout {
     int L, n, npairs, nq, rs;                       // rs: entries per row of A: 0..L-1 (entry L is never finite
@@ -67,12 +69,12 @@ struct ClusterLayout {
 // Row number of A[R][j], j in R: the rows of the sets before R in numeric order (the sum of their sizes),
 // then the members of R in increasing order.  The sum of the sizes of all sets below R: a member b of R
 // with h members above it stands for the 2^b sets that agree with R above b and lack b; they have
-// h + (a free choice below b) members: h 2^b + b 2^(b-1) in all.
+// h + (a free choice below b) members: h 2^b + b 2^(b-1) in all (b 2^(b-1) written (b << b) >> 1: no case for b = 0).
 __host__ __device__ inline uint32_t cluster_first_row(uint32_t R, int n) {
     uint32_t rows = 0, above = 0;
     for (int b = n - 1; b >= 0; --b) {
         if (!((R >> b) & 1u)) continue;
-        rows += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+        rows += (above << b) + (((uint32_t)b << b) >> 1);
         ++above;
     }
     return rows;
@@ -86,7 +88,7 @@ __host__ __device__ inline uint32_t cluster_first_row_with(uint32_t first_row, u
 #else
     const uint32_t above = (uint32_t)__builtin_popcount(Rp >> (j + 1));
 #endif
-    return first_row + (above << j) + (j ? (uint32_t)j << (j - 1) : 0u) + below;
+    return first_row + (above << j) + (((uint32_t)j << j) >> 1) + below;
 }
 
 size_t cluster_tables_bytes(int L, int n) { return ClusterLayout::make(L, n).stride; }
@@ -239,7 +241,7 @@ __device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int
         do { --b; } while (kClBinomials.c[b][i] > index);
         set |= 1u << b;
         index -= kClBinomials.c[b][i];
-        rows += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+        rows += (above << b) + (((uint32_t)b << b) >> 1);
         ++above;
     }
     first_row = rows;
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
         uint32_t a[CA];      // row A[R'][member m], two entries per lane
         uint32_t moff[CA];   // dword offset of member m's quotient row from the row of (j, 0)
         {
-            const uint32_t* arow = A32 + (size_t)first_row * rd + lane;
+            const uint32_t* arow = A32 + (size_t)(first_row * (uint32_t)rd) + lane;   // 32 bits hold an instance's dwords
             uint32_t bits = mp;
 #pragma unroll
             for (int m = 0; m < C; ++m) {
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             }
             // row of j within R' + j: after the members below it
             const uint32_t out_row = cluster_first_row_with(first_row, mp, j) + (uint32_t)__popc(mp & ((1u << j) - 1u));
-            if (lane < rd) A32[(size_t)out_row * rd + lane] = res[0] | (res[1] << 16);
+            if (lane < rd) A32[(size_t)(out_row * (uint32_t)rd) + lane] = res[0] | (res[1] << 16);
             __builtin_amdgcn_wave_barrier();
         }
         if (C > 0 && u + 1u < u_end) {
@@ -407,7 +409,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             for (uint32_t bits = mp; bits; ++above) {
                 const int b = 31 - __clz(bits);
                 bits ^= 1u << b;
-                first_row += (above << b) + (b ? (uint32_t)b << (b - 1) : 0u);
+                first_row += (above << b) + (((uint32_t)b << b) >> 1);
             }
         }
     }
