@@ -255,3 +255,33 @@ def test_grouped_kernel_row_lengths(ppo):
         w = W.random_instances(7000 + n, 3 if k == 9 else 10, L, k, capacity_factor=1.15 + 0.1 * (n % 4),
                                quantised=bool(n % 3 == 0))
         assert_same(gpu_solve(ppo, w), O.subset_dp(w.t, w.m, w.M, w.B), f"grouped row lengths k={k} L={L}")
+
+
+def test_issue_probe_runs(ppo):
+    """The measurement aid launches and keeps its work: every lane writes the sum of its four accumulators."""
+    import torch
+    for wps in (1, 4):
+        sink = torch.full((256 * 256 * wps,), -1, dtype=torch.int32, device="cuda:0")
+        ppo.ppo_probe_valu(wps, 10, sink)
+        torch.cuda.synchronize()
+        got = sink.cpu().numpy().view(np.uint32).reshape(256, 256 * wps)
+        # by hand: a = min(max(a, x), y) halfword by halfword settles after one round
+        tid = np.arange(256 * wps, dtype=np.uint32)[None, :]
+        blk = np.arange(256, dtype=np.uint32)[:, None]
+        x = (blk * np.uint32(0x00010001) + np.uint32(0x00030005)).astype(np.uint32)
+        yv = (np.uint32(0x7F007F00) ^ tid).astype(np.uint32)
+
+        def halves(v):
+            return (v & np.uint32(0xFFFF)).astype(np.uint32), (v >> np.uint32(16)).astype(np.uint32)
+
+        def clamp(a):
+            out = np.zeros(np.broadcast(a, x, yv).shape, np.uint32)
+            for h, (ah, xh, yh) in enumerate(zip(halves(a), halves(x), halves(yv))):
+                out |= (np.minimum(np.maximum(ah, xh), yh).astype(np.uint32) << np.uint32(16 * h))
+            return out
+
+        want = np.zeros((256, 256 * wps), np.uint32)
+        for mul in (1, 3, 5, 7):
+            want = (want + clamp((tid * np.uint32(mul)).astype(np.uint32))).astype(np.uint32)
+        assert np.array_equal(got, want)
+
