@@ -550,27 +550,29 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
             uint32_t acc[kChunkPairs];
 #pragma unroll
             for (int t = 0; t < kChunkPairs; ++t) {
-                // y's first candidate is the upper half of the dword at the output's own index
-                uint32_t a = chain_init(PPO_B(t, 0), ctrl[t], init_mask);
-                // steps min(n, depth) .. 1 from registers (see ppo_chain_asm.h); chunk c has depth 16 + 4c
+                // y's first candidate is the upper half of the dword at the output's own index: the block starts
+                // the accumulator from it, then runs steps min(n, depth) .. 1 from registers (see
+                // ppo_chain_asm.h); chunk c has depth 16 + 4c
+                uint32_t a;
 #define PPO_B4(t, i) "v"(PPO_B(t, i)), "v"(PPO_B(t, i + 1)), "v"(PPO_B(t, i + 2)), "v"(PPO_B(t, i + 3))
                 if constexpr (c == 0) {
                     asm volatile(PPO_CHAIN_ASM_0
-                                 : "+v"(a)
+                                 : "=&v"(a)
                                  : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
-                                   PPO_B4(t, 12), "v"(PPO_B(t, 16))
+                                   PPO_B4(t, 12), "v"(PPO_B(t, 16)), "s"(ctrl[t]), "v"(init_mask)
                                  : "s98", "s99", "scc");
                 } else if constexpr (c == 1) {
                     asm volatile(PPO_CHAIN_ASM_1
-                                 : "+v"(a)
+                                 : "=&v"(a)
                                  : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
-                                   PPO_B4(t, 12), PPO_B4(t, 16), "v"(PPO_B(t, 20))
+                                   PPO_B4(t, 12), PPO_B4(t, 16), "v"(PPO_B(t, 20)), "s"(ctrl[t]), "v"(init_mask)
                                  : "s98", "s99", "scc");
                 } else {
                     asm volatile(PPO_CHAIN_ASM_2
-                                 : "+v"(a)
+                                 : "=&v"(a)
                                  : "s"(ctrl[t] & WinDesc::kJumpMask), PPO_B4(t, 0), PPO_B4(t, 4), PPO_B4(t, 8),
-                                   PPO_B4(t, 12), PPO_B4(t, 16), PPO_B4(t, 20), "v"(PPO_B(t, 24))
+                                   PPO_B4(t, 12), PPO_B4(t, 16), PPO_B4(t, 20), "v"(PPO_B(t, 24)), "s"(ctrl[t]),
+                                   "v"(init_mask)
                                  : "s98", "s99", "scc");
                 }
 #undef PPO_B4
