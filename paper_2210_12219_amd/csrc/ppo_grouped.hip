@@ -200,11 +200,21 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //      `avail` ends up holding the six remaining nodes in ascending order, four bits each
     auto decode_group = [&](uint32_t pr, uint64_t& prefix_out, uint64_t& avail_out) {
         uint64_t avail_ = 0xBA9876543210ull, prefix_ = 0;
-        uint32_t rem = pr;
+        // The digits of pr in the factorial number system, four bits each.  Position p has k - p values, so the
+        // last position of the prefix has base 7, the one before it 8, ...: taken from the least significant end
+        // the divisors are the constants 7 .. 12 (a multiplication each), not (k-1-p)!/720.
+        uint32_t digits = 0, rem = pr;
+#pragma unroll
+        for (int q = 0; q < PPO_MAX_K - 6; ++q) {
+            if (q < p0) {
+                const uint32_t base = 7u + (uint32_t)q;
+                const uint32_t next = rem / base;
+                digits |= (rem - next * base) << (4 * (p0 - 1 - q));
+                rem = next;
+            }
+        }
         for (int p = 0; p < p0; ++p) {
-            const uint32_t f = factorial_u32(k - 1 - p) / 720u;
-            const uint32_t d = rem / f;
-            rem -= d * f;
+            const uint32_t d = (digits >> (4 * p)) & 15u;
             const uint32_t sh = 4u * d;
             const uint64_t node = (avail_ >> sh) & 0xFull;
             const uint64_t lowbits = avail_ & ((1ull << sh) - 1ull);
