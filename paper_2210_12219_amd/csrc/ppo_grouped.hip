@@ -422,21 +422,21 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         uint32_t* out = ((s_first & 1) ? buf1 : buf0) + slot_dword(ent);
         const uint32_t* qrow = qtab + link_row(s_first, ent) * QROW + link_col(s_first);
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
-        if (MODE == kGrpShared && p0 >= 1) {
-            const uint32_t* fin = lds + gs.srow_off + (s_first & 1) * NP;
-            for (int jj = j0; jj < j1; ++jj) out[jj * 32] = pk_max(fin[jj], qrow[jj]);
-        } else {
-            const uint32_t* d0row = lds + gs.d0_off + row_node(0, c) * y.wt_cols;   // the initial row of the node
-            int jj = j0;
-            for (; jj + 4 <= j1; jj += 4) {
-                const uint32_t e0 = d0row[jj], e1 = d0row[jj + 1], e2 = d0row[jj + 2], e3 = d0row[jj + 3];
-                out[jj * 32] = pk_max(e0, qrow[jj]);
-                out[(jj + 1) * 32] = pk_max(e1, qrow[jj + 1]);
-                out[(jj + 2) * 32] = pk_max(e2, qrow[jj + 2]);
-                out[(jj + 3) * 32] = pk_max(e3, qrow[jj + 3]);
-            }
-            for (; jj < j1; ++jj) out[jj * 32] = pk_max(d0row[jj], qrow[jj]);
+        // the initial row of the node, or the last row of the shared prefix
+        const uint32_t* first_row = (MODE == kGrpShared && p0 >= 1) ? lds + gs.srow_off + (s_first & 1) * NP
+                                                                    : lds + gs.d0_off + row_node(0, c) * y.wt_cols;
+        int jj = j0;
+        // four dwords at a time, all eight reads before the first write (the compiler cannot tell that the
+        // writes leave the tables alone and would otherwise wait for each read in turn)
+        for (; jj + 4 <= j1; jj += 4) {
+            const uint32_t e0 = first_row[jj], e1 = first_row[jj + 1], e2 = first_row[jj + 2], e3 = first_row[jj + 3];
+            const uint32_t q0 = qrow[jj], q1 = qrow[jj + 1], q2 = qrow[jj + 2], q3 = qrow[jj + 3];
+            out[jj * 32] = pk_max(e0, q0);
+            out[(jj + 1) * 32] = pk_max(e1, q1);
+            out[(jj + 2) * 32] = pk_max(e2, q2);
+            out[(jj + 3) * 32] = pk_max(e3, q3);
         }
+        for (; jj < j1; ++jj) out[jj * 32] = pk_max(first_row[jj], qrow[jj]);
     }
 
     // ---- rows 1 .. k-2.  The output dwords of a lane set's row are cut into parts of kJobPairs dwords; a job
