@@ -493,13 +493,30 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     };
     // the parts of a job's addresses that do not depend on the buffers' roles: descriptors of (node, row, part),
     // and the quotient row from the schedule entry
+    // What a job's set-up needs and only the group, the row and the job decide, for all rows at once: lane
+    // 2 (s - 1) + j works out the values of job j in row s (about thirty scalar instructions per job and row
+    // otherwise), and the row loop picks them with a lane read.
+    //   job_desc: dword offset of the job's first chunk in the descriptor table
+    //   job_link: the row of the quotient table is a base (bits 0-7) plus the field of the schedule entry
+    //             at a shift (bits 8-15) under a mask (bits 16-23)
+    uint32_t job_desc, job_link;
+    {
+        const int s_ = (lane >> 1) + 1, j_ = lane & 1;
+        const int set_ = j_ ? job_set[1] : job_set[0], first_ = j_ ? job_first[1] : job_first[0];
+        const uint64_t packed = s_ < p0 ? prefix : avail;
+        const int idx = (s_ < p0 ? s_ : set_) & 15;
+        const uint32_t node = (uint32_t)((packed >> (4 * idx)) & 0xFull);
+        job_desc = node * desc_node_stride + (uint32_t)((s_ - 1) * y.wt_cols * WinDesc::kWords) +
+                   (uint32_t)((first_ / kChunkPairs) * (WinDesc::kWords * kChunkPairs));
+        const uint32_t lr_base = s_ + 1 < p0 ? (uint32_t)s_ : s_ + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
+        const uint32_t lr_shift = s_ + 1 == p0 ? 13u : 9u, lr_mask = s_ + 1 < p0 ? 0u : s_ + 1 == p0 ? 7u : 15u;
+        job_link = (lr_base & 0xFFu) | (lr_shift << 8) | (lr_mask << 16);
+    }
     auto job_quotients = [&](int s, int j, Job& J) {
-        J.desc_base = (uint32_t)row_node(s, job_set[j]) * desc_node_stride + (uint32_t)((s - 1) * y.wt_cols * WinDesc::kWords) +
-                      (uint32_t)((job_first[j] / kChunkPairs) * (WinDesc::kWords * kChunkPairs));
-        // row of the quotient table = a base + a field of the schedule entry
-        const uint32_t lr_base = s + 1 < p0 ? (uint32_t)s : s + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
-        const uint32_t lr_shift = s + 1 == p0 ? 13u : 9u, lr_mask = s + 1 < p0 ? 0u : s + 1 == p0 ? 7u : 15u;
-        const uint32_t lr = lr_base + ((J.ent >> lr_shift) & lr_mask);
+        const int r = 2 * (s - 1) + j;
+        J.desc_base = (uint32_t)__builtin_amdgcn_readlane((int)job_desc, r);
+        const uint32_t link = (uint32_t)__builtin_amdgcn_readlane((int)job_link, r);
+        const uint32_t lr = (link & 0xFFu) + ((J.ent >> ((link >> 8) & 0xFFu)) & (link >> 16));
         J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + 4u * (uint32_t)(link_col(s) + job_first[j]));
     };
 
