@@ -472,11 +472,6 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         job_set[j] = (wave + 3 * j) % 6;
         job_first[j] = (job_valid[j] ? job_part[j] : 0) * kJobPairs;
     }
-    // first lane set of row s in the schedule table
-    auto first_set = [&](int s) { return s < p0 ? 36 : (s - p0) * 6; };
-    auto load_ent = [&](int s, int j) -> uint32_t {
-        return (uint32_t)lds_load_u16(ent_lane + (uint32_t)(first_set(s) + job_set[j]) * 128u);
-    };
     // Descriptors and quotients of chunk c of job j in row s.  The descriptors are the same for every lane,
     // but they are fetched with vector loads on purpose: scalar loads complete under the same counter as LDS
     // reads, out of order, so one in flight would make every wait for an LDS result a wait for everything.
@@ -499,7 +494,9 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     //   job_desc: dword offset of the job's first chunk in the descriptor table
     //   job_link: the row of the quotient table is a base (bits 0-7) plus the field of the schedule entry
     //             at a shift (bits 8-15) under a mask (bits 16-23)
-    uint32_t job_desc, job_link;
+    //   job_misc: byte offset of the job's row in the schedule table (bits 0-15); byte offset of the quotient
+    //             dword of the job's first output within a row of the quotient table (bits 16-31)
+    uint32_t job_desc, job_link, job_misc;
     {
         const int s_ = (lane >> 1) + 1, j_ = lane & 1;
         const int set_ = j_ ? job_set[1] : job_set[0], first_ = j_ ? job_first[1] : job_first[0];
@@ -511,13 +508,22 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t lr_base = s_ + 1 < p0 ? (uint32_t)s_ : s_ + 1 == p0 ? (uint32_t)nA : (uint32_t)(nA + nB);
         const uint32_t lr_shift = s_ + 1 == p0 ? 13u : 9u, lr_mask = s_ + 1 < p0 ? 0u : s_ + 1 == p0 ? 7u : 15u;
         job_link = (lr_base & 0xFFu) | (lr_shift << 8) | (lr_mask << 16);
+        // the schedule table holds the six lane sets of every row from p0 on, then (from 36) those of the prefix rows
+        const uint32_t ent_row = (uint32_t)((s_ < p0 ? 36 : (s_ - p0) * 6) + set_) * 128u;
+        const uint32_t qcol = 4u * (uint32_t)(((s_ & 1) ? (s_ - 1) / 2 : QD + s_ / 2) + first_);
+        job_misc = (ent_row & 0xFFFFu) | (qcol << 16);
     }
+    auto load_job_ent = [&](int s, int j) -> uint32_t {
+        const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)job_misc, 2 * (s - 1) + j);
+        return (uint32_t)lds_load_u16(ent_lane + (misc & 0xFFFFu));
+    };
     auto job_quotients = [&](int s, int j, Job& J) {
         const int r = 2 * (s - 1) + j;
         J.desc_base = (uint32_t)__builtin_amdgcn_readlane((int)job_desc, r);
         const uint32_t link = (uint32_t)__builtin_amdgcn_readlane((int)job_link, r);
         const uint32_t lr = (link & 0xFFu) + ((J.ent >> ((link >> 8) & 0xFFu)) & (link >> 16));
-        J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + 4u * (uint32_t)(link_col(s) + job_first[j]));
+        const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)job_misc, r);
+        J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + (misc >> 16));
     };
 
     // addresses of job j in row s (the buffers swap roles from row to row)
@@ -532,8 +538,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     // ahead of the barrier that ends that row
     Job J0, J1;
     ChunkIn DA, DB;
-    J0.ent = load_ent(s_first + 1, 0);
-    J1.ent = load_ent(s_first + 1, 1);
+    J0.ent = load_job_ent(s_first + 1, 0);
+    J1.ent = load_job_ent(s_first + 1, 1);
     job_quotients(s_first + 1, 0, J0);
     job_addresses(s_first + 1, 0, J0);
     request_chunk(0, J0, DA);
@@ -702,8 +708,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         request_chunk(2, J1, DB);
         fetch(J1, B1, F2{}, F3{});
         if (s + 1 <= k - 2) {
-            J0.ent = load_ent(s + 1, 0);
-            J1.ent = load_ent(s + 1, 1);
+            J0.ent = load_job_ent(s + 1, 0);
+            J1.ent = load_job_ent(s + 1, 1);
         }
         if (chunk_live(1, 1)) run_chunk(1, C1{}, J1, B1, DA);
         if (chunk_live(1, 2)) run_chunk(1, C2{}, J1, B1, DB);
