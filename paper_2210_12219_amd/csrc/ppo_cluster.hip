@@ -79,18 +79,6 @@ __host__ __device__ inline uint32_t cluster_first_row(uint32_t R, int n) {
     }
     return rows;
 }
-// first row of R' + j from the first row of R' (j not in R'): the sets counted gain j's own term, and every
-// member of R' below j has one more member above it
-__host__ __device__ inline uint32_t cluster_first_row_with(uint32_t first_row, uint32_t Rp, int j) {
-    const uint32_t below = Rp & ((1u << j) - 1u);
-#if defined(__HIP_DEVICE_COMPILE__)
-    const uint32_t above = (uint32_t)__popc(Rp >> (j + 1));
-#else
-    const uint32_t above = (uint32_t)__builtin_popcount(Rp >> (j + 1));
-#endif
-    return first_row + (above << j) + (((uint32_t)j << j) >> 1) + below;
-}
-
 size_t cluster_tables_bytes(int L, int n) { return ClusterLayout::make(L, n).stride; }
 size_t cluster_rows_bytes(int L, int n) { return ClusterLayout::make(L, n).rows_bytes(); }
 
@@ -345,6 +333,18 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
+        // Where the rows of this set go: lane j works out the dword offset of row A[R' + j][j], once per set, and
+        // the loop below picks it with a lane read instead of a dozen scalar instructions per row.  The first row
+        // of R' + j from the first row of R' (j not in R'): the sets counted gain j's own term, and every member of
+        // R' below j has one more member above it (their terms grow by 2^b each: `below` in all); then j's place
+        // among the members.
+        uint32_t out_off;
+        {
+            const uint32_t jl = (uint32_t)lane & 31u;
+            const uint32_t below = mp & ((1u << jl) - 1u);
+            const uint32_t above = (uint32_t)__popc((mp >> jl) >> 1);
+            out_off = (first_row + (above << jl) + ((jl << jl) >> 1) + below + (uint32_t)__popc(below)) * (uint32_t)rd;
+        }
         for (uint32_t jb = all & ~mp; jb; jb &= jb - 1u) {
             const int j = __ffs(jb) - 1;
             uint32_t v = inf2;
@@ -397,8 +397,8 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
                 res[h] = r1 < r2 ? r1 : r2;
             }
             // row of j within R' + j: after the members below it
-            const uint32_t out_row = cluster_first_row_with(first_row, mp, j) + (uint32_t)__popc(mp & ((1u << j) - 1u));
-            if (lane < rd) A32[(size_t)(out_row * (uint32_t)rd) + lane] = res[0] | (res[1] << 16);
+            const uint32_t row_off = (uint32_t)__builtin_amdgcn_readlane((int)out_off, j);
+            if (lane < rd) A32[(size_t)row_off + lane] = res[0] | (res[1] << 16);
             __builtin_amdgcn_wave_barrier();
         }
         if (C > 0 && u + 1u < u_end) {
