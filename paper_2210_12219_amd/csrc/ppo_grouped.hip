@@ -655,12 +655,22 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                         const uint32_t cnt = WinDesc::fold_dwords(ctrl[t]);
                         const uint32_t last_mask = (ctrl[t] & WinDesc::kWxEven) ? kCodeInf : 0u;
                         const uint32_t first = cbase + below[t];   // dword n+1
-                        const uint32_t last = pk_max(lds_load(first - cnt * 128u), last_mask);
+                        const uint32_t last = lds_load(first - cnt * 128u);
                         uint32_t tacc = cnt == 0u ? kInf2 : bn1[t];
                         for (uint32_t i = 1; i < cnt; ++i) tacc = pk_min(tacc, lds_load(first - i * 128u));
-                        tacc = pk_min(tacc, last);
-                        tacc = pk_min(tacc, align16(tacc, tacc));
-                        acc[t] = pk_min(acc[t], pk_max(tacc, kCodeInf << 16));
+                        // last dword under its mask, both halves folded into one, into x's half of the result.  One
+                        // block: between packed instructions written one by one the compiler puts a wait state
+                        // each (it takes their high-half operand selectors for a partial write of the result),
+                        // which these full-width results do not need.
+                        uint32_t t1, t2;
+                        asm("v_pk_max_u16 %1, %3, %4\n"
+                            "v_pk_min_u16 %1, %5, %1\n"
+                            "v_alignbit_b32 %2, %1, %1, 16\n"
+                            "v_pk_min_u16 %1, %1, %2\n"
+                            "v_pk_max_u16 %1, %1, %6\n"
+                            "v_pk_min_u16 %0, %0, %1"
+                            : "+v"(acc[t]), "=&v"(t1), "=&v"(t2)
+                            : "v"(last), "s"(last_mask), "v"(tacc), "s"((uint32_t)(kCodeInf << 16)));
                     }
                 }
             }
