@@ -66,7 +66,7 @@ __device__ __forceinline__ uint32_t lds_load(uint32_t byte_addr) { return *(cons
 __device__ __forceinline__ uint32_t align16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
 struct GroupedShape {
-    int NE, NP, QD, QROW, nA, nB, nQ;
+    int NE, NP, QD, QROW, QPITCH, nA, nB, nQ;
     uint32_t buf_off, buf_dwords, q_off, slot_off, d0_off, srow_off, total_bytes;  // offsets in dwords
     __host__ __device__ static GroupedShape make(int L, int k) {
         GroupedShape g;
@@ -74,6 +74,8 @@ struct GroupedShape {
         g.NP = (g.NE + 1) >> 1;
         g.QD = L / 2 + 1;
         g.QROW = 2 * g.QD + 2;
+        g.QPITCH = g.QROW | 1;   // rows of the table in LDS an odd number of dwords apart: lanes that gather the same
+                                 // column of different rows (their own links) then hit different banks
         const int p0 = k - 6;
         g.nA = p0 > 1 ? p0 - 1 : 0;   // links inside the prefix
         g.nB = p0 > 0 ? 6 : 0;        // links from the last prefix node to each remaining node
@@ -81,7 +83,7 @@ struct GroupedShape {
         g.buf_off = (uint32_t)(kDeep + 1) * 32u;   // room for the fixed-depth fetches and the masked step below dword 0
         g.buf_dwords = 12u * g.NP * 32u;
         g.q_off = g.buf_off + 2u * g.buf_dwords;
-        g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QROW);
+        g.slot_off = g.q_off + (uint32_t)(g.nQ * g.QPITCH);
         g.d0_off = g.slot_off + 42u * 64u / 2u;   // schedule entries are 16 bits
         g.srow_off = g.d0_off + (uint32_t)(k * align_up((size_t)g.NP, 4));
         g.total_bytes = (g.srow_off + 3u * (uint32_t)g.NP + 3u) * 4u;   // two shared rows, their linked form (one dword below it), two flags
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = k - 6;
     const GroupedShape gs = GroupedShape::make(L, k);
-    const int NP = gs.NP, QD = gs.QD, QROW = gs.QROW, nA = gs.nA, nB = gs.nB;
+    const int NP = gs.NP, QD = gs.QD, QROW = gs.QROW, QPITCH = gs.QPITCH, nA = gs.nA, nB = gs.nB;
     // A workgroup handles groups_per_block groups of one parity, one after the other (group_begin is even,
     // so the parity of a group is the parity of its index); the schedule table is staged once.
     const uint32_t par = blockIdx.x & 1u;
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
 #pragma unroll
                 for (int c = 0; c < kQCols; ++c) {
                     const int col = lane + 64 * c;
-                    if (col < QROW) qtab[row * QROW + col] = qreg[r * kQCols + c];
+                    if (col < QROW) qtab[row * QPITCH + col] = qreg[r * kQCols + c];
                 }
             }
         }
@@ -420,7 +422,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const int set = p0 > 0 ? 36 + c : c;
         const uint32_t ent = slotTab[set * 64 + lane];
         uint32_t* out = ((s_first & 1) ? buf1 : buf0) + slot_dword(ent);
-        const uint32_t* qrow = qtab + link_row(s_first, ent) * QROW + link_col(s_first);
+        const uint32_t* qrow = qtab + link_row(s_first, ent) * QPITCH + link_col(s_first);
         const int j0 = half * ((NP + 1) / 2), j1 = half ? NP : (NP + 1) / 2;
         // the initial row of the node, or the last row of the shared prefix
         const uint32_t* first_row = (MODE == kGrpShared && p0 >= 1) ? lds + gs.srow_off + (s_first & 1) * NP
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
         const uint32_t link = (uint32_t)__builtin_amdgcn_readlane((int)job_link, r);
         const uint32_t lr = (link & 0xFFu) + ((J.ent >> ((link >> 8) & 0xFFu)) & (link >> 16));
         const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)job_misc, r);
-        J.qa_addr = __umul24(lr, (uint32_t)(QROW * 4)) + (qtab_addr + (misc >> 16));
+        J.qa_addr = __umul24(lr, (uint32_t)(QPITCH * 4)) + (qtab_addr + (misc >> 16));
     };
 
     // addresses of job j in row s (the buffers swap roles from row to row)
