@@ -250,10 +250,12 @@ struct ClusterLds {
         s.total = s.run_off + (uint32_t)waves * kClRunLevels * kClRunRow * 2;
         return s;
     }
-    // 8 waves per workgroup while two workgroups fit a compute unit's 160 KB, else 16
+    // as many waves on a compute unit as its 160 KB of LDS allow (a row is a chain of dependent steps, so what
+    // counts is the number of rows in flight): two workgroups of 16 if they fit, else two of 8, else one of 16
     __host__ static ClusterLds choose(const ClusterLayout& y) {
-        const ClusterLds s = make(y, 8);
-        return 2u * s.total <= 160u * 1024u ? s : make(y, 16);
+        const ClusterLds big = make(y, 16), small = make(y, 8);
+        if (2u * big.total <= 160u * 1024u) return big;
+        return 2u * small.total <= 160u * 1024u ? small : big;
     }
 };
 
