@@ -195,7 +195,9 @@ __global__ __launch_bounds__(kClCountThreads) void cluster_count_kernel(ClusterL
 // the minimum over the window (e, hi[j][e]] is two reads.  grid.x waves share the sets, grid.y = instance.
 // ---------------------------------------------------------------------------------------------
 constexpr int kClRunLevels = 7;    // runs of 2^0 .. 2^6 entries
-constexpr int kClRunRow = 192;     // entries per run-minimum row: 128 computed per set, the rest constant
+constexpr int kClRunRow = 160;     // entries per run-minimum row: 128 computed per set, the rest constant
+static_assert(kClRunRow / 2 >= 64 + (1 << (kClRunLevels - 3)) && kClRunRow % 2 == 0,
+              "the longest runs (2^(levels-1) entries) are built from dwords up to 2^(levels-3) beyond a lane's own");
 constexpr int kClQueryRow = 128;   // window queries per node in LDS: one dword per entry e
 
 typedef unsigned short cl_ushort2 __attribute__((ext_vector_type(2)));
