@@ -54,13 +54,16 @@ struct ClusterLayout {
         off = align_up(off + (size_t)y.nq * 4, 16);
         y.ord_off = (uint32_t)off;   // the layers 0 .. L-2 in increasing order of t (one byte each)
         off = align_up(off + (size_t)L, 256);
-        // what the level kernel keeps in LDS, ready to be copied: quotient rows of every ordered pair (64 dwords
-        // each), then the window queries of every (node, entry) (128 dwords per node)
+        // what the level kernel keeps in LDS, ready to be copied: quotient rows of every ordered pair (rs / 2
+        // dwords each, the pitch of the rows of A), then the window queries of every (node, entry) (128 dwords
+        // per node)
         y.img_off = (uint32_t)off;
-        off = align_up(off + (size_t)n * n * 256 + (size_t)n * 512, 256);
+        off = align_up(off + q_image_bytes(n, y.rs) + (size_t)n * 512, 256);
         y.stride = (uint32_t)off;
         return y;
     }
+    // bytes of the quotient rows in the LDS image (the window queries follow, 16-byte aligned)
+    __host__ __device__ static size_t q_image_bytes(int n, int rs) { return align_up((size_t)n * n * (rs / 2) * 4, 16); }
     // rows A[R][j] exist for j in R only: n 2^(n-1) of them per instance
     __host__ __device__ size_t rows_per_instance() const { return (size_t)n << (n - 1); }
     __host__ __device__ size_t rows_bytes() const { return rows_per_instance() * (size_t)rs * sizeof(uint16_t); }
@@ -238,16 +241,17 @@ __device__ __forceinline__ uint32_t cluster_set_at(uint32_t index, int size, int
     return set;
 }
 
-// LDS of the level kernel: the quotient rows of every ORDERED pair of nodes, 64 dwords each (so that the row
-// of (j, j'') is a fixed distance j'' * 256 bytes from the row of (j, 0)), the window queries of every
-// (node, entry), and the run-minimum tables of each wave.
+// LDS of the level kernel: the quotient rows of every ORDERED pair of nodes, rs / 2 dwords each (so that the row
+// of (j, j'') is a fixed distance from the row of (j, 0); lanes beyond a row read on into the next one, or into
+// the queries after the last, and drop what they read), the window queries of every (node, entry), and the
+// run-minimum tables of each wave.
 struct ClusterLds {
     uint32_t hi_off, run_off, total;
     int waves;
     __host__ __device__ static ClusterLds make(const ClusterLayout& y, int waves) {
         ClusterLds s;
         s.waves = waves;
-        s.hi_off = (uint32_t)y.n * (uint32_t)y.n * 256u;
+        s.hi_off = (uint32_t)ClusterLayout::q_image_bytes(y.n, y.rs);
         s.run_off = (uint32_t)align_up((size_t)s.hi_off + (size_t)y.n * kClQueryRow * 4, 16);
         s.total = s.run_off + (uint32_t)waves * kClRunLevels * kClRunRow * 2;
         return s;
@@ -289,7 +293,8 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
     {
         const uint4* img = reinterpret_cast<const uint4*>(base + y.img_off);
         uint4* dst = reinterpret_cast<uint4*>(cl_smem);
-        const int first = more ? 0 : n * n * 16, count = n * n * 16 + n * 32;   // the quotient rows only if used
+        const int qrows16 = (int)(lds.hi_off / 16u);
+        const int first = more ? 0 : qrows16, count = qrows16 + n * 32;   // the quotient rows only if used
         for (int i = first + tid; i < count; i += threads) dst[i] = img[i];
     }
     // entries 128.. of the run-minimum rows never change: rest[L] = 0 if L = 128, +inf beyond the chain
@@ -323,7 +328,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             uint32_t bits = mp;
 #pragma unroll
             for (int m = 0; m < C; ++m) {
-                moff[m] = (uint32_t)(__ffs(bits) - 1) * 64u;
+                moff[m] = (uint32_t)(__ffs(bits) - 1) * (uint32_t)rd;
                 bits &= bits - 1u;
                 a[m] = (more && lane < rd) ? arow[m * rd] : inf2;
             }
@@ -353,7 +358,7 @@ __global__ __launch_bounds__(1024) void cluster_level_kernel(ClusterLayout y,
             const int j = __ffs(jb) - 1;
             uint32_t v = inf2;
             if (more) {
-                const uint32_t* qj = q32 + (j * n) * 64 + lane;
+                const uint32_t* qj = q32 + (j * n) * rd + lane;
                 uint32_t x[CA];
 #pragma unroll
                 for (int m = 0; m < C; ++m) x[m] = cl_pk_max(qj[moff[m]], a[m]);
@@ -613,10 +618,10 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_image_kernel(ClusterLay
     unsigned char* base = ws + (size_t)inst * y.stride;
     const uint16_t* __restrict__ qc = reinterpret_cast<const uint16_t*>(base + y.qc_off);
     uint16_t* q16 = reinterpret_cast<uint16_t*>(base + y.img_off);
-    uint32_t* query = reinterpret_cast<uint32_t*>(base + y.img_off) + n * n * 64;
-    for (int i = tid; i < n * n * 128; i += kClPreThreads) {
-        const int e = i & 127, jj = i >> 7, j = jj / n, j2 = jj - j * n;
-        q16[i] = (uint16_t)((j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
+    uint32_t* query = reinterpret_cast<uint32_t*>(base + y.img_off + ClusterLayout::q_image_bytes(n, y.rs));
+    for (int i = tid; i < (int)(ClusterLayout::q_image_bytes(n, y.rs) / 2); i += kClPreThreads) {
+        const int e = i % y.rs, jj = i / y.rs, j = jj / n, j2 = jj - j * n;   // jj = n * n: the padding
+        q16[i] = (uint16_t)((jj < n * n && j != j2 && e >= 1 && e <= L - 1) ? qc[pair_index(j, j2, n) * L + e - 1] : kClInf);
     }
     for (int i = tid; i < n * kClQueryRow; i += kClPreThreads) {
         const int j = i / kClQueryRow, e = i - j * kClQueryRow;
