@@ -43,6 +43,14 @@ MUTANTS = [
      "return (float)(I->P[e] - I->P[i]) <= I->M[node]; }", "segment size rounded to binary32 before the comparison"),
     (CLUSTER, "I->P[i + 1] = I->P[i] + (double)m[i];", "I->P[i + 1] = (double)(float)(I->P[i] + (double)m[i]);",
      "prefix sums accumulated in binary32"),
+    (CLUSTER, "if (bf_best_cuts(I, W->seq, p, &b, cut) && (!W->found || b < W->bbeta)) {",
+     "if (bf_best_cuts(I, W->seq, p, &b, cut) && (!W->found || b <= W->bbeta)) {",
+     "definition route: the last optimal sequence instead of the first"),
+    (CLUSTER, "if (!isinf(b) && (!W->found || b < W->bbeta)) {", "if (!isinf(b) && (!W->found || b <= W->bbeta)) {",
+     "exhaustive route: the last optimal sequence instead of the first"),
+    (CLUSTER, "if (p == I->pmax) return;\n    for (int j = 0; j < I->n; ++j) {\n        if (W->used[j]) continue;\n        W->used[j] = 1; W->seq[p] = j;\n        bf_walk(W, p + 1);",
+     "if (p > I->pmax) return;\n    for (int j = 0; j < I->n; ++j) {\n        if (W->used[j]) continue;\n        W->used[j] = 1; W->seq[p] = j;\n        bf_walk(W, p + 1);",
+     "definition route: one segment more than allowed"),
     (CLUSTER, "volatile float q = I->t[cut - 1] / I->B[a * I->n + b];", "volatile float q = I->t[cut] / I->B[a * I->n + b];",
      "tensor of the layer after the cut instead of the one before"),
     (CLUSTER, "volatile float q = I->t[cut - 1] / I->B[a * I->n + b];", "volatile float q = I->t[cut - 1] / I->B[b * I->n + b];",
