@@ -477,7 +477,8 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
     // Descriptors and quotients of chunk c of job j in row s.  The descriptors are the same for every lane,
     // but they are fetched with vector loads on purpose: scalar loads complete under the same counter as LDS
     // reads, out of order, so one in flight would make every wait for an LDS result a wait for everything.
-    auto chunk_live = [&](int j, int c) { return job_valid[j] && job_first[j] + c * kChunkPairs < NP; };
+    // (a wave's second job is never the row's last part: all its chunks have outputs)
+    auto chunk_live = [&](int j, int c) { return job_valid[j] && (j == 1 || job_first[j] + c * kChunkPairs < NP); };
     auto request_chunk = [&](int c, const Job& J, ChunkIn& D) {
         const uint4* dp = reinterpret_cast<const uint4*>(wt + J.desc_base + (uint32_t)(c * (WinDesc::kWords * kChunkPairs))) + vzero;
         // ctrl is used first: requested last, its arrival means that all four words are there
@@ -677,7 +678,9 @@ __global__ __launch_bounds__(kGrpThreads) void enumerate_grouped_kernel(
                 }
             }
             const uint32_t obase = J.out_addr + (uint32_t)(c * kChunkPairs * 128);
-            if (np >= kChunkPairs) {
+            // only a row's last part can be short, and that part is always a wave's first job: the second job's
+            // chunks are whole (j is a constant at every place this is expanded)
+            if (j == 1 || np >= kChunkPairs) {
 #pragma unroll
                 for (int t = 0; t < kChunkPairs; ++t) lds_store(obase + (uint32_t)t * 128u, pk_max(acc[t], X.qv[t]));
             } else {
