@@ -56,8 +56,8 @@ def algorithmic_ops_per_ordering(w):
 # (FETCH_SIZE, then WRITE_SIZE) of `bench.py --steps 1 --warmup 0 --no-cpu-baseline --copy-probe`, each counter
 # scaled by what it reads for the probe's 256 MiB (see profiles/).  Keyed by ppo_version(): a library whose
 # kernel has changed since reports no traffic.
-MEASURED_TRAFFIC_BYTES = {("headline", 116): 4.852e7,
-                          ("cluster_mixed_n20", 116): 4.573e9}   # the 20 level launches of one n = 20 solve   # re-measure when the kernel changes
+MEASURED_TRAFFIC_BYTES = {("headline", 117): 4.752e7,
+                          ("cluster_mixed_n20", 117): 4.573e9}   # the 20 level launches of one n = 20 solve   # re-measure when the kernel changes
 
 
 def copy_probe(torch):

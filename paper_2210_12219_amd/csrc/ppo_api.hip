@@ -99,7 +99,7 @@ static bool bad_keys(const void* keys) { return !keys || misaligned(keys, 8); }
 
 extern "C" {
 
-int ppo_version(void) { return 116; }
+int ppo_version(void) { return 117; }
 
 int ppo_set_enumeration(int variant) {
     if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC) return PPO_EINVAL;

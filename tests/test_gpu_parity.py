@@ -104,6 +104,25 @@ def test_headline_workload_full(ppo):
     sampled_orderings_match(ppo, w, [0, 17, 63], 3, 3000, seed=1)
 
 
+def test_headline_in_two_ragged_pieces(ppo):
+    """The headline search cut at a rank inside a group of orderings: the large piece starts ragged and is
+    long enough for the launch shape with more groups per workgroup; the pieces' common key is the whole
+    search's, checked against the independent subset DP."""
+    import torch
+    w = W.headline()
+    dev = ppo.to_device(w)
+    ws = ppo.alloc_workspace(w.L, w.k, w.n_inst)
+    keys = torch.empty(w.n_inst, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_prepare(*dev, ws)
+    ppo.ppo_init_keys(keys)
+    cut = 16 * 720 + 257
+    for a, b in ((cut, math.factorial(w.k)), (0, cut)):
+        ppo.ppo_solve_range(w.L, w.k, w.n_inst, ws, a, b, keys)
+    out = ppo.ppo_finalize(w.L, w.k, w.n_inst, ws, keys)
+    torch.cuda.synchronize()
+    assert_same(tuple(x.cpu().numpy() for x in out), O.subset_dp(w.t, w.m, w.M, w.B), "headline in two pieces")
+
+
 def test_large_workload_full(ppo):
     w = W.large()
     got = gpu_solve(ppo, w)
