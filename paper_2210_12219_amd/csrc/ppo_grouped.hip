@@ -806,11 +806,12 @@ hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws,
     const uint32_t gbeg = 2u * (rank_begin / 720u), gend = 2u * ((rank_end + 719u) / 720u);
     // groups per workgroup: enough workgroups to fill the chip several times over, else as many as 8; 16 where
     // that leaves no ragged last workgroup and still many workgroups per compute unit (a workgroup's start-up
-    // is then paid half as often).  The bounded mode stays at 8: its bound tightens between workgroups.
+    // is then paid half as often).  The bounded mode stays at 8: its bound tightens between workgroups; so
+    // does the mode that exports beta per ordering, which never runs at such sizes.
     const uint32_t pairs = (gend - gbeg) / 2;
     uint32_t gpb = 8;
     while (gpb > 1 && (uint64_t)(pairs / gpb) * 2u * (uint64_t)n_inst < 4096u) gpb >>= 1;
-    if (!shared_prefix && pairs % 16u == 0 && (uint64_t)(pairs / 16u) * 2u * (uint64_t)n_inst >= 16384u) gpb = 16;
+    if (!shared_prefix && !beta_export && pairs % 16u == 0 && (uint64_t)(pairs / 16u) * 2u * (uint64_t)n_inst >= 16384u) gpb = 16;
     const dim3 grid(2u * ((pairs + gpb - 1) / gpb), n_inst);
     if (beta_export)
         return launch_mode<kGrpExport>(grid, gs, stream, y, ws, rank_begin, rank_end, gbeg, gend, gpb, best_key, beta_export, nullptr);
