@@ -57,6 +57,7 @@ static int cl_fits(const cl_t *I, int i, int e, int node) { return (I->P[e] - I-
 
 static float cl_gamma(const cl_t *I, int cut, int a, int b) {
     volatile float q = I->t[cut - 1] / I->B[a * I->n + b];
+    if (q == 0.0f) return 0.0f; /* nothing to send takes no time: +0, also when t carries a sign bit */
     return q;
 }
 
@@ -65,7 +66,7 @@ static int cl_check(const float *t, const float *m, int L, const float *M, const
     if (n > ORC_MAX_N || L > ORC_MAX_L) return ORC_ETOOBIG;
     if (!t || !m || !M || !B) return ORC_EINVAL;
     for (int i = 0; i < L; ++i)
-        if (!isfinite(t[i]) || !isfinite(m[i]) || t[i] < 0.0f || signbit(t[i]) || m[i] < 0.0f) return ORC_EDATA;
+        if (!isfinite(t[i]) || !isfinite(m[i]) || t[i] < 0.0f || m[i] < 0.0f) return ORC_EDATA;
     for (int j = 0; j < n; ++j)
         if (!isfinite(M[j]) || M[j] < 0.0f) return ORC_EDATA;
     for (int a = 0; a < n; ++a)

@@ -64,8 +64,8 @@ static int check_scalars(int L, int k) {
     return ORC_OK;
 }
 
-/* Data preconditions: finite, t >= +0 (negative zero would give gamma = -0, whose bit pattern does not
- * order like its value), m,M >= 0, off-diagonal B > 0 and bit-symmetric. */
+/* Data preconditions: finite, t >= 0 (a zero of either sign is a size of zero), m,M >= 0, off-diagonal
+ * B > 0 and bit-symmetric. */
 int ppo_oracle_check_inputs(const float *t, const float *m, int L, const float *M, const float *B, int k,
                             int n_inst) {
     int rc = check_scalars(L, k);
@@ -74,7 +74,7 @@ int ppo_oracle_check_inputs(const float *t, const float *m, int L, const float *
     for (int n = 0; n < n_inst; ++n) {
         for (int i = 0; i < L; ++i) {
             float a = t[(size_t)n * L + i], b = m[(size_t)n * L + i];
-            if (!isfinite(a) || !isfinite(b) || a < 0.0f || signbit(a) || b < 0.0f) return ORC_EDATA;
+            if (!isfinite(a) || !isfinite(b) || a < 0.0f || b < 0.0f) return ORC_EDATA;
         }
         for (int j = 0; j < k; ++j) {
             float c = M[(size_t)n * k + j];
@@ -102,6 +102,7 @@ static int fits(const inst_t *I, int i, int e, int node) { return (I->P[e] - I->
 static float gamma_of(const inst_t *I, int cut, int a, int b) {
     /* Eq. 3: the tensor leaving the last layer before the cut, over the link between the two hosts */
     volatile float q = I->t[cut - 1] / I->B[a * I->k + b];
+    if (q == 0.0f) return 0.0f; /* nothing to send takes no time: +0, also when t carries a sign bit */
     return q;
 }
 

@@ -310,10 +310,31 @@ def test_precondition_violations_are_rejected():
     t2 = t.copy(); t2[0, 2] = -1.0
     assert O.check_inputs(t2, m, M, B) == -3
     t3 = t.copy(); t3[0, 1] = -0.0
-    assert O.check_inputs(t3, m, M, B) == -3          # negative zero transfer size
+    assert O.check_inputs(t3, m, M, B) == 0           # a zero of either sign is a size of zero
     m2 = m.copy(); m2[0, 0] = np.nan
     assert O.check_inputs(t, m2, M, B) == -3
     with pytest.raises(O.OracleError):
         O.exhaustive(t2, m, M, B)
     # k > L
     assert O.check_inputs(t[:, :2], m[:, :2], M, B) == -1
+
+
+def test_a_zero_transfer_size_of_either_sign_takes_no_time():
+    """Sec. III-B, Eq. 3 with t = 0: nothing is sent, gamma = +0.  A zero that carries a sign bit is still a
+    zero: every route gives what it gives for +0, and never the bit pattern of -0."""
+    w = W.random_instances(21, 40, 7, 3, capacity_factor=2.0)
+    t = w.t.copy()
+    t[:, ::2] = np.float32(-0.0)
+    plus = np.abs(t)
+    assert np.signbit(t).any() and not np.signbit(plus).any()
+    for route in (O.bruteforce, lambda *a: O.exhaustive(*a)[:3], O.subset_dp):
+        got, ref = route(t, w.m, w.M, w.B), route(plus, w.m, w.M, w.B)
+        assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32))
+        assert np.array_equal(got[1], ref[1]) and np.array_equal(got[2], ref[2])
+        assert not (got[0].view(np.uint32) == 0x80000000).any() and (got[0].view(np.uint32) == 0).any()
+    from oracle import ppo_cluster_oracle as CO
+    for i in range(6):
+        a = CO.bruteforce(t[i], w.m[i], w.M[i], w.B[i])
+        b = CO.bruteforce(plus[i], w.m[i], w.M[i], w.B[i])
+        assert np.float32(a[0]).view(np.uint32) == np.float32(b[0]).view(np.uint32) != 0x80000000
+        assert a[1] == b[1] and np.array_equal(a[2], b[2]) and np.array_equal(a[3], b[3])
