@@ -31,9 +31,10 @@
  *   - Return value: 0 on success, a negative PPO_E* code otherwise; on error nothing was enqueued
  *     by that call (PPO_EHIP excepted: a launch may have failed half-way).  n_inst = 0 succeeds
  *     and does nothing.
- *   - Data preconditions, not checked on the device: every value finite; t >= +0 (no negative
- *     zero), m >= 0, M >= 0; B[a][b] > 0 and bit-identical to B[b][a] for a != b (the element with
- *     the smaller row index is the one read); the diagonal of B and t[.][L-1] are ignored.
+ *   - Data preconditions, not checked on the device: every value finite; t >= 0 (a zero of either sign
+ *     counts as +0: sending nothing takes no time), m >= 0, M >= 0; B[a][b] > 0 and bit-identical to
+ *     B[b][a] for a != b (the element with the smaller row index is the one read); the diagonal of B and
+ *     t[.][L-1] are ignored.
  *   - Limits: 1 <= k <= L, k <= PPO_MAX_K (so that k! fits 32 bits), L <= PPO_MAX_L.
  *   - Concurrent calls are allowed when their outputs and workspaces are distinct.
  */

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kClPreThreads) void cluster_tables_kernel(const flo
     // search per link instead of a comparison with every quotient.
     __shared__ float t_s[PPO_MAX_L];
     __shared__ unsigned char ord_s[PPO_MAX_L];
-    for (int i = tid; i < L - 1; i += kClPreThreads) t_s[i] = ti[i];
+    for (int i = tid; i < L - 1; i += kClPreThreads) t_s[i] = ti[i] == 0.0f ? 0.0f : ti[i];   // -0 is a size of zero: +0
     __syncthreads();
     for (int i = tid; i < L - 1; i += kClPreThreads) {
         const float x = t_s[i];
@@ -647,8 +647,8 @@ hipError_t launch_cluster_tables(const float* t, const float* m, const float* M,
     if (y.nq > 0) {
         const int slices = (y.nq + kClCountThreads - 1) / kClCountThreads;
         const uint32_t lds_bytes = (uint32_t)y.nq * 4u;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_count_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        static std::atomic<uint64_t> lds_allowed{0};
+        e = allow_full_lds(reinterpret_cast<const void*>(&cluster_count_kernel), lds_allowed);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(cluster_count_kernel, dim3(slices, n_inst), dim3(kClCountThreads), lds_bytes, stream, y, w);
         e = hipGetLastError();
@@ -665,8 +665,8 @@ using ClLevelLaunch = hipError_t (*)(dim3, dim3, uint32_t, hipStream_t, const Cl
 template <int C>
 static hipError_t cluster_launch_level(dim3 grid, dim3 block, uint32_t lds_bytes, hipStream_t stream, const ClusterLayout& y,
                                        const unsigned char* ws, uint16_t* rows, int pmax, int exact) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cluster_level_kernel<C>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&cluster_level_kernel<C>), lds_allowed);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cluster_level_kernel<C>, grid, block, lds_bytes, stream, y, ws, rows, pmax, exact);
     return hipGetLastError();

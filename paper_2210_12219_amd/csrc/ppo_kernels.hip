@@ -102,7 +102,9 @@ __global__ __launch_bounds__(kPreThreads) void precompute_kernel(const float* __
     __shared__ float t_s[PPO_MAX_L];
     __shared__ unsigned char ord_s[PPO_MAX_L];
     __syncthreads();
-    for (int i = tid; i < L - 1; i += kPreThreads) t_s[i] = ti[i];
+    // a transfer size of zero is +0 whatever its sign bit says: -0 / B would be -0, whose bit pattern does not
+    // order like its value in the key
+    for (int i = tid; i < L - 1; i += kPreThreads) t_s[i] = ti[i] == 0.0f ? 0.0f : ti[i];
     __syncthreads();
     for (int i = tid; i < L - 1; i += kPreThreads) {
         const float x = t_s[i];
@@ -390,8 +392,8 @@ hipError_t launch_enumerate_grouped(const Layout& y, int n_inst, const void* ws,
                                     uint64_t* skipped_groups, hipStream_t stream);
 
 // 0: pick per shape (grouped kernel when k >= 6 and the rows fit LDS), 1: always the generic kernel
-static int g_enumeration_variant = 0;
-void set_enumeration_variant(int v) { g_enumeration_variant = v; }
+static std::atomic<int> g_enumeration_variant{0};   // read by every launch, set by tests: atomic, so that a set during a launch on another thread is a plain race-free read of either value
+void set_enumeration_variant(int v) { g_enumeration_variant.store(v, std::memory_order_relaxed); }
 
 size_t enumerate_lds_bytes(const Layout& y) { return (size_t)y.dec_off + (size_t)(y.L + 1) * kEnumThreads * 2; }
 
@@ -402,7 +404,7 @@ hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_
                             hipStream_t stream) {
     const uint32_t span = rank_end - rank_begin;
     if (span == 0 || n_inst == 0) return hipSuccess;
-    if (g_enumeration_variant == 0 && grouped_supported(y.L, y.k))
+    if (g_enumeration_variant.load(std::memory_order_relaxed) == 0 && grouped_supported(y.L, y.k))
         return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, shared_prefix,
                                         skipped_groups, stream);
     const size_t lds = enumerate_lds_bytes(y);
@@ -410,15 +412,15 @@ hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_
     if (gx > 4096u) gx = 4096u;
     hipError_t e;
     if (beta_export) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static std::atomic<uint64_t> lds_allowed{0};
+        e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_kernel<true>), lds_allowed);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(enumerate_kernel<true>, dim3(gx, n_inst), dim3(kEnumThreads), lds, stream, y,
                            static_cast<const unsigned char*>(ws), rank_begin, rank_end,
                            reinterpret_cast<unsigned long long*>(best_key), beta_export);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static std::atomic<uint64_t> lds_allowed{0};
+        e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_kernel<false>), lds_allowed);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(enumerate_kernel<false>, dim3(gx, n_inst), dim3(kEnumThreads), lds, stream, y,
                            static_cast<const unsigned char*>(ws), rank_begin, rank_end,

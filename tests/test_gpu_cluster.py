@@ -184,6 +184,64 @@ def test_cluster_of_twenty(ppo):
             check_solution(w, i, six, 6, rng)
 
 
+def embed_with_decoys(w, i, n_big, rng):
+    """Instance i of w inside a cluster of n_big nodes: the real nodes keep their relative order (so the
+    lexicographic tie rule carries over), the others hold less than the lightest layer and can host nothing."""
+    n0 = w.k
+    pos = np.sort(rng.choice(n_big, n0, replace=False))
+    M = np.full(n_big, 0.5 * float(w.m[i].min()), np.float32)
+    assert M[0] > 0 and (M[0] < w.m[i]).all()
+    M[pos] = w.M[i]
+    up = np.triu(np.exp(rng.uniform(np.log(1.0), np.log(100.0), (n_big, n_big))), 1)
+    B = (up + up.T).astype(np.float32)
+    B[np.ix_(pos, pos)] = w.B[i]
+    return pos, M, B
+
+
+def test_cluster_of_twenty_exact_through_decoy_nodes(ppo):
+    """n = 20 with every segment count allowed (a million node sets, 32-bit row numbers, every level of the
+    DP), bit for bit: a cluster of 11 to 13 real nodes that the oracle solves, plus nodes too small for any
+    layer, which change nothing (the oracle's own pins show that).  Expected beta, segment count, cuts are
+    the small cluster's; the node sequence is the small one's through the embedding."""
+    import torch
+    rng = np.random.default_rng(2020)
+    cases = [(W.random_instances(311, 2, 100, 12, capacity_factor=1.7), "L=100, eight segments or so"),
+             (W.cluster_mixed(13, L=100, n_inst=1, seed=21), "L=100 mixed"),
+             (W.random_instances(312, 2, 128, 11, capacity_factor=2.5), "L=128"),
+             (W.cluster_geometric(12, 16, n_inst=2, seed=23), "paper-shaped, ties")]
+    for w, what in cases:
+        n0 = w.k
+        t = np.ascontiguousarray(w.t)
+        m = np.ascontiguousarray(w.m)
+        Ms, Bs, poss = [], [], []
+        for i in range(w.n_inst):
+            pos, M, B = embed_with_decoys(w, i, 20, rng)
+            poss.append(pos); Ms.append(M); Bs.append(B)
+        big = W.Workload(w.name + "+decoys", w.L, 20, w.n_inst, w.seed, t, m, np.stack(Ms), np.stack(Bs))
+        print(f"cluster n=20 through decoys: {what}", flush=True)
+        got = solve(ppo, big)
+        for i in range(w.n_inst):
+            beta, p, cuts, order = CO.subset_dp(w.t[i], w.m[i], w.M[i], w.B[i])
+            assert bits(got[0][i]) == bits(beta) and got[1][i] == p, (what, i, got[0][i], beta, got[1][i], p)
+            want_order = np.full(20, -1, np.int32)
+            want_order[:p] = poss[i][order[:p]]
+            want_cuts = np.full(19, -1, np.int32)
+            want_cuts[:max(p - 1, 0)] = cuts[:max(p - 1, 0)]
+            assert np.array_equal(got[3][i], want_order), (what, i, got[3][i], want_order)
+            assert np.array_equal(got[2][i], want_cuts), (what, i)
+        assert max(int(x) for x in got[1]) >= 2
+
+
+def test_cluster_seventeen_and_eighteen_against_the_oracle(ppo):
+    """Above n = 16 with every segment count allowed and a short chain, where the oracle still finishes."""
+    for n, L, seed, cf in ((17, 16, 927, 0.35), (18, 12, 927, 0.5), (17, 12, 920, 0.35), (17, 16, 917, 0.35)):
+        w = W.random_instances(seed, 1, L, n, capacity_factor=cf * n)
+        print(f"cluster n={n} L={L}", flush=True)
+        ref = oracle(w, n, CO.subset_dp)
+        assert ref[1][0] >= 5
+        assert_same(solve(ppo, w), ref, f"n={n} L={L}")
+
+
 def test_cluster_sixteen_against_the_oracle(ppo):
     w = W.cluster_mixed(16, L=100, n_inst=1, seed=12)
     print("cluster n=16 L=100", flush=True)

@@ -123,6 +123,69 @@ def test_headline_in_two_ragged_pieces(ppo):
     assert_same(tuple(x.cpu().numpy() for x in out), O.subset_dp(w.t, w.m, w.M, w.B), "headline in two pieces")
 
 
+def test_headline_in_both_launch_shapes(ppo):
+    """The enumeration launch gives a workgroup 16 groups of orderings where the grid stays large (all 64
+    headline instances at once: 5040 / 16 * 2 * 64 = 40,320 workgroups) and 8 otherwise (16 instances at a
+    time: 10,080 workgroups of 16 groups would be fewer than 16,384).  Both shapes over the whole rank range
+    must leave the same keys, and they are the subset DP's."""
+    import torch
+    w = W.headline()
+    kf = math.factorial(w.k)
+    assert (kf // 720) % 16 == 0 and (kf // 720 // 16) * 2 * 64 >= 16384 > (kf // 720 // 16) * 2 * 16
+    dev = ppo.to_device(w)
+    ws = ppo.alloc_workspace(w.L, w.k, w.n_inst)
+    ppo.ppo_prepare(*dev, ws)
+    keys16 = torch.empty(w.n_inst, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_init_keys(keys16)
+    ppo.ppo_solve_range(w.L, w.k, w.n_inst, ws, 0, kf, keys16)
+    keys8 = torch.empty(w.n_inst, dtype=torch.int64, device="cuda:0")
+    ppo.ppo_init_keys(keys8)
+    for first in range(0, w.n_inst, 16):
+        part = tuple(x[first:first + 16].contiguous() for x in dev)
+        ws_part = ppo.alloc_workspace(w.L, w.k, 16)
+        ppo.ppo_prepare(*part, ws_part)
+        ppo.ppo_solve_range(w.L, w.k, 16, ws_part, 0, kf, keys8[first:first + 16])
+    torch.cuda.synchronize()
+    assert np.array_equal(keys16.cpu().numpy(), keys8.cpu().numpy())
+    ref = O.subset_dp(w.t, w.m, w.M, w.B)
+    k16 = keys16.cpu().numpy().view(np.uint64)
+    assert np.array_equal((k16 >> np.uint64(32)).astype(np.uint32), bits(ref[0]))
+    want_rank = np.array([O.rank(ref[2][i]) for i in range(w.n_inst)], np.uint64)
+    assert np.array_equal(k16 & np.uint64(0xFFFFFFFF), want_rank)
+
+
+def test_grouped_kernel_at_twelve_nodes(ppo):
+    """k = 12 with rows short enough for the grouped kernel (L - k + 2 <= 96): six prefix digits, five links
+    inside the prefix, three passes over the quotient rows.  Ragged rank ranges at both ends of [0, 12!)
+    through every route that takes a range, against the oracle on the same ranges."""
+    import torch
+    kf = math.factorial(12)
+    for seed, L in ((1, 30), (2, 47), (3, 60)):
+        w = W.random_instances(1200 + seed, 2, L, 12, capacity_factor=1.3 + 0.1 * seed)
+        dev = ppo.to_device(w)
+        ws = ppo.alloc_workspace(L, 12, 2)
+        ppo.ppo_prepare(*dev, ws)
+        for r0, r1 in ((0, 30011), (kf - 25013, kf), (kf // 2 - 977, kf // 2 + 20000)):
+            print(f"k=12 L={L} ranks [{r0}, {r1})", flush=True)
+            ref = O.exhaustive(w.t, w.m, w.M, w.B, rank_range=(r0, r1))[:3]
+            for bounded in (False, True):
+                keys = torch.empty(2, dtype=torch.int64, device="cuda:0")
+                ppo.ppo_init_keys(keys)
+                if bounded:
+                    ppo.ppo_solve_range_bounded(L, 12, 2, ws, r0, r1, keys, None)
+                else:
+                    ppo.ppo_solve_range(L, 12, 2, ws, r0, r1, keys)
+                out = tuple(x.cpu().numpy() for x in ppo.ppo_finalize(L, 12, 2, ws, keys))
+                torch.cuda.synchronize()
+                assert_same(out, ref, f"k=12 L={L} [{r0},{r1}) bounded={bounded}")
+            for j in range(2):
+                a, b = r0, min(r1, r0 + 6000)
+                got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], a, b)
+                torch.cuda.synchronize()
+                per, _ = O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], a, b)
+                assert np.array_equal(bits(got.cpu().numpy()), bits(per)), (L, j, a)
+
+
 def test_large_workload_full(ppo):
     w = W.large()
     got = gpu_solve(ppo, w)
@@ -164,6 +227,16 @@ def test_degenerate_shapes(ppo):
     got = gpu_solve(ppo, w)
     assert (bits(got[0]) == 0).all()
     assert_same(got, O.bruteforce(w.t, w.m, w.M, w.B), "t=0")
+    # a zero with the sign bit set is a size of zero too: gamma = +0, never the bit pattern of -0
+    w = W.random_instances(6, 30, 7, 3, capacity_factor=2.0)
+    w.t[:, ::2] = np.float32(-0.0)
+    assert np.signbit(w.t).any()
+    got = gpu_solve(ppo, w)
+    ref = O.bruteforce(w.t, w.m, w.M, w.B)
+    assert not (bits(ref[0]) == 0x80000000).any() and (bits(ref[0]) == 0).any()
+    assert_same(got, ref, "t=-0")
+    plus = W.Workload(w.name, w.L, w.k, w.n_inst, w.seed, np.abs(w.t), w.m, w.M, w.B)
+    assert_same(got, O.bruteforce(plus.t, plus.m, plus.M, plus.B), "t=-0 against t=+0")
 
 
 def test_memory_rule_in_binary64(ppo):
