@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ppo.h"
 #include "ppo_chain_asm.h"
 
@@ -19,6 +21,22 @@ constexpr uint32_t kCodeInf = 0x7C00u;   // value +inf
 constexpr uint32_t kInfBits = 0x7F800000u;
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// A kernel that asks for more than 64 KB of dynamic LDS has to have its limit raised first.  The limit is a
+// property of the kernel on a device, shared by every thread of the process, so it is raised once (per kernel
+// and device; `done` holds one bit per device) to all the LDS a compute unit has, never to a launch's own
+// size: two host threads launching different shapes then cannot lower each other's limit.
+constexpr int kLdsBytesPerCU = 160 * 1024;
+inline hipError_t allow_full_lds(const void* kernel, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPerCU);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 // Per-instance tables written by the precompute kernel and read by the enumeration and traceback.
 //   lo  [k][L+1] u8   lo[j][e] = first layer i such that layers [i,e) fit on node j (== e: none)

@@ -17,17 +17,6 @@ struct Graph {
     std::vector<int> first, adj;   // successors of v: adj[first[v] .. first[v+1])
 };
 
-// does every path from v reach `target` before a vertex deeper than it (or a dead end)?  memo: 0 unknown, 1 yes, 2 no
-bool all_paths_reach(const Graph& g, const std::vector<int>& depth, int v, int target, std::vector<unsigned char>& memo) {
-    if (v == target) return true;
-    if (depth[v] >= depth[target]) return false;           // as deep as the target or deeper, and not the target
-    if (memo[v]) return memo[v] == 1;
-    bool ok = g.first[v + 1] > g.first[v];                  // a dead end never reaches the target
-    for (int e = g.first[v]; ok && e < g.first[v + 1]; ++e) ok = all_paths_reach(g, depth, g.adj[e], target, memo);
-    memo[v] = ok ? 1 : 2;
-    return ok;
-}
-
 }  // namespace
 
 extern "C" int ppo_chain_from_dag(int n_vertices, int n_edges, const int32_t* edge_src, const int32_t* edge_dst,
@@ -80,25 +69,39 @@ extern "C" int ppo_chain_from_dag(int n_vertices, int n_edges, const int32_t* ed
         vertex_at[depth[v]] = v;
     }
     // partition points in order of depth
+    // Every path that leaves the last point p must reach the candidate u (alone at depth d) before a deeper
+    // vertex, and a path that ends does not reach it.  An edge leads to a strictly deeper vertex, and every
+    // vertex deeper than p is reached from p (all paths from the source pass p first).  So u qualifies iff no
+    // vertex of depth in [depth(p), d) is a dead end or has a successor deeper than d: one running maximum of
+    // "deepest successor" over the depth levels since p, no recursion, linear in the size of the graph.
+    constexpr int kDeadEnd = 0x7FFFFFFF;
+    std::vector<int> reach_of_level(deepest + 1, 0);
+    for (int v = 0; v < V; ++v) {
+        int far = g.first[v + 1] > g.first[v] ? 0 : kDeadEnd;
+        for (int e = g.first[v]; e < g.first[v + 1]; ++e) far = depth[g.adj[e]] > far ? depth[g.adj[e]] : far;
+        if (far > reach_of_level[depth[v]]) reach_of_level[depth[v]] = far;
+    }
     std::vector<int> points{source};
-    std::vector<unsigned char> memo(V);
+    int reach = reach_of_level[0];   // deepest successor of the levels from the last point's to d - 1
     for (int d = 1; d <= deepest; ++d) {
-        if (at_depth[d] != 1) continue;
-        const int u = vertex_at[d];
-        memo.assign(V, 0);
-        if (all_paths_reach(g, depth, points.back(), u, memo)) points.push_back(u);
+        if (at_depth[d] == 1 && reach <= d) {
+            points.push_back(vertex_at[d]);
+            reach = 0;
+        }
+        if (reach_of_level[d] > reach) reach = reach_of_level[d];
     }
     const bool tail = depth[points.back()] < deepest;
     const int L = (int)points.size() + (tail ? 1 : 0);
     *n_layers = L;
     if (L > max_layers) return PPO_ENOSPC;
     // layer of a vertex: the first partition point at its depth or deeper (the tail after the last one)
-    std::vector<double> sum(L, 0.0);
-    for (int v = 0; v < V; ++v) {
-        int i = 0;
-        while (i < (int)points.size() && depth[points[i]] < depth[v]) ++i;
-        sum[i] += (double)weight[v];
+    std::vector<int> layer_of_depth(deepest + 1);
+    for (int d = 0, i = 0; d <= deepest; ++d) {
+        while (i < (int)points.size() && depth[points[i]] < d) ++i;
+        layer_of_depth[d] = i;
     }
+    std::vector<double> sum(L, 0.0);
+    for (int v = 0; v < V; ++v) sum[layer_of_depth[depth[v]]] += (double)weight[v];
     for (int i = 0; i < L; ++i) {
         m[i] = (float)sum[i];
         const bool is_point = i < (int)points.size();

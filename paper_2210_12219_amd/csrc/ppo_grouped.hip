@@ -786,8 +786,8 @@ template <int MODE>
 static hipError_t launch_mode(const dim3& grid, const GroupedShape& gs, hipStream_t stream, const Layout& y, const void* ws,
                               uint32_t rank_begin, uint32_t rank_end, uint32_t gbeg, uint32_t gend, uint32_t gpb,
                               uint64_t* best_key, float* beta_export, uint64_t* skipped_groups) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&enumerate_grouped_kernel<MODE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)gs.total_bytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_grouped_kernel<MODE>), lds_allowed);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(enumerate_grouped_kernel<MODE>, grid, dim3(kGrpThreads), gs.total_bytes, stream, y,
                        static_cast<const unsigned char*>(ws), rank_begin, rank_end, gbeg, gend, gpb,

@@ -105,3 +105,21 @@ def test_bad_graphs_are_refused():
     for bad in ([(0, 1), (1, 2), (2, 1)], [(0, 2), (1, 2)]):
         with pytest.raises(ValueError):
             DO.chain_from_dag(3, bad, np.ones(3), np.ones(3))
+
+
+def test_a_very_long_layer_graph_needs_no_deep_recursion():
+    """300,000 residual blocks in a row, and one shortcut from the source past all of them: the walk from a
+    partition point towards a candidate passes every vertex in between."""
+    blocks = 300_000
+    edges, v = [], 0
+    for _ in range(blocks):
+        edges += [(v, v + 1), (v + 1, v + 2), (v, v + 2)]
+        v += 2
+    n = v + 1
+    w = np.ones(n, np.float32)
+    o = np.full(n, 2.0, np.float32)
+    t, m, p = binding.ppo_chain_from_dag(n, edges, w, o)
+    assert len(p) == blocks + 1 and list(p[:3]) == [0, 2, 4] and (m[1:] == 2.0).all() and m[0] == 1.0
+    edges.append((0, n - 1))              # now nothing but the source and the last vertex is a point
+    t, m, p = binding.ppo_chain_from_dag(n, edges, w, o)
+    assert list(p) == [0, n - 1] and m[1] == np.float32(n - 1)
