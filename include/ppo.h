@@ -97,6 +97,18 @@ int ppo_solve_ws(const float *t, const float *m, int L, const float *M, const fl
                  float *beta_out, int32_t *cuts_out, int32_t *order_out, void *workspace, size_t workspace_bytes,
                  void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): ppo_solve with its scratch in an array that is part of the library itself,
+ * PPO_STATIC_SCRATCH_BYTES per GPU, held from the library's first use on that GPU until the process ends.
+ * Calls no allocator of any kind.  Arguments, results and errors as for ppo_solve; in addition
+ * PPO_ENOSPC when ppo_workspace_bytes(L, k, n_inst) exceeds PPO_STATIC_SCRATCH_BYTES (the headline shape,
+ * L = 100, k = 10, fits 127 instances).  Every call on one GPU uses that GPU's one array: calls that overlap
+ * in time on one GPU (different streams or threads) race and must be serialised by the caller.  The first
+ * call on a device looks up the array's address (hipGetSymbolAddress); make it outside a capture. */
+#define PPO_STATIC_SCRATCH_BYTES (16u << 20)
+int ppo_solve_static(const float *t, const float *m, int L, const float *M, const float *B, int k, int n_inst,
+                     float *beta_out, int32_t *cuts_out, int32_t *order_out, void *stream);
+
 /* The same search in separate stages, for callers that split the rank range (over time, streams or
  * devices) or want to time the stages.  All stages of one search share one workspace.
  *

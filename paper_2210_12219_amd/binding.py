@@ -47,6 +47,7 @@ def load() -> C.CDLL:
         lib.ppo_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_workspace_bytes.restype = sz
         lib.ppo_solve.argtypes = inst + [i, vp, vp, vp, vp]
+        lib.ppo_solve_static.argtypes = inst + [i, vp, vp, vp, vp]
         lib.ppo_solve_ws.argtypes = inst + [i, vp, vp, vp, vp, sz, vp]
         lib.ppo_prepare.argtypes = inst + [i, vp, sz, vp]
         lib.ppo_init_keys.argtypes = [vp, i, vp]
@@ -142,6 +143,20 @@ def ppo_solve(t, m, M, B, out=None, workspace=None, stream=None):
     else:
         assert workspace.is_cuda and workspace.dtype == torch.uint8
         _check(load().ppo_solve_ws(*args, C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    return beta, cuts, order
+
+
+PPO_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def ppo_solve_static(t, m, M, B, out, stream=None):
+    """ppo_solve with the library's own static scratch: allocates nothing (the caller brings the outputs)."""
+    torch = _torch()
+    n, L, k = _shape(t, m, M, B)
+    beta, cuts, order = out
+    f32, i32 = torch.float32, torch.int32
+    _check(load().ppo_solve_static(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, n, _dev(beta, f32),
+                                   C.c_void_p(cuts.data_ptr()), _dev(order, i32), _stream(stream)))
     return beta, cuts, order
 
 

@@ -1,4 +1,5 @@
 // C ABI of the ppo library (declared in include/ppo.h): argument checks, workspace carving, launches.
+#include <mutex>
 #include <string>
 
 #include "ppo_common.h"
@@ -310,6 +311,48 @@ int ppo_solve(const float* t, const float* m, int L, const float* M, const float
     hipError_t e = hipFreeAsync(ws, s);
     if (rc == PPO_OK && e != hipSuccess) rc = hip_fail(e, "hipFreeAsync");
     return rc;
+}
+
+// Scratch of ppo_solve_static: one array per GPU, part of the library's code object, held until the process
+// ends.  In host code this name only stands for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[PPO_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up at the first call on that device)
+int static_scratch(void** out) {
+    int dev = -1;
+    PPO_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return PPO_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        PPO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress (static scratch)");
+        if (!p) return PPO_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PPO_OK;
+}
+}  // namespace
+
+int ppo_solve_static(const float* t, const float* m, int L, const float* M, const float* B, int k, int n_inst,
+                     float* beta_out, int32_t* cuts_out, int32_t* order_out, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
+    if (ppo_workspace_bytes(L, k, n_inst) > (size_t)PPO_STATIC_SCRATCH_BYTES) return PPO_ENOSPC;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    // every table a kernel reads is written by the stage before it and the keys are set by a fill kernel, so
+    // whatever the previous call left in the array does not matter
+    return ppo_solve_ws(t, m, L, M, B, k, n_inst, beta_out, cuts_out, order_out, ws, (size_t)PPO_STATIC_SCRATCH_BYTES, stream);
 }
 
 int ppo_eval_orderings(const float* t, const float* m, int L, const float* M, const float* B, int k,
