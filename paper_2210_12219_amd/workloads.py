@@ -265,3 +265,23 @@ def cluster_mixed(n: int, L: int = 100, n_inst: int = 8, seed: int = 6, capacity
         Ms.append(raw * (capacity_factor * float(np.sum(m)) / float(np.mean(raw))))
         Bs.append(_symmetric_bandwidth(rng, n, 1.0, 100.0))
     return _finish(f"cluster_mixed_n{n}", L, n, n_inst, seed, ts, ms, Ms, Bs)
+
+
+# ---------------------------------------------------------------------------------------------
+# Compute stages (Sec. I, Eq. 1): per-layer work and per-node speed beside a workload's arrays.
+# ---------------------------------------------------------------------------------------------
+def compute_terms(w: Workload, seed: int = 7, seconds: float = 1.0, quantised: bool = False):
+    """(work [n_inst, L], speed [n_inst, k]) float32 for the instances of w.  The paper gives one data
+    point (ResNet50 on a Raspberry Pi 4: 225 ms for the whole model, 7.5 times less than one average
+    transfer) and no per-layer figures, so these are synthetic: work per layer log-uniform over a
+    factor of 30, speeds 1x, 2x or 4x a unit, scaled so that the whole model takes `seconds` on a node
+    of speed 1.  With quantised=True both take few small integer values (equal stage times occur)."""
+    rng = np.random.default_rng(seed)
+    if quantised:
+        work = rng.integers(1, 5, (w.n_inst, w.L)).astype(np.float64)
+        speed = rng.integers(1, 4, (w.n_inst, w.k)).astype(np.float64)
+    else:
+        work = np.exp(rng.uniform(np.log(1.0), np.log(30.0), (w.n_inst, w.L)))
+        work *= seconds / work.sum(axis=1, keepdims=True)
+        speed = rng.choice(np.array([1.0, 2.0, 4.0]), size=(w.n_inst, w.k))
+    return np.ascontiguousarray(work, dtype=np.float32), np.ascontiguousarray(speed, dtype=np.float32)
