@@ -165,6 +165,29 @@ int ppo_finalize(int L, int k, int n_inst, const void *workspace, size_t workspa
 int ppo_eval_orderings(const float *t, const float *m, int L, const float *M, const float *B, int k,
                        uint64_t rank_begin, uint64_t rank_end, float *beta_per_ordering, void *stream);
 
+/* The search with the compute-time term (paper Sec. I, Eq. 1: the bottleneck latency is the largest stage of
+ * the pipeline, the compute time c_k of the operations on node k and the communication time gamma_k between
+ * nodes k-1 and k alike; the paper then drops the compute times, Eq. 2; this entry point keeps them).
+ *   w [n_inst][L]   compute work of layer i (any unit, >= 0)
+ *   v [n_inst][k]   speed of node j (that unit per second, > 0)
+ *   comp_s = (work of segment s) / v[order[s]]:  Q[i+1] = Q[i] + (double)w[i] in index order in binary64,
+ *            comp = (float)((Q[e] - Q[i]) / (double)v[j]), one rounding to binary32
+ *   beta   = max over every comp_s (s = 0..k-1) and every gamma_s (s = 1..k-1, Eq. 3)
+ * Everything else (memory rule, arithmetic of gamma, uniqueness of order and cuts, outputs, +inf and -1 when
+ * nothing is feasible) as for ppo_solve; with w = 0 the results are those of ppo_solve bit for bit.  Every
+ * ordering runs its own DP on binary32 values (a compute stage depends on both ends of its segment, so the
+ * 16-bit order codes of ppo_solve do not apply); a plain path, not the tuned one.  Allocates its scratch
+ * (k (L+1)^2 words per instance, mostly) with the stream-ordered allocator. */
+int ppo_solve_ct(const float *t, const float *m, const float *w, int L, const float *M, const float *v,
+                 const float *B, int k, int n_inst, float *beta_out, int32_t *cuts_out, int32_t *order_out,
+                 void *stream);
+
+/* Diagnostic export for the same: beta (with the compute-time term) of each ordering of ONE instance with
+ * rank in [rank_begin, rank_end), written to beta_per_ordering [rank_end - rank_begin]. */
+int ppo_eval_orderings_ct(const float *t, const float *m, const float *w, int L, const float *M, const float *v,
+                          const float *B, int k, uint64_t rank_begin, uint64_t rank_end, float *beta_per_ordering,
+                          void *stream);
+
 /* Cluster form (paper Sec. III-B: the partitioner fixes how many partitions there are and the placement
  * picks that many nodes of the communication graph as a simple path; Sec. IV: clusters of 5 to 50
  * devices).  The exact counterpart: over every number of segments p, 1 <= p <= min(max_segments, L),

@@ -56,6 +56,9 @@ def load() -> C.CDLL:
         lib.ppo_solve_subsets.argtypes = [i, i, i, vp, sz, vp, vp]
         lib.ppo_finalize.argtypes = [i, i, i, vp, sz, vp, vp, vp, vp, vp]
         lib.ppo_eval_orderings.argtypes = inst + [u64, u64, vp, vp]
+        inst_ct = [vp, vp, vp, i, vp, vp, vp, i]
+        lib.ppo_solve_ct.argtypes = inst_ct + [i, vp, vp, vp, vp]
+        lib.ppo_eval_orderings_ct.argtypes = inst_ct + [u64, u64, vp, vp]
         lib.ppo_chain_from_dag.argtypes = [i, i, vp, vp, vp, vp, i, vp, vp, vp, vp]
         lib.ppo_min_sum_partition.argtypes = [vp, vp, i, vp, i, vp, vp, vp, vp]
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
@@ -229,6 +232,30 @@ def ppo_eval_orderings(t, m, M, B, rank_begin, rank_end, stream=None):
     out = torch.empty(int(rank_end - rank_begin), dtype=f32, device=t.device)
     _check(load().ppo_eval_orderings(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), k, int(rank_begin),
                                      int(rank_end), C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def ppo_solve_ct(t, m, w, M, v, B, out=None, stream=None):
+    """The search with the compute-time term: w [n,L] per-layer work, v [n,k] node speeds; (beta, cuts, order)."""
+    torch = _torch()
+    n, L, k = _shape(t, m, M, B)
+    assert tuple(w.shape) == (n, L) and tuple(v.shape) == (n, k)
+    beta, cuts, order = out if out is not None else alloc_outputs(n, k, t.device)
+    f32, i32 = torch.float32, torch.int32
+    _check(load().ppo_solve_ct(_dev(t, f32), _dev(m, f32), _dev(w, f32), L, _dev(M, f32), _dev(v, f32), _dev(B, f32), k, n,
+                               _dev(beta, f32), C.c_void_p(cuts.data_ptr()), _dev(order, i32), _stream(stream)))
+    return beta, cuts, order
+
+
+def ppo_eval_orderings_ct(t, m, w, M, v, B, rank_begin, rank_end, stream=None):
+    """beta (with the compute-time term) of every ordering of ONE instance with rank in the range."""
+    torch = _torch()
+    L, k = t.shape[0], M.shape[0]
+    f32 = torch.float32
+    out = torch.empty(int(rank_end - rank_begin), dtype=f32, device=t.device)
+    _check(load().ppo_eval_orderings_ct(_dev(t, f32), _dev(m, f32), _dev(w, f32), L, _dev(M, f32), _dev(v, f32),
+                                        _dev(B, f32), k, int(rank_begin), int(rank_end), C.c_void_p(out.data_ptr()),
+                                        _stream(stream)))
     return out
 
 

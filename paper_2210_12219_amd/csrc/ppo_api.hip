@@ -23,6 +23,11 @@ hipError_t launch_cluster_tables_from_prepared(const Layout&, const void*, int, 
 hipError_t launch_min_sum_partition(const float*, const float*, int, const float*, int, int32_t*, int32_t*, double*,
                                     hipStream_t);
 hipError_t launch_valu_probe(int, int, uint32_t*, hipStream_t);
+size_t ct_tables_bytes(int L, int k);
+hipError_t launch_ct_tables(const float*, const float*, const float*, const float*, const float*, const float*, int, int,
+                            int, void*, hipStream_t);
+hipError_t launch_ct_enumerate(int, int, int, const void*, uint32_t, uint32_t, uint64_t*, float*, hipStream_t);
+hipError_t launch_ct_traceback(int, int, int, const void*, const uint64_t*, float*, int32_t*, int32_t*, hipStream_t);
 }  // namespace ppo
 
 namespace {
@@ -374,6 +379,57 @@ int ppo_eval_orderings(const float* t, const float* m, int L, const float* M, co
     hipError_t e2 = hipFreeAsync(ws, s);
     if (rc == PPO_OK && e2 != hipSuccess) rc = hip_fail(e2, "hipFreeAsync");
     return rc;
+}
+
+// The search with the compute-time term: tables, one DP per ordering, traceback, all on scratch from the
+// stream-ordered allocator (tables of every instance, then one key each).
+int ppo_solve_ct(const float* t, const float* m, const float* w, int L, const float* M, const float* v, const float* B,
+                 int k, int n_inst, float* beta_out, int32_t* cuts_out, int32_t* order_out, void* stream) {
+    int rc = check_shape(L, k, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !w || !M || !v || !B || !beta_out || !order_out || (k > 1 && !cuts_out)) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t tables = ppo::ct_tables_bytes(L, k);
+    unsigned char* ws = nullptr;
+    PPO_HIP(hipMallocAsync(reinterpret_cast<void**>(&ws), tables * (size_t)n_inst + (size_t)n_inst * sizeof(uint64_t), s),
+            "hipMallocAsync (compute-term tables)");
+    uint64_t* keys = reinterpret_cast<uint64_t*>(ws + tables * (size_t)n_inst);   // tables is a multiple of 256
+    hipError_t e = ppo::launch_init_keys(keys, n_inst, s);
+    for (int first = 0; first < n_inst && e == hipSuccess; first += kInstPerLaunch) {
+        const int n = n_inst - first < kInstPerLaunch ? n_inst - first : kInstPerLaunch;
+        unsigned char* wsi = ws + tables * (size_t)first;
+        e = ppo::launch_ct_tables(t + (size_t)first * L, m + (size_t)first * L, w + (size_t)first * L, M + (size_t)first * k,
+                                  v + (size_t)first * k, B + (size_t)first * k * k, L, k, n, wsi, s);
+        if (e == hipSuccess) e = ppo::launch_ct_enumerate(L, k, n, wsi, 0u, ppo::factorial_u32(k), keys + first, nullptr, s);
+        if (e == hipSuccess)
+            e = ppo::launch_ct_traceback(L, k, n, wsi, keys + first, beta_out + first, cuts_out + (size_t)first * (k - 1),
+                                         order_out + (size_t)first * k, s);
+    }
+    const hipError_t e2 = hipFreeAsync(ws, s);
+    PPO_HIP(e, "compute-term search launch");
+    PPO_HIP(e2, "hipFreeAsync (compute-term tables)");
+    return PPO_OK;
+}
+
+int ppo_eval_orderings_ct(const float* t, const float* m, const float* w, int L, const float* M, const float* v,
+                          const float* B, int k, uint64_t rank_begin, uint64_t rank_end, float* beta_per_ordering,
+                          void* stream) {
+    int rc = check_shape(L, k, 1);
+    if (rc) return rc;
+    if (rank_begin > rank_end || rank_end > (uint64_t)ppo::factorial_u32(k)) return PPO_EINVAL;
+    if (rank_begin == rank_end) return PPO_OK;
+    if (!t || !m || !w || !M || !v || !B || !beta_per_ordering) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void* ws = nullptr;
+    PPO_HIP(hipMallocAsync(&ws, ppo::ct_tables_bytes(L, k), s), "hipMallocAsync (compute-term tables)");
+    hipError_t e = ppo::launch_ct_tables(t, m, w, M, v, B, L, k, 1, ws, s);
+    if (e == hipSuccess)
+        e = ppo::launch_ct_enumerate(L, k, 1, ws, (uint32_t)rank_begin, (uint32_t)rank_end, nullptr, beta_per_ordering, s);
+    const hipError_t e2 = hipFreeAsync(ws, s);
+    PPO_HIP(e, "compute-term per-ordering launch");
+    PPO_HIP(e2, "hipFreeAsync (compute-term tables)");
+    return PPO_OK;
 }
 
 int ppo_probe_valu(int waves_per_simd, int iters, uint32_t* sink, void* stream) {
