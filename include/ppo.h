@@ -71,12 +71,15 @@ const char *ppo_strerror(int code);
 
 /* Which enumeration kernel ppo_solve_range (and everything built on it) launches.  Process-wide,
  * not synchronised with calls in flight on other threads; meant for tests and tuning.
- *   PPO_ENUM_AUTO     grouped kernel (wave-uniform memory windows) when k >= 6 and L-k+2 <= 96,
- *                     otherwise the generic kernel
+ *   PPO_ENUM_AUTO     paired kernel (two orderings per lane, rows in registers, wave-uniform memory windows)
+ *                     when k >= 6 and L-k+2 <= 96, otherwise the generic kernel
  *   PPO_ENUM_GENERIC  always the generic kernel (one ordering per lane, any shape within the limits)
- * Both produce identical results. */
+ *   PPO_ENUM_GROUPED  the grouped kernel (one ordering per lane, rows in LDS, wave-uniform windows) where it
+ *                     applies (same shapes), otherwise the generic kernel
+ * All produce identical results. */
 #define PPO_ENUM_AUTO 0
 #define PPO_ENUM_GENERIC 1
+#define PPO_ENUM_GROUPED 2
 int ppo_set_enumeration(int variant);
 
 /* Bytes of device scratch that ppo_solve_ws / ppo_prepare need for this shape (0 on bad shape). */
@@ -102,7 +105,7 @@ int ppo_solve_ws(const float *t, const float *m, int L, const float *M, const fl
  * PPO_STATIC_SCRATCH_BYTES per GPU, held from the library's first use on that GPU until the process ends.
  * Calls no allocator of any kind.  Arguments, results and errors as for ppo_solve; in addition
  * PPO_ENOSPC when ppo_workspace_bytes(L, k, n_inst) exceeds PPO_STATIC_SCRATCH_BYTES (the headline shape,
- * L = 100, k = 10, fits 127 instances).  Every call on one GPU uses that GPU's one array: calls that overlap
+ * L = 100, k = 10, fits 112 instances).  Every call on one GPU uses that GPU's one array: calls that overlap
  * in time on one GPU (different streams or threads) race and must be serialised by the caller.  The first
  * call on a device looks up the array's address (hipGetSymbolAddress); make it outside a capture. */
 #define PPO_STATIC_SCRATCH_BYTES (16u << 20)

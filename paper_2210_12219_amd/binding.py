@@ -108,7 +108,7 @@ def ppo_strerror(code: int) -> str:
     return load().ppo_strerror(code).decode()
 
 
-PPO_ENUM_AUTO, PPO_ENUM_GENERIC = 0, 1
+PPO_ENUM_AUTO, PPO_ENUM_GENERIC, PPO_ENUM_GROUPED = 0, 1, 2
 
 
 def ppo_set_enumeration(variant: int):

@@ -32,8 +32,27 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    check_paired_kernel(verbose)
     os.replace(tmp, LIB)
     return LIB
+
+
+def check_paired_kernel(verbose: bool = False) -> None:
+    """The paired enumeration kernel keeps values in fixed registers between inline-assembly blocks and jumps to
+    offsets computed from instruction sizes: verify both on the code the toolchain emitted (csrc/check_pair_code.py)."""
+    import sys
+    import tempfile
+    src = os.path.join(PKG, "csrc", "ppo_paired.hip")
+    with tempfile.TemporaryDirectory() as d:
+        asm, obj = os.path.join(d, "paired.s"), os.path.join(d, "paired.elf")
+        device_flags = [f for f in FLAGS if f not in ("-fPIC", "-shared")]
+        subprocess.check_call([HIPCC, *device_flags, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
+                               "--cuda-device-only", "-S", "-o", asm, src])
+        clang = os.path.join(os.path.dirname(os.path.realpath(HIPCC)), "..", "llvm", "bin", "clang")
+        if not os.path.exists(clang):
+            clang = "/opt/rocm/llvm/bin/clang"
+        subprocess.check_call([clang, "-x", "assembler", "-target", "amdgcn-amd-amdhsa", "-mcpu=gfx950", "-c", asm, "-o", obj])
+        subprocess.check_call([sys.executable, os.path.join(PKG, "csrc", "check_pair_code.py"), asm, obj])
 
 
 if __name__ == "__main__":

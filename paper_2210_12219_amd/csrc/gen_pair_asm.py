@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Writes ppo_pair_asm.h: the register-resident row steps of the paired enumeration kernel, as inline
+assembly for gfx950, and the table of entry offsets the precompute kernel needs.
+
+A lane holds the DP row of its pair of orderings in registers: entry u (1 <= u <= 95) in v[RB + u], the lower
+ordering in bits 0..15 and the upper one in bits 16..31, both as 16-bit order codes.  Output u of a row is the
+minimum of the w entries u, u-1, ..., u-w+1 of the row before it (w, the window length, is the same for all
+lanes and both halves: every ordering of the wave has the same node at this row) and replaces entry u in
+place; the outputs are worked from the highest u down, so every input is still there when it is needed.
+
+The code of a row is unrolled over u.  For every u there are two descending chains of packed three-input
+minima (two new entries per instruction), one for even and one for odd w, each ending in the instruction that
+writes v[RB + u]; a chain is entered at the step that leaves exactly w entries to fold, by a computed jump
+whose target comes from a table the precompute kernel wrote for this (node, row): 16-bit offsets from the
+block's base in units of four bytes, two per dword, read into scalar registers.  After the last instruction of
+a chain the header of output u-1 follows (a copy of it after each chain), which starts the accumulator at
++inf and jumps again.  w = 0 (no legal segment start) writes +inf and branches to that header.
+
+Blocks (each one `asm volatile` statement in the kernel; fixed registers, declared clobbered there):
+  LOAD     entries NE-1..1 from the lane's slot in LDS (one dword per entry, 1536 bytes apart)
+  LOADX    the same, then the upper half of every entry replaced by that of another slot (the pairing changes)
+  QMAX     entry u = max(entry u, code of t[u+s-2]/B of the lane's link), both halves the same link
+  COMPUTE  the chains
+  STORE    entries NE-1..1 to the lane's slot
+  EXTRACT  entry NE-1 to an output register
+Every block that works on a range of entries is entered at entry NE-1 by a computed jump (all entries of one
+block have the same size).
+"""
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+UMAX = 95            # highest entry index a row can have (L - k + 2 <= 96)
+RB = 40              # entry u lives in v[RB + u]
+VQ = RB + UMAX + 1   # 24 registers for the quotient dwords of QMAX
+VACC = VQ + 24
+VINF = VACC + 1
+VA1 = VINF + 1       # slot address + 43 rows, + 86 rows
+VA2 = VA1 + 1
+VB1 = VA2 + 1        # the same for the second slot of LOADX
+VB2 = VB1 + 1
+VTOP = VB2           # highest fixed register
+ROW_BYTES = 384 * 4  # distance of two entries of one slot in LDS
+ST0 = 36             # s[ST0 .. ST0+47]: the offset table of the row (two offsets per register)
+SPC = 84             # s[84:85] jump target, s[86:87] base
+SBASE = 86
+STMP = 88
+SMASK = 89
+
+
+def R(u):
+    assert 1 <= u <= UMAX
+    return f"v{RB + u}"
+
+
+def addr_for(u, a0, a1, a2):
+    """address register and offset of entry u (entries 1..43 from a0, 44..86 from a1, 87..95 from a2)."""
+    i = u - 1
+    if i < 43:
+        return a0, i * ROW_BYTES
+    if i < 86:
+        return a1, (i - 43) * ROW_BYTES
+    return a2, (i - 86) * ROW_BYTES
+
+
+def entry_jump(stride):
+    """jump to entry `skip` of the table that follows (skip = 95 - highest entry, in %[skip])."""
+    return [f"s_mul_i32 s{STMP}, %[skip], {stride}",
+            f"s_add_u32 s{STMP}, s{STMP}, 12",
+            f"s_getpc_b64 s[{SPC}:{SPC + 1}]",
+            f"s_add_u32 s{SPC}, s{SPC}, s{STMP}",
+            f"s_addc_u32 s{SPC + 1}, s{SPC + 1}, 0",
+            f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
+
+
+def block_load(extra):
+    """extra: after the lane's own slot, the upper half of every entry is replaced by the upper half of the same
+    entry of a second slot.  (A 16-bit load into a register half is no use here: on this chip it clears the other
+    half.)  The second slot is read whole, 24 entries at a time, and merged under a mask."""
+    lines = [f"v_add_u32_e32 v{VA1}, {43 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {86 * ROW_BYTES}, %[addr]"]
+    if extra:
+        lines += [f"v_add_u32_e32 v{VB1}, {43 * ROW_BYTES}, %[addr2]", f"v_add_u32_e32 v{VB2}, {86 * ROW_BYTES}, %[addr2]",
+                  f"s_mov_b32 s{SMASK}, 0xffff"]
+    lines += entry_jump(8)
+    for u in range(UMAX, 0, -1):
+        a, off = addr_for(u, "%[addr]", f"v{VA1}", f"v{VA2}")
+        lines.append(f"ds_read_b32 {R(u)}, {a} offset:{off}")
+    if extra:
+        for first in range(1, UMAX + 1, 24):
+            us = list(range(first, min(first + 24, UMAX + 1)))
+            for n, u in enumerate(us):
+                b, off2 = addr_for(u, "%[addr2]", f"v{VB1}", f"v{VB2}")
+                lines.append(f"ds_read_b32 v{VQ + n}, {b} offset:{off2}")
+            lines.append("s_waitcnt lgkmcnt(0)")
+            for n, u in enumerate(us):
+                lines.append(f"v_bfi_b32 {R(u)}, s{SMASK}, {R(u)}, v{VQ + n}")
+    return lines
+
+
+def block_store():
+    lines = [f"v_add_u32_e32 v{VA1}, {43 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {86 * ROW_BYTES}, %[addr]"]
+    lines += entry_jump(8)
+    for u in range(UMAX, 0, -1):
+        a, off = addr_for(u, "%[addr]", f"v{VA1}", f"v{VA2}")
+        lines.append(f"ds_write_b32 {a}, {R(u)} offset:{off}")
+    return lines
+
+
+def block_qmax():
+    """%[qaddr]: LDS byte address of the lane's quotient dword for entries 1 and 2; dword j covers entries 2j+1
+    (lower half) and 2j+2 (upper half).  The loaded entries must have arrived: waits for everything first."""
+    lines = []
+    for batch in range(2):
+        for j in range(24 * batch, 24 * batch + 24):
+            lines.append(f"ds_read_b32 v{VQ + j % 24}, %[qaddr] offset:{4 * j}")
+        lines.append("s_waitcnt lgkmcnt(0)")
+        for j in range(24 * batch, 24 * batch + 24):
+            for h in range(2):
+                u = 2 * j + 1 + h
+                if u <= UMAX:
+                    lines.append(f"v_pk_max_u16 {R(u)}, {R(u)}, v{VQ + j % 24} op_sel:[0,{h}] op_sel_hi:[1,{h}]")
+    return lines
+
+
+def header(u):
+    """start of output u: accumulator +inf, jump to the entry the table names (five instructions, 20 bytes)."""
+    x, hi = (u - 1) // 2, (u - 1) & 1
+    first = f"s_lshr_b32 s{STMP}, s{ST0 + x}, 16" if hi else f"s_and_b32 s{STMP}, s{ST0 + x}, s{SMASK}"
+    return [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
+            f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
+            f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
+            f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
+
+
+HEADER_BYTES = 20
+
+
+def jmax_even(u):
+    return (u - 2) // 2 if u >= 2 else -1     # steps before the last instruction of the even chain
+
+
+def jmax_odd(u):
+    return (u - 1) // 2
+
+
+def block_compute():
+    """returns (lines, offsets) with offsets[u] = (even_base, odd_base, zero) and offsets['end'], in bytes from
+    the base (the instruction after s_getpc)."""
+    lines = [f"s_load_dwordx16 s[{ST0}:{ST0 + 15}], %[desc], 0x0",
+             f"s_load_dwordx16 s[{ST0 + 16}:{ST0 + 31}], %[desc], 0x40",
+             f"s_load_dwordx16 s[{ST0 + 32}:{ST0 + 47}], %[desc], 0x80",
+             f"s_mov_b32 s{SMASK}, 0xffff",
+             f"v_mov_b32_e32 v{VINF}, 0x7c007c00",
+             f"s_mul_i32 s{STMP}, %[skip], {HEADER_BYTES}",
+             "s_waitcnt lgkmcnt(0)",
+             f"s_getpc_b64 s[{SBASE}:{SBASE + 1}]"]
+    pos = 0   # bytes from the base
+    body = []
+
+    def emit(ls, size):
+        nonlocal pos
+        body.extend(ls)
+        pos += size
+
+    # the first header: jump to the standalone header of the highest entry
+    emit([f"s_add_u32 s{STMP}, s{STMP}, 16",           # distance from the base to the table of standalone headers
+          f"s_add_u32 s{SPC}, s{SBASE}, s{STMP}",
+          f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
+          f"s_setpc_b64 s[{SPC}:{SPC + 1}]"], 16)
+    for u in range(UMAX, 0, -1):
+        emit(header(u), HEADER_BYTES)
+    offsets = {}
+    for u in range(UMAX, 0, -1):
+        nxt = header(u - 1) if u > 1 else None
+        je, jo = jmax_even(u), jmax_odd(u)
+        even_base = pos
+        if je >= 0:
+            for J in range(je, 0, -1):
+                emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"], 8)
+            emit([f"v_pk_minimum3_f16 {R(u)}, v{VACC}, {R(u)}, {R(u - 1)}"], 8)
+            if nxt:
+                emit(nxt, HEADER_BYTES)
+            else:
+                emit(["s_branch ppo_pair_end"], 4)
+        odd_base = pos
+        for J in range(jo, 0, -1):
+            emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"], 8)
+        emit([f"v_pk_min_u16 {R(u)}, v{VACC}, {R(u)}"], 8)
+        if nxt:
+            emit(nxt, HEADER_BYTES)
+        else:
+            emit(["s_branch ppo_pair_end"], 4)
+        zero = pos
+        emit([f"v_mov_b32_e32 {R(u)}, v{VINF}"], 4)
+        if nxt:
+            emit(nxt, HEADER_BYTES)
+        offsets[u] = (even_base if je >= 0 else None, odd_base, zero)
+    offsets["end"] = pos
+    body.append("ppo_pair_end:")
+    return lines + body, offsets
+
+
+def block_extract():
+    lines = entry_jump(8)
+    for u in range(UMAX, 0, -1):
+        lines += [f"v_mov_b32_e32 %[res], {R(u)}", "s_branch ppo_pair_out"]
+    lines.append("ppo_pair_out:")
+    return lines
+
+
+def entry_offset(offsets, u, w):
+    """byte offset of the instruction at which output u with a window of w entries starts."""
+    assert 0 <= w <= u
+    even_base, odd_base, zero = offsets[u]
+    if w == 0:
+        return zero
+    if w & 1:
+        return odd_base + 8 * (jmax_odd(u) - (w - 1) // 2)
+    return even_base + 8 * (jmax_even(u) - (w // 2 - 1))
+
+
+def c_string(lines):
+    return " \\\n".join('    "' + ln + '\\n"' for ln in lines)
+
+
+def main():
+    compute, offsets = block_compute()
+    assert offsets["end"] // 4 < 65536
+    clobber_v = ", ".join(f'"v{i}"' for i in range(RB + 1, VTOP + 1))
+    clobber_s = ", ".join(f'"s{i}"' for i in range(ST0, ST0 + 48)) + ", " + ", ".join(f'"s{i}"' for i in range(SPC, SMASK + 1))
+    out = ["// Generated by gen_pair_asm.py; do not edit.  Row steps of the paired enumeration kernel (see the generator).",
+           "#pragma once", "#include <stdint.h>", "",
+           f"#define PPO_PAIR_UMAX {UMAX}",
+           f"#define PPO_PAIR_RB {RB}",
+           f"#define PPO_PAIR_VTOP {VTOP}",
+           f"#define PPO_PAIR_ROW_BYTES {ROW_BYTES}",
+           f"#define PPO_PAIR_CLOBBER_V {clobber_v}",
+           f"#define PPO_PAIR_CLOBBER_S {clobber_s}, \"scc\"", ""]
+    for name, lines in (("LOAD", block_load(False)), ("LOADX", block_load(True)), ("STORE", block_store()),
+                        ("QMAX", block_qmax()), ("COMPUTE", compute), ("EXTRACT", block_extract())):
+        out.append(f"#define PPO_PAIR_{name}_ASM \\")
+        out.append(c_string(lines))
+        out.append("")
+    # entry offsets for the precompute kernel, in units of four bytes from the base of COMPUTE
+    ev = [0] + [(offsets[u][0] or 0) // 4 for u in range(1, UMAX + 1)]
+    od = [0] + [offsets[u][1] // 4 for u in range(1, UMAX + 1)]
+    ze = [0] + [offsets[u][2] // 4 for u in range(1, UMAX + 1)]
+    out += ["namespace ppo {",
+            "// Where output u of a row with a window of w entries (0 <= w <= u) starts: offset of that instruction from",
+            "// the base of the COMPUTE block, in units of four bytes.  Even w: the even chain of u, entered so that",
+            "// w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps; w = 0: the",
+            "// instruction that writes +inf.",
+            "__host__ __device__ inline uint32_t pair_entry_offset(uint32_t u, uint32_t w) {",
+            "    constexpr uint16_t even_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ev)) + "};",
+            "    constexpr uint16_t odd_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, od)) + "};",
+            "    constexpr uint16_t zero[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ze)) + "};",
+            "    if (w == 0u) return zero[u];",
+            "    if (w & 1u) return odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
+            "    return even_base[u] + 2u * ((u - 2u) / 2u - (w / 2u - 1u));",
+            "}",
+            f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block",
+            "}  // namespace ppo", ""]
+    path = os.path.join(HERE, "ppo_pair_asm.h")
+    with open(path, "w") as f:
+        f.write("\n".join(out))
+    # the same offsets for the build step's check of the compiled code
+    import json
+    with open(os.path.join(HERE, "ppo_pair_layout.json"), "w") as f:
+        json.dump({"umax": UMAX, "rb": RB, "vtop": VTOP, "vacc": VACC, "vinf": VINF, "sbase": SBASE,
+                   "entries": {str(u): {str(w): entry_offset(offsets, u, w) for w in range(0, u + 1)} for u in range(1, UMAX + 1)},
+                   "end": offsets["end"]}, f)
+    print("wrote", path, "compute block", offsets["end"], "bytes")
+
+
+if __name__ == "__main__":
+    main()

@@ -52,6 +52,8 @@ inline hipError_t allow_full_lds(const void* kernel, std::atomic<uint64_t>& done
 //       for a = -1 .. QD-1, where QD = L/2+1 and codes outside 0..L-2 read as +inf
 //   d0  [k][wt_cols] u32   row 0 of the DP for first node j, two codes per dword: code of 0 at
 //       index i if 1 <= i <= L-k+1 and layers [0,i) fit node j, else +inf (index i = 2*col, 2*col+1)
+//   pt  [k][k-1][48] u32   for node j and DP row s = 1..k-1: where the paired kernel enters its code for each
+//       output of the row (see ppo_paired.hip)
 //   qv  [npairs][L-1] f32   the quotients themselves, each link's row in increasing order (between the two
 //       kernels that make the tables);  ord [L-1] u8  the layers in increasing order of t: entry r of a row
 //       of qv belongs to layer ord[r]
@@ -115,9 +117,13 @@ struct WinDesc {
     }
 };
 
+// Entry offsets of the paired enumeration kernel for one (node, DP row): where the chain of every output of
+// the row starts in that kernel's unrolled code, 16 bits each, outputs 2x+1 and 2x+2 in dword x.
+constexpr int kPairTableDwords = 48;
+
 struct Layout {
     int L, k, npairs, wt_cols, qa_cols;
-    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, d0_off, qv_off, ord_off, stride;  // bytes within one instance's slice
+    uint32_t lo_off, qc_off, dec_off, low_off, wt_off, qa_off, d0_off, qv_off, ord_off, pt_off, stride;  // bytes within one instance's slice
 
     __host__ __device__ static Layout make(int L, int k) {
         Layout y;
@@ -145,7 +151,9 @@ struct Layout {
         y.qv_off = (uint32_t)off;
         off = align_up(off + (size_t)y.npairs * (L > 1 ? L - 1 : 0) * 4, 16);
         y.ord_off = (uint32_t)off;
-        off = align_up(off + (size_t)L, 256);
+        off = align_up(off + (size_t)L, 64);
+        y.pt_off = (uint32_t)off;   // entry offsets of the paired kernel: [k][k-1][kPairTableDwords] u32
+        off = align_up(off + (size_t)k * (k > 1 ? k - 1 : 0) * kPairTableDwords * 4, 256);
         y.stride = (uint32_t)off;
         return y;
     }

@@ -368,6 +368,11 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
     }
 }
 
+bool paired_supported(int L, int k);
+hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream);
+hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
+                                   uint64_t* best_key, float* beta_export, hipStream_t stream);
+
 hipError_t launch_precompute(const float* t, const float* m, const float* M, const float* B, const Layout& y,
                              int n_inst, void* ws, hipStream_t stream) {
     hipLaunchKernelGGL(precompute_kernel, dim3(n_inst), dim3(kPreThreads), 0, stream, t, m, M, B, y,
@@ -377,7 +382,9 @@ hipError_t launch_precompute(const float* t, const float* m, const float* M, con
     const int ppb = kPreThreads / (y.L - 1);
     hipLaunchKernelGGL(codes_kernel, dim3((y.npairs + ppb - 1) / ppb, n_inst), dim3(kPreThreads), 0, stream, y,
                        static_cast<unsigned char*>(ws));
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_pair_tables(y, n_inst, ws, stream);
 }
 
 hipError_t launch_init_keys(uint64_t* keys, int n_inst, hipStream_t stream) {
@@ -404,7 +411,10 @@ hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_
                             hipStream_t stream) {
     const uint32_t span = rank_end - rank_begin;
     if (span == 0 || n_inst == 0) return hipSuccess;
-    if (g_enumeration_variant.load(std::memory_order_relaxed) == 0 && grouped_supported(y.L, y.k))
+    const int variant = g_enumeration_variant.load(std::memory_order_relaxed);
+    if (variant == PPO_ENUM_AUTO && !shared_prefix && paired_supported(y.L, y.k))
+        return launch_enumerate_paired(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, stream);
+    if ((variant == PPO_ENUM_AUTO || variant == PPO_ENUM_GROUPED) && grouped_supported(y.L, y.k))
         return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, shared_prefix,
                                         skipped_groups, stream);
     const size_t lds = enumerate_lds_bytes(y);

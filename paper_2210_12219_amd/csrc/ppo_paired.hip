@@ -1,0 +1,318 @@
+// Paired enumeration kernel for k >= 6: two orderings per lane, the DP row in registers.
+//
+// One workgroup of six waves evaluates the 720 orderings that share a prefix of k-6 nodes.  Every ordering runs
+// all of its k DP rows (the unit the headline figure counts).  Wave c holds, at every row, the orderings that
+// put the c-th of the six remaining nodes at that row: the memory window [lo[node][e], e-1] is then the same for
+// the whole wave, and since a lane's two orderings (one per 16-bit half of its registers) are chosen to share
+// that node as well, every instruction works on both halves alike: one packed three-input minimum folds two
+// candidates into two orderings at once, with no masks and no per-lane control.
+//
+// Row convention.  Entry u of a row (1 <= u <= NE-1, NE = L-k+2) stands for the segment end e = u + s of DP
+// row s.  A lane keeps entry u in register v[PPO_PAIR_RB + u].  Before row s is computed the registers hold
+//     g_s[i] = max(D_{s-1}[i], q_{pi_{s-1},pi_s}[i-1])       at u = i - s + 1
+// and D_s[e] = min over i in [max(lo[pi_s][e], s), e-1] of g_s[i] is the minimum of the w = e - max(lo, s)
+// entries u, u-1, .., u-w+1 with u = e - s; it replaces entry u in place (the outputs are worked from the
+// highest u down).  The chains that do this are generated code entered by computed jumps (ppo_pair_asm.h);
+// the jump targets of a (node, row) come from a table written by pair_tables_kernel below.
+//
+// Which orderings a lane holds changes from row to row (the node at the row must be the wave's), so between
+// rows the entries go through LDS: slot = pair, one dword per entry, entry-major, the bank of a slot being its
+// coset class (ppo_pair_tables.h), conflict free by construction.  The rows of the shared prefix and the first
+// row after it need no exchange: all orderings of a lane set keep their node there.  The pairing changes once,
+// before the row of position 4 of the six: only upper halves move (see gen_pair_tables.py).
+#include "ppo_common.h"
+#include "ppo_pair_asm.h"
+#include "ppo_pair_tables.h"
+
+namespace ppo {
+
+constexpr int kPairWaves = 6;
+constexpr int kPairThreads = kPairWaves * 64;
+constexpr int kPairSlots = 384;   // 12 indices x 32 banks; banks 30 and 31 hold the spare slots
+
+struct PairedShape {
+    int NE, QD, QROW, QPITCH, nA, nB, nQ;
+    uint32_t q_off, total_bytes;   // q_off in dwords
+    __host__ __device__ static PairedShape make(int L, int k) {
+        PairedShape g;
+        g.NE = L - k + 2;
+        g.QD = L / 2 + 1;
+        g.QROW = 2 * g.QD + 2;
+        g.QPITCH = g.QROW | 1;
+        const int p0 = k - 6;
+        g.nA = p0 > 1 ? p0 - 1 : 0;
+        g.nB = p0 > 0 ? 6 : 0;
+        g.nQ = g.nA + g.nB + 15;
+        g.q_off = (uint32_t)(g.NE - 1) * kPairSlots;
+        // 64 dwords behind the table: the quotient reads of a row always take 48 dwords from their first column
+        g.total_bytes = (g.q_off + (uint32_t)(g.nQ * g.QPITCH) + 64u) * 4u;
+        return g;
+    }
+};
+
+bool paired_supported(int L, int k) {
+    if (k < 6) return false;
+    const PairedShape g = PairedShape::make(L, k);
+    return g.NE - 1 <= PPO_PAIR_UMAX && g.total_bytes <= (uint32_t)kLdsBytesPerCU;
+}
+
+// spare slot that holds the first DP row of node j (both halves the same), and the spare slots of the idle lanes
+__host__ __device__ inline uint32_t pair_d0_slot(int j) { return (uint32_t)(2 + j / 2) * 32u + 30u + (uint32_t)(j & 1); }
+
+// ---------------------------------------------------------------------------------------------
+// Entry offsets: for node j and DP row s = 1..k-1, where the chain of each output starts.  Row k-1 needs
+// D[L] only: its highest output is computed and the one below it is sent to the end of the block.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline uint32_t pair_row_offset(int L, int k, int s, uint32_t u, uint32_t lo_e) {
+    const uint32_t top = (uint32_t)(L - k + 1);   // highest output index, NE - 1
+    if (u > top) return kPairEnd;
+    if (s == k - 1 && u != top) return kPairEnd;
+    const uint32_t e = u + (uint32_t)s;
+    const uint32_t first = lo_e > (uint32_t)s ? lo_e : (uint32_t)s;
+    const uint32_t w = e > first ? e - first : 0u;   // e - s = u bounds it
+    return pair_entry_offset(u, w);
+}
+
+__global__ __launch_bounds__(256) void pair_tables_kernel(Layout y, unsigned char* __restrict__ ws) {
+    const int L = y.L, k = y.k, inst = blockIdx.x;
+    unsigned char* base = ws + (size_t)inst * y.stride;
+    const unsigned char* lo = base + y.lo_off;
+    uint32_t* pt = reinterpret_cast<uint32_t*>(base + y.pt_off);
+    const int total = k * (k - 1) * kPairTableDwords;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+        const int x = idx % kPairTableDwords, s = (idx / kPairTableDwords) % (k - 1) + 1, j = idx / (kPairTableDwords * (k - 1));
+        uint32_t v = 0;
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t u = (uint32_t)(2 * x + 1 + h);
+            const uint32_t e = u + (uint32_t)s;
+            const uint32_t lo_e = e <= (uint32_t)L ? lo[j * (L + 1) + e] : 0u;
+            v |= pair_row_offset(L, k, s, u, lo_e) << (16 * h);
+        }
+        pt[idx] = v;
+    }
+}
+
+hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream) {
+    if (y.k < 2) return hipSuccess;
+    hipLaunchKernelGGL(pair_tables_kernel, dim3(n_inst), dim3(256), 0, stream, y, static_cast<unsigned char*>(ws));
+    return hipGetLastError();
+}
+
+typedef __attribute__((address_space(3))) uint32_t pair_lds_u32_t;
+__device__ __forceinline__ uint32_t pair_lds_addr(const uint32_t* p) { return (uint32_t)(uintptr_t)(const pair_lds_u32_t*)p; }
+
+// The row steps.  Every block works on fixed registers (the row in v[PPO_PAIR_RB + 1 ..], see the generator) that
+// are declared clobbered here; the values live in them from one block to the next, and the build step checks in
+// the compiled code that nothing between the blocks touches them.
+#define PPO_PAIR_CLOBBERS PPO_PAIR_CLOBBER_V, PPO_PAIR_CLOBBER_S, "memory"
+__device__ __forceinline__ void pair_load(uint32_t addr, uint32_t skip) {
+    asm volatile(PPO_PAIR_LOAD_ASM : : [addr] "v"(addr), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+}
+__device__ __forceinline__ void pair_load_exchange(uint32_t addr, uint32_t addr2, uint32_t skip) {
+    asm volatile(PPO_PAIR_LOADX_ASM : : [addr] "v"(addr), [addr2] "v"(addr2), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+}
+__device__ __forceinline__ void pair_store(uint32_t addr, uint32_t skip) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n" PPO_PAIR_STORE_ASM : : [addr] "v"(addr), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+}
+__device__ __forceinline__ void pair_qmax(uint32_t qaddr) {
+    asm volatile(PPO_PAIR_QMAX_ASM : : [qaddr] "v"(qaddr) : PPO_PAIR_CLOBBERS);
+}
+__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip) {
+    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+}
+__device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
+    uint32_t res;
+    asm volatile("s_waitcnt lgkmcnt(0)\n" PPO_PAIR_EXTRACT_ASM : [res] "=v"(res) : [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+    return res;
+}
+
+// beta_export: null for the search; else beta of every ordering of the range is written out as well (one kernel
+// for both: a second instantiation would be a second copy of the generated code)
+__global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
+    Layout y, const unsigned char* __restrict__ ws, uint32_t rank_begin, uint32_t rank_end, uint32_t prefix_begin,
+    uint32_t prefix_end, uint32_t prefixes_per_block, unsigned long long* __restrict__ best_key,
+    float* __restrict__ beta_export) {
+    extern __shared__ __align__(16) uint32_t lds[];
+    const bool EXPORT = beta_export != nullptr;
+    const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = k - 6;
+    const PairedShape ps = PairedShape::make(L, k);
+    const int NE = ps.NE, QD = ps.QD, QROW = ps.QROW, QPITCH = ps.QPITCH, nA = ps.nA, nB = ps.nB;
+    const uint32_t skip = (uint32_t)__builtin_amdgcn_readfirstlane(PPO_PAIR_UMAX - (NE - 1));
+
+    const unsigned char* base = ws + (size_t)inst * y.stride;
+    const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
+    const uint32_t* __restrict__ qa = reinterpret_cast<const uint32_t*>(base + y.qa_off);
+    const uint32_t* __restrict__ pt = reinterpret_cast<const uint32_t*>(base + y.pt_off);
+    uint32_t* const qtab = lds + ps.q_off;
+    const uint32_t buf_addr = pair_lds_addr(lds), qtab_addr = pair_lds_addr(qtab);
+
+    // the lane's schedule: which pair it holds at the row of each of the six positions
+    const uint32_t lc0 = kPairLane[wave][lane][0], lc1 = kPairLane[wave][lane][1], lc2 = kPairLane[wave][lane][2],
+                   lc3 = kPairLane[wave][lane][3];
+    auto slot_addr = [&](int r) -> uint32_t {
+        const uint32_t s = ((r < 3 ? lc0 >> (9 * r) : lc1 >> (9 * (r - 3))) & 511u);
+        return buf_addr + s * 4u;
+    };
+    // first DP rows of all nodes into their spare slots, and +inf into the spare slots of the idle lanes
+    {
+        const uint32_t* d0src = reinterpret_cast<const uint32_t*>(base + y.d0_off);
+        for (int idx = tid; idx < k * (NE - 1); idx += kPairThreads) {
+            const int j = idx / (NE - 1), u = idx - j * (NE - 1) + 1;
+            const uint32_t c = (d0src[j * y.wt_cols + (u >> 1)] >> (16 * (u & 1))) & 0xFFFFu;
+            lds[(u - 1) * kPairSlots + pair_d0_slot(j)] = c | (c << 16);
+        }
+        for (int idx = tid; idx < 4 * (NE - 1); idx += kPairThreads) {
+            const int n = idx & 3, u = (idx >> 2) + 1;
+            lds[(u - 1) * kPairSlots + 30 + (n & 1) + 32 * (n >> 1)] = kCodeInf | (kCodeInf << 16);
+        }
+    }
+    unsigned long long best = PPO_KEY_NONE;
+
+    // prefix of a group from the Lehmer digits of its index (weights (k-1-p)!/6!); `avail` ends up holding the
+    // six remaining nodes in ascending order, four bits each
+    auto decode_group = [&](uint32_t pr, uint64_t& prefix_out, uint64_t& avail_out) {
+        uint64_t avail_ = 0xBA9876543210ull, prefix_ = 0;
+        uint32_t digits = 0, rem = pr;
+#pragma unroll
+        for (int q = 0; q < PPO_MAX_K - 6; ++q) {
+            if (q < p0) {
+                const uint32_t b = 7u + (uint32_t)q;
+                const uint32_t next = rem / b;
+                digits |= (rem - next * b) << (4 * (p0 - 1 - q));
+                rem = next;
+            }
+        }
+        for (int p = 0; p < p0; ++p) {
+            const uint32_t d = (digits >> (4 * p)) & 15u;
+            const uint32_t sh = 4u * d;
+            const uint64_t node = (avail_ >> sh) & 0xFull;
+            const uint64_t lowbits = avail_ & ((1ull << sh) - 1ull);
+            avail_ = lowbits | ((avail_ >> 4) & ~((1ull << sh) - 1ull));
+            prefix_ |= node << (4 * p);
+        }
+        prefix_out = prefix_;
+        avail_out = avail_;
+    };
+    auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
+
+    const uint32_t prefix_first = prefix_begin + blockIdx.x * prefixes_per_block;
+    for (uint32_t gi = 0; gi < prefixes_per_block; ++gi) {
+        const uint32_t pr = prefix_first + gi;
+        if (pr >= prefix_end) break;
+        uint64_t prefix, avail;
+        decode_group(pr, prefix, avail);
+        auto pnode = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
+        auto rnode = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
+        __syncthreads();   // the previous group is done with the quotient rows and with the row buffer
+        // quotient rows of the links this group can cross: wave w stages rows w, w+6, ...
+        for (int row = wave; row < ps.nQ; row += kPairWaves) {
+            int a, b;
+            if (row < nA) {
+                a = pnode(row); b = pnode(row + 1);
+            } else if (row < nA + nB) {
+                a = pnode(p0 - 1); b = rnode(row - nA);
+            } else {
+                int pi = row - nA - nB, ca = 0;
+                while (pi >= 5 - ca) { pi -= 5 - ca; ++ca; }
+                a = rnode(ca); b = rnode(ca + 1 + pi);
+            }
+            const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
+            for (int col = lane; col < QROW; col += 64) qtab[row * QPITCH + col] = qsrc[col];
+        }
+        __syncthreads();
+
+        // The k rows in turn.  Rows 0 .. p0 stay in registers (the node of each is the same for all orderings of
+        // the wave whatever the lane holds); from the row of position 1 on, a row is loaded from the slots its
+        // lanes hold now, and every row but the last is stored for the next one.  One copy of each block: the
+        // generated code is large, and its labels are not unique on purpose (a second copy would not assemble).
+        const uint32_t d0_addr = buf_addr + pair_d0_slot(p0 > 0 ? pnode(0) : rnode(wave)) * 4u;
+#pragma unroll 1
+        for (int s = 0; s < k; ++s) {
+            const int r = s - p0;
+            if (s == 0 || r >= 1) {
+                const uint32_t a = s == 0 ? d0_addr : slot_addr(r);
+                if (r == 4) {
+                    pair_load_exchange(a, buf_addr + (lc2 & 511u) * 4u, skip);
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __syncthreads();   // every upper half has been fetched before a slot is overwritten
+                } else {
+                    pair_load(a, skip);
+                }
+            }
+            if (s >= 1) {
+                // the link between the nodes of rows s-1 and s, and the node of row s
+                uint32_t qrow;
+                int node;
+                if (s < p0) {
+                    qrow = (uint32_t)(s - 1);
+                    node = pnode(s);
+                } else if (s == p0) {
+                    qrow = (uint32_t)(nA + wave);
+                    node = rnode(wave);
+                } else {
+                    qrow = (uint32_t)(nA + nB) + ((lc2 >> (9 + 4 * (r - 1))) & 15u);
+                    node = rnode(wave);
+                }
+                pair_qmax(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u);
+                const uint32_t* desc = pt + (uint32_t)__builtin_amdgcn_readfirstlane((node * (k - 1) + (s - 1)) * kPairTableDwords);
+                pair_compute(desc, skip);
+            }
+            if (r >= 0 && s < k - 1) {
+                pair_store(slot_addr(r), skip);
+                __syncthreads();
+            }
+        }
+        const uint32_t res = pair_extract(skip);   // D[L] of the lane's two orderings
+        if (lc3 >> 31) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t code = (res >> (16 * h)) & 0xFFFFu;
+                const uint32_t r = pr * 720u + ((lc3 >> (10 * h)) & 1023u);
+                if (r >= rank_begin && r < rank_end) {
+                    if (EXPORT) {
+                        const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+                        beta_export[r - rank_begin] = __uint_as_float(bits);
+                    }
+                    const unsigned long long key = ((unsigned long long)code << 32) | r;
+                    best = key < best ? key : best;
+                }
+            }
+        }
+    }
+
+    if (!EXPORT) {
+        for (int off = 32; off >= 1; off >>= 1) {
+            const unsigned long long o = __shfl_xor(best, off, 64);
+            best = o < best ? o : best;
+        }
+        if (lane == 0 && best != PPO_KEY_NONE) {
+            const uint32_t code = (uint32_t)(best >> 32);
+            const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+            const unsigned long long key = ((unsigned long long)bits << 32) | (best & 0xFFFFFFFFull);
+            if (key < best_key[inst]) atomicMin(best_key + inst, key);
+        }
+    }
+}
+
+hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
+                                   uint64_t* best_key, float* beta_export, hipStream_t stream) {
+    if (rank_end <= rank_begin || n_inst == 0) return hipSuccess;
+    const PairedShape ps = PairedShape::make(y.L, y.k);
+    const uint32_t pbeg = rank_begin / 720u, pend = (rank_end + 719u) / 720u;
+    const uint32_t count = pend - pbeg;
+    // groups per workgroup: as many as 8, fewer where the grid would fall under a few thousand workgroups
+    uint32_t ppb = 8;
+    while (ppb > 1 && (uint64_t)(count / ppb) * (uint64_t)n_inst < 4096u) ppb >>= 1;
+    const dim3 grid((count + ppb - 1) / ppb, n_inst);
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_paired_kernel), lds_allowed);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(enumerate_paired_kernel, grid, dim3(kPairThreads), ps.total_bytes, stream, y,
+                       static_cast<const unsigned char*>(ws), rank_begin, rank_end, pbeg, pend, ppb,
+                       reinterpret_cast<unsigned long long*>(best_key), beta_export);
+    return hipGetLastError();
+}
+
+}  // namespace ppo

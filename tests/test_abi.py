@@ -78,7 +78,7 @@ def test_bad_arguments_are_refused_without_a_gpu(lib):
     assert lib.ppo_solve_static(p, p, 100, p, p, 13, 1, p, p, p, s) == binding.PPO_ETOOBIG
     assert lib.ppo_solve_static(null, p, 4, p, p, 2, 1, p, p, p, s) == binding.PPO_EINVAL
     assert lib.ppo_solve_static(null, null, 4, null, null, 2, 0, null, null, null, s) == binding.PPO_OK
-    assert binding.ppo_workspace_bytes(100, 10, 127) <= binding.PPO_STATIC_SCRATCH_BYTES < binding.ppo_workspace_bytes(100, 10, 128)
+    assert binding.ppo_workspace_bytes(100, 10, 112) <= binding.PPO_STATIC_SCRATCH_BYTES < binding.ppo_workspace_bytes(100, 10, 113)
     assert lib.ppo_solve_static(p, p, 100, p, p, 10, 128, p, p, p, s) == binding.PPO_ENOSPC
     # rank ranges
     assert lib.ppo_solve_range(4, 3, 1, p, 1 << 20, 5, 4, p, s) == binding.PPO_EINVAL

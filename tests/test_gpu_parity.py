@@ -349,6 +349,31 @@ def test_grouped_kernel_row_lengths(ppo):
         assert_same(gpu_solve(ppo, w), O.subset_dp(w.t, w.m, w.M, w.B), f"grouped row lengths k={k} L={L}")
 
 
+def test_grouped_kernel_behind_the_switch(ppo):
+    """The grouped kernel (one ordering per lane, rows in LDS) is what the bounded search runs and what
+    PPO_ENUM_GROUPED selects: with the switch set, the headline keys, row lengths at its part boundaries, k = 12 and
+    per-ordering values, against the oracle."""
+    import torch
+    ppo.ppo_set_enumeration(ppo.PPO_ENUM_GROUPED)
+    try:
+        w = W.headline()
+        assert_same(gpu_solve(ppo, w), O.subset_dp(w.t, w.m, w.M, w.B), "headline, grouped kernel")
+        sampled_orderings_match(ppo, w, [5], 2, 3000, seed=7)
+        for n, (k, L) in enumerate([(6, 6), (6, 28), (6, 29), (6, 53), (6, 77), (6, 100), (7, 54), (9, 57), (9, 103)]):
+            w = W.random_instances(7100 + n, 4, L, k, capacity_factor=1.15 + 0.1 * (n % 4), quantised=bool(n % 3 == 0))
+            assert_same(gpu_solve(ppo, w), O.subset_dp(w.t, w.m, w.M, w.B), f"grouped kernel k={k} L={L}")
+        kf = math.factorial(12)
+        w = W.random_instances(1299, 1, 40, 12, capacity_factor=1.4)
+        dev = ppo.to_device(w)
+        r0, r1 = kf - 9000, kf
+        got = ppo.ppo_eval_orderings(dev[0][0], dev[1][0], dev[2][0], dev[3][0], r0, r1)
+        torch.cuda.synchronize()
+        per, _ = O.eval_orderings(w.t[0], w.m[0], w.M[0], w.B[0], r0, r1)
+        assert np.array_equal(bits(got.cpu().numpy()), bits(per))
+    finally:
+        ppo.ppo_set_enumeration(ppo.PPO_ENUM_AUTO)
+
+
 def test_issue_probe_runs(ppo):
     """The measurement aid launches and keeps its work: every lane writes the sum of its four accumulators."""
     import torch

@@ -35,7 +35,7 @@ def test_static_scratch_entry_point_matches_ppo_solve():
         assert np.isfinite(ref[0].cpu().numpy()).any()
     # a batch beyond the array is refused, and nothing is written
     w = W.headline()
-    n_over = 128
+    n_over = 113
     assert ppo.ppo_workspace_bytes(w.L, w.k, n_over) > ppo.PPO_STATIC_SCRATCH_BYTES
     p = C.c_void_p(0x1000)
     assert lib.ppo_solve_static(p, p, w.L, p, p, w.k, n_over, p, p, p, stream) == ppo.PPO_ENOSPC
