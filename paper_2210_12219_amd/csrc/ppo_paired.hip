@@ -26,13 +26,14 @@
 
 namespace ppo {
 
-constexpr int kPairWaves = 6;
-constexpr int kPairThreads = kPairWaves * 64;
+constexpr int kPairWaves = 6;                    // waves of a team: one per node that can sit at a row
+constexpr int kPairTeams = 2;                    // two teams per workgroup, each on a group of its own
+constexpr int kPairThreads = kPairTeams * kPairWaves * 64;
 constexpr int kPairSlots = 384;   // 12 indices x 32 banks; banks 30 and 31 hold the spare slots
 
 struct PairedShape {
     int NE, QD, QROW, QPITCH, nA, nB, nQ;
-    uint32_t q_off, total_bytes;   // q_off in dwords
+    uint32_t q_off, q_dwords, sync_off, total_bytes;   // offsets in dwords
     __host__ __device__ static PairedShape make(int L, int k) {
         PairedShape g;
         g.NE = L - k + 2;
@@ -44,8 +45,10 @@ struct PairedShape {
         g.nB = p0 > 0 ? 6 : 0;
         g.nQ = g.nA + g.nB + 15;
         g.q_off = (uint32_t)(g.NE - 1) * kPairSlots;
-        // 64 dwords behind the table: the quotient reads of a row always take 48 dwords from their first column
-        g.total_bytes = (g.q_off + (uint32_t)(g.nQ * g.QPITCH) + 64u) * 4u;
+        g.q_dwords = (uint32_t)(g.nQ * g.QPITCH);          // one quotient table per team
+        g.sync_off = g.q_off + kPairTeams * g.q_dwords;    // then the counters the teams synchronise with
+        // 64 dwords behind the tables: the quotient reads of a row always take 48 dwords from their first column
+        g.total_bytes = (g.sync_off + 64u) * 4u;
         return g;
     }
 };
@@ -126,6 +129,24 @@ __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
     return res;
 }
 
+// Synchronisation of the two teams.  A team (six waves) works on one group; its rows 0 .. p0 need no LDS, its
+// later rows go through the one row buffer of the workgroup.  The teams take turns at the buffer: while one
+// exchanges rows, the other computes the register-only rows of its next group, so that every SIMD has waves of
+// both kinds to issue from.  Waves of a team meet at a counter in LDS (the hardware barrier would stop the other
+// team as well); the buffer passes to the next group when every wave of the group before it has fetched its last
+// row.  All counters only grow; a wave compares them with counts of its own.
+struct PairSync {
+    uint32_t team[kPairTeams];   // waves of the team that have reached their n-th meeting, summed over n
+    uint32_t done;               // waves that are through with the row buffer, summed over the groups in turn
+};
+__device__ __forceinline__ void pair_spin_until(volatile uint32_t* counter, uint32_t target) {
+    while (__hip_atomic_load(const_cast<uint32_t*>(counter), __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
+        __builtin_amdgcn_s_sleep(1);
+}
+__device__ __forceinline__ void pair_arrive(uint32_t* counter) {
+    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // beta_export: null for the search; else beta of every ordering of the range is written out as well (one kernel
 // for both: a second instantiation would be a second copy of the generated code)
 __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
@@ -135,7 +156,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     extern __shared__ __align__(16) uint32_t lds[];
     const bool EXPORT = beta_export != nullptr;
     const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = wave_id / kPairWaves, wave = wave_id - team * kPairWaves;
     const int p0 = k - 6;
     const PairedShape ps = PairedShape::make(L, k);
     const int NE = ps.NE, QD = ps.QD, QROW = ps.QROW, QPITCH = ps.QPITCH, nA = ps.nA, nB = ps.nB;
@@ -145,7 +167,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
     const uint32_t* __restrict__ qa = reinterpret_cast<const uint32_t*>(base + y.qa_off);
     const uint32_t* __restrict__ pt = reinterpret_cast<const uint32_t*>(base + y.pt_off);
-    uint32_t* const qtab = lds + ps.q_off;
+    uint32_t* const qtab = lds + ps.q_off + (uint32_t)team * ps.q_dwords;
+    PairSync* const sync = reinterpret_cast<PairSync*>(lds + ps.sync_off);
     const uint32_t buf_addr = pair_lds_addr(lds), qtab_addr = pair_lds_addr(qtab);
 
     // the lane's schedule: which pair it holds at the row of each of the six positions
@@ -167,8 +190,17 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
             const int n = idx & 3, u = (idx >> 2) + 1;
             lds[(u - 1) * kPairSlots + 30 + (n & 1) + 32 * (n >> 1)] = kCodeInf | (kCodeInf << 16);
         }
+        if (tid < (int)(sizeof(PairSync) / 4)) lds[ps.sync_off + tid] = 0u;
     }
+    __syncthreads();   // the only hardware barrier: from here on the teams run on their own
     unsigned long long best = PPO_KEY_NONE;
+    uint32_t meetings = 0;   // meetings of this wave's team so far
+    auto team_meet = [&]() {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        pair_arrive(&sync->team[team]);
+        ++meetings;
+        pair_spin_until(&sync->team[team], meetings * (uint32_t)kPairWaves);
+    };
 
     // prefix of a group from the Lehmer digits of its index (weights (k-1-p)!/6!); `avail` ends up holding the
     // six remaining nodes in ascending order, four bits each
@@ -197,15 +229,16 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     };
     auto link_col = [&](int s) -> int { return (s & 1) ? (s - 1) / 2 : QD + s / 2; };
 
+    // the groups of this workgroup in turn, even ones to team 0, odd ones to team 1
     const uint32_t prefix_first = prefix_begin + blockIdx.x * prefixes_per_block;
-    for (uint32_t gi = 0; gi < prefixes_per_block; ++gi) {
+    for (uint32_t gi = (uint32_t)team; gi < prefixes_per_block; gi += kPairTeams) {
         const uint32_t pr = prefix_first + gi;
         if (pr >= prefix_end) break;
         uint64_t prefix, avail;
         decode_group(pr, prefix, avail);
         auto pnode = [=](int p) { return (int)((prefix >> (4 * p)) & 0xFull); };
         auto rnode = [=](int c) { return (int)((avail >> (4 * c)) & 0xFull); };
-        __syncthreads();   // the previous group is done with the quotient rows and with the row buffer
+        team_meet();   // the team is done with the quotient rows of its previous group
         // quotient rows of the links this group can cross: wave w stages rows w, w+6, ...
         for (int row = wave; row < ps.nQ; row += kPairWaves) {
             int a, b;
@@ -221,7 +254,7 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
             const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
             for (int col = lane; col < QROW; col += 64) qtab[row * QPITCH + col] = qsrc[col];
         }
-        __syncthreads();
+        team_meet();
 
         // The k rows in turn.  Rows 0 .. p0 stay in registers (the node of each is the same for all orderings of
         // the wave whatever the lane holds); from the row of position 1 on, a row is loaded from the slots its
@@ -235,8 +268,7 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 const uint32_t a = s == 0 ? d0_addr : slot_addr(r);
                 if (r == 4) {
                     pair_load_exchange(a, buf_addr + (lc2 & 511u) * 4u, skip);
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    __syncthreads();   // every upper half has been fetched before a slot is overwritten
+                    team_meet();   // every upper half has been fetched before a slot is overwritten
                 } else {
                     pair_load(a, skip);
                 }
@@ -256,12 +288,15 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                     node = rnode(wave);
                 }
                 pair_qmax(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u);
+                if (s == k - 1) pair_arrive(&sync->done);   // the last row is in registers: the buffer can go on
                 const uint32_t* desc = pt + (uint32_t)__builtin_amdgcn_readfirstlane((node * (k - 1) + (s - 1)) * kPairTableDwords);
                 pair_compute(desc, skip);
             }
             if (r >= 0 && s < k - 1) {
+                // the first store of a group waits for the buffer: every wave of the group before it has fetched its last row
+                if (r == 0) pair_spin_until(&sync->done, gi * (uint32_t)kPairWaves);
                 pair_store(slot_addr(r), skip);
-                __syncthreads();
+                team_meet();
             }
         }
         const uint32_t res = pair_extract(skip);   // D[L] of the lane's two orderings
@@ -302,9 +337,10 @@ hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, 
     const PairedShape ps = PairedShape::make(y.L, y.k);
     const uint32_t pbeg = rank_begin / 720u, pend = (rank_end + 719u) / 720u;
     const uint32_t count = pend - pbeg;
-    // groups per workgroup: as many as 8, fewer where the grid would fall under a few thousand workgroups
-    uint32_t ppb = 8;
-    while (ppb > 1 && (uint64_t)(count / ppb) * (uint64_t)n_inst < 4096u) ppb >>= 1;
+    // groups per workgroup (its two teams take them in turn): as many as 16, fewer where the grid would fall
+    // under a few thousand workgroups, never fewer than two
+    uint32_t ppb = 16;
+    while (ppb > 2 && (uint64_t)(count / ppb) * (uint64_t)n_inst < 4096u) ppb >>= 1;
     const dim3 grid((count + ppb - 1) / ppb, n_inst);
     static std::atomic<uint64_t> lds_allowed{0};
     const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_paired_kernel), lds_allowed);
