@@ -230,6 +230,45 @@ int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, con
 int ppo_min_sum_partition(const float *t, const float *m, int L, const float *kappa, int n_inst, int32_t *segs_out,
                           int32_t *cuts_out, double *sum_out, void *stream);
 
+/* The paper's own placement algorithm (Sec. III-B2), for scoring against the exact optimum of ppo_solve_cluster:
+ * cuts by the partitioning step above (Alg. 1, capacity kappa: the paper's nodes are alike in memory); the
+ * transfer sizes at the cuts sorted into n_classes classes (Eq. 5); classes matched from the highest down, within
+ * a class the runs of consecutive cuts from the longest down (Alg. 3); a run of r cuts gets the path of r + 1
+ * unused nodes whose weakest link is strongest, between the ends that neighbouring runs have fixed: bisection
+ * over the descending list of bandwidths for the highest threshold whose graph of links at or above it (Eq. 8)
+ * holds such a path (Alg. 2).  Readings where the paper is open: classes are bins of equal width between the
+ * least and the greatest of t[0 .. L-2]; the path search (colour coding in the paper) is depth first in
+ * increasing node order, returns the smallest node sequence, and gives up after 20,000 nodes put on the path; a
+ * run both of whose ends are fixed and adjacent is matched already; if a run cannot be matched, the matching
+ * starts again with one class fewer.
+ *   t, m [n_inst][L]   kappa [n_inst]   B [n_inst][n][n]      1 <= n <= PPO_HEURISTIC_MAX_N, L <= PPO_MAX_L
+ *   beta_out    [n_inst]        Eq. 2 of the placement found; +inf if the chain cannot be partitioned or needs
+ *                               more partitions than there are nodes
+ *   segs_out    [n_inst]        number of partitions p; 0 if none
+ *   cuts_out    [n_inst][L-1]   c_1..c_{p-1}, then -1 (may be NULL when L = 1)
+ *   order_out   [n_inst][n]     node of every partition, then -1
+ *   classes_out [n_inst]        classes the matching succeeded with; may be NULL
+ * Allocates n_inst doubles of scratch with the stream-ordered allocator. */
+#define PPO_HEURISTIC_MAX_N 64
+int ppo_place_kpath(const float *t, const float *m, int L, const float *kappa, const float *B, int n, int n_inst,
+                    int n_classes, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,
+                    int32_t *classes_out, void *stream);
+
+/* The two systems the paper compares its algorithm with (Sec. IV).
+ *   PPO_BASELINE_JOINT   partitions: from the current layer on, the fitting end with the smallest transfer size
+ *                        (the rest of the chain as soon as it fits); nodes: from a start node always on over the
+ *                        best link to an unused node; the start node with the least bottleneck.  Ties go to the
+ *                        smaller index.
+ *   PPO_BASELINE_RANDOM  again and again a random unused node and a random number of layers among those that fit
+ *                        it.  The random numbers are an input: draws [n_inst][n_draws], values in [0, 1), two per
+ *                        partition (value x picks item floor(x * count)); +inf if they or the nodes run out.
+ * Outputs as for ppo_place_kpath. */
+#define PPO_BASELINE_JOINT 1
+#define PPO_BASELINE_RANDOM 2
+int ppo_place_baseline(const float *t, const float *m, int L, const float *kappa, const float *B, int n, int n_inst,
+                       int kind, const float *draws, int n_draws, float *beta_out, int32_t *segs_out,
+                       int32_t *cuts_out, int32_t *order_out, void *stream);
+
 /* From a model's layer graph to the chain (paper Sec. III-A).  HOST routine: every pointer is a host pointer,
  * nothing is enqueued on the GPU.
  *   n_vertices layers, n_edges data dependencies edge_src[e] -> edge_dst[e] (a DAG with exactly one vertex

@@ -61,6 +61,8 @@ def load() -> C.CDLL:
         lib.ppo_eval_orderings_ct.argtypes = inst_ct + [u64, u64, vp, vp]
         lib.ppo_chain_from_dag.argtypes = [i, i, vp, vp, vp, vp, i, vp, vp, vp, vp]
         lib.ppo_min_sum_partition.argtypes = [vp, vp, i, vp, i, vp, vp, vp, vp]
+        lib.ppo_place_kpath.argtypes = [vp, vp, i, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp]
+        lib.ppo_place_baseline.argtypes = [vp, vp, i, vp, vp, i, i, i, vp, i, vp, vp, vp, vp, vp]
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_cluster_workspace_bytes.restype = sz
         lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
@@ -271,6 +273,44 @@ def ppo_min_sum_partition(t, m, kappa, stream=None):
                                         C.c_void_p(segs.data_ptr()), C.c_void_p(cuts.data_ptr()),
                                         C.c_void_p(total.data_ptr()), _stream(stream)))
     return segs, cuts, total
+
+
+PPO_BASELINE_JOINT, PPO_BASELINE_RANDOM = 1, 2
+PPO_HEURISTIC_MAX_N = 64
+
+
+def _place_outputs(torch, n_inst, L, n, device):
+    return (torch.empty(n_inst, dtype=torch.float32, device=device), torch.empty(n_inst, dtype=torch.int32, device=device),
+            torch.empty((n_inst, max(L - 1, 0)), dtype=torch.int32, device=device),
+            torch.empty((n_inst, n), dtype=torch.int32, device=device))
+
+
+def ppo_place_kpath(t, m, kappa, B, n_classes, stream=None):
+    """The paper's placement algorithm: (beta [n], segs [n], cuts [n, L-1], order [n, nodes], classes used [n])."""
+    torch = _torch()
+    n_inst, L = t.shape
+    n = B.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    beta, segs, cuts, order = _place_outputs(torch, n_inst, L, n, t.device)
+    used = torch.empty(n_inst, dtype=i32, device=t.device)
+    _check(load().ppo_place_kpath(_dev(t, f32), _dev(m, f32), L, _dev(kappa, f32), _dev(B, f32), n, n_inst, int(n_classes),
+                                  _dev(beta, f32), _dev(segs, i32), C.c_void_p(cuts.data_ptr()), _dev(order, i32),
+                                  _dev(used, i32), _stream(stream)))
+    return beta, segs, cuts, order, used
+
+
+def ppo_place_baseline(t, m, kappa, B, kind, draws=None, stream=None):
+    """The paper's comparison systems: (beta, segs, cuts, order); draws [n, n_draws] for the random one."""
+    torch = _torch()
+    n_inst, L = t.shape
+    n = B.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    beta, segs, cuts, order = _place_outputs(torch, n_inst, L, n, t.device)
+    n_draws = 0 if draws is None else draws.shape[1]
+    _check(load().ppo_place_baseline(_dev(t, f32), _dev(m, f32), L, _dev(kappa, f32), _dev(B, f32), n, n_inst, int(kind),
+                                     None if draws is None else _dev(draws, f32), n_draws, _dev(beta, f32), _dev(segs, i32),
+                                     C.c_void_p(cuts.data_ptr()), _dev(order, i32), _stream(stream)))
+    return beta, segs, cuts, order
 
 
 def ppo_chain_from_dag(n_vertices, edges, weight, out_size):

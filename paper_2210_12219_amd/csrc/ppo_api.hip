@@ -23,6 +23,8 @@ hipError_t launch_cluster_tables_from_prepared(const Layout&, const void*, int, 
 hipError_t launch_min_sum_partition(const float*, const float*, int, const float*, int, int32_t*, int32_t*, double*,
                                     hipStream_t);
 hipError_t launch_valu_probe(int, int, uint32_t*, hipStream_t);
+hipError_t launch_heuristic(const float*, const float*, int, const float*, const float*, int, int, int, int, const float*,
+                            int, const int32_t*, const int32_t*, float*, int32_t*, int32_t*, int32_t*, int32_t*, hipStream_t);
 size_t ct_tables_bytes(int L, int k);
 hipError_t launch_ct_tables(const float*, const float*, const float*, const float*, const float*, const float*, int, int,
                             int, void*, hipStream_t);
@@ -429,6 +431,61 @@ int ppo_eval_orderings_ct(const float* t, const float* m, const float* w, int L,
     const hipError_t e2 = hipFreeAsync(ws, s);
     PPO_HIP(e, "compute-term per-ordering launch");
     PPO_HIP(e2, "hipFreeAsync (compute-term tables)");
+    return PPO_OK;
+}
+
+static int check_place_shape(int L, int n, int n_inst) {
+    if (L < 1 || n < 1 || n_inst < 0) return PPO_EINVAL;
+    if (L > PPO_MAX_L || n > PPO_HEURISTIC_MAX_N) return PPO_ETOOBIG;
+    return PPO_OK;
+}
+
+int ppo_place_kpath(const float* t, const float* m, int L, const float* kappa, const float* B, int n, int n_inst,
+                    int n_classes, float* beta_out, int32_t* segs_out, int32_t* cuts_out, int32_t* order_out,
+                    int32_t* classes_out, void* stream) {
+    int rc = check_place_shape(L, n, n_inst);
+    if (rc) return rc;
+    if (n_classes < 1) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !kappa || !B || !beta_out || !segs_out || !order_out || (L > 1 && !cuts_out)) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double* sums = nullptr;   // the partitioning step's sums: not part of this call's results
+    PPO_HIP(hipMallocAsync(reinterpret_cast<void**>(&sums), sizeof(double) * (size_t)n_inst, s), "hipMallocAsync (partition sums)");
+    hipError_t e = hipSuccess;
+    for (int first = 0; first < n_inst && e == hipSuccess; first += kInstPerLaunch) {
+        const int cnt = n_inst - first < kInstPerLaunch ? n_inst - first : kInstPerLaunch;
+        int32_t* cuts = cuts_out ? cuts_out + (size_t)first * (L - 1) : nullptr;
+        e = ppo::launch_min_sum_partition(t + (size_t)first * L, m + (size_t)first * L, L, kappa + first, cnt, segs_out + first,
+                                          cuts, sums + first, s);
+        if (e == hipSuccess)
+            e = ppo::launch_heuristic(t + (size_t)first * L, m + (size_t)first * L, L, kappa + first, B + (size_t)first * n * n, n,
+                                      cnt, n_classes, 0, nullptr, 0, segs_out + first, cuts, beta_out + first, segs_out + first,
+                                      cuts, order_out + (size_t)first * n, classes_out ? classes_out + first : nullptr, s);
+    }
+    const hipError_t e2 = hipFreeAsync(sums, s);
+    PPO_HIP(e, "placement heuristic launch");
+    PPO_HIP(e2, "hipFreeAsync (partition sums)");
+    return PPO_OK;
+}
+
+int ppo_place_baseline(const float* t, const float* m, int L, const float* kappa, const float* B, int n, int n_inst,
+                       int kind, const float* draws, int n_draws, float* beta_out, int32_t* segs_out, int32_t* cuts_out,
+                       int32_t* order_out, void* stream) {
+    int rc = check_place_shape(L, n, n_inst);
+    if (rc) return rc;
+    if (kind != PPO_BASELINE_JOINT && kind != PPO_BASELINE_RANDOM) return PPO_EINVAL;
+    if (kind == PPO_BASELINE_RANDOM && (n_draws < 2 || !draws)) return PPO_EINVAL;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !kappa || !B || !beta_out || !segs_out || !order_out || (L > 1 && !cuts_out)) return PPO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int first = 0; first < n_inst; first += kInstPerLaunch) {
+        const int cnt = n_inst - first < kInstPerLaunch ? n_inst - first : kInstPerLaunch;
+        PPO_HIP(ppo::launch_heuristic(t + (size_t)first * L, m + (size_t)first * L, L, kappa + first, B + (size_t)first * n * n, n,
+                                      cnt, 1, kind, draws ? draws + (size_t)first * n_draws : nullptr, n_draws, nullptr, nullptr,
+                                      beta_out + first, segs_out + first, cuts_out ? cuts_out + (size_t)first * (L - 1) : nullptr,
+                                      order_out + (size_t)first * n, nullptr, s),
+                "comparison system launch");
+    }
     return PPO_OK;
 }
 
