@@ -52,12 +52,13 @@ def algorithmic_ops_per_ordering(w):
     return cand, maxops
 
 
-# HBM bytes per launch of the enumeration kernel at the headline workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE) of `bench.py --steps 1 --warmup 0 --no-cpu-baseline --copy-probe`, each counter
-# scaled by what it reads for the probe's 256 MiB (see profiles/).  Keyed by ppo_version(): a library whose
-# kernel has changed since reports no traffic.
-MEASURED_TRAFFIC_BYTES = {("headline", 117): 4.752e7,
-                          ("cluster_mixed_n20", 117): 4.573e9}   # the 20 level launches of one n = 20 solve   # re-measure when the kernel changes
+def profiled(name, version):
+    """Figures that only a profiler run can give (HBM traffic, share of the vector issue slots), read from the
+    summary under profiles/ that `python -m paper_2210_12219_amd.profile_summary` wrote from rocprofv3 output, and
+    only while that summary is of the library version that is running; otherwise {}."""
+    from paper_2210_12219_amd.profile_summary import read_summary
+    got = read_summary(os.path.join(ROOT, "profiles", name + ".md"))
+    return got if got.get("ppo_version") == float(version) else {}
 
 
 def copy_probe(torch):
@@ -91,6 +92,47 @@ def bench_partition(args, torch, ppo, workloads):
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_inst} chains of L={w.L}, capacity 0.2 of the model",
                    "segments_found": [int(x) for x in out[0].cpu().numpy()[:8]]},
+        "roofline": None}), flush=True)
+
+
+def bench_approx(args, torch, ppo, workloads):
+    """Not the headline: the experiment of the paper's Sec. V with the true optimum in place of Theorem 1's bound:
+    bottleneck latency of the paper's placement algorithm (and of its greedy comparison system) over the exact
+    optimum of the same instance, on the paper-shaped clusters (Sec. IV)."""
+    rows = []
+    t_exact = t_heur = 0.0
+    for n in (5, 10, 15, 20):
+        for cap in (32, 16):
+            n_inst = 32 if n < 20 else 12
+            w = workloads.cluster_geometric(n, cap, n_inst=n_inst, seed=500 + n)
+            dev = ppo.to_device(w)
+            kappa = torch.from_numpy(np.ascontiguousarray(w.M[:, 0])).cuda()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            exact = ppo.ppo_solve_cluster(*dev)[0]
+            torch.cuda.synchronize()
+            c1 = time.perf_counter()
+            heur = ppo.ppo_place_kpath(dev[0], dev[1], kappa, dev[3], args.classes)[0]
+            joint = ppo.ppo_place_baseline(dev[0], dev[1], kappa, dev[3], ppo.PPO_BASELINE_JOINT)[0]
+            torch.cuda.synchronize()
+            c2 = time.perf_counter()
+            t_exact += c1 - c0
+            t_heur += c2 - c1
+            e, h, j = (x.cpu().numpy().astype(np.float64) for x in (exact, heur, joint))
+            ok = np.isfinite(e) & np.isfinite(h) & (e > 0)
+            okj = ok & np.isfinite(j)
+            rows.append({"nodes": n, "capacity_mb": cap, "instances": int(ok.sum()),
+                         "heuristic_over_exact": float(np.mean(h[ok] / e[ok])) if ok.any() else None,
+                         "heuristic_optimal_share": float(np.mean(h[ok] == e[ok])) if ok.any() else None,
+                         "joint_over_exact": float(np.mean(j[okj] / e[okj])) if okj.any() else None})
+    ratios = [r["heuristic_over_exact"] for r in rows if r["heuristic_over_exact"] is not None]
+    print(json.dumps({
+        "metric": f"bottleneck latency of the paper's placement algorithm ({args.classes} classes) over the exact optimum, mean",
+        "value": float(np.mean(ratios)), "unit": "ratio", "n_gpus": 1, "steps": 1, "warmup": 0,
+        "ms_per_step": (t_exact + t_heur) * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cluster_geometric: 50-layer chain, n = 5..20 devices of 32 and 16 MB, Shannon-rate links",
+                   "by_cluster": rows, "seconds_exact": t_exact, "seconds_heuristic_and_joint": t_heur},
         "roofline": None}), flush=True)
 
 
@@ -158,7 +200,7 @@ def bench_cluster(args, torch, ppo, workloads):
         # against the whole call (tables, one launch per level, trace), not the level kernel alone
         "roofline": {"bound": "hbm", "kernel": "cluster_level_kernel (all levels) + tables + trace",
                      "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, ppo.load().ppo_version()))
+                     "traffic": profiled(f"cluster_solve_n{N}", ppo.load().ppo_version()).get("traffic_bytes_per_launch")
                      if (n_inst == 1 and pmax == N) else None,
                      "bytes_per_step": alg_bytes},
     }
@@ -186,6 +228,10 @@ def main():
     ap.add_argument("--partition", action="store_true",
                     help="time ppo_min_sum_partition (the paper's own partitioning step) on 4096 chains of L=96: "
                          "a separate figure in instances per second")
+    ap.add_argument("--approx", action="store_true",
+                    help="the paper's placement algorithm against the exact optimum on paper-shaped clusters "
+                         "(ppo_place_kpath / ppo_place_baseline / ppo_solve_cluster): mean ratio of bottleneck latencies")
+    ap.add_argument("--classes", type=int, default=5, help="with --approx: number of transfer-size classes")
     ap.add_argument("--valu-probe", action="store_true",
                     help="measure the issue rate of packed 16-bit vector instructions (ppo_probe_valu): the measured "
                          "peak to set beside the nominal one")
@@ -208,6 +254,8 @@ def main():
         return bench_cluster(args, torch, ppo, workloads)
     if args.partition:
         return bench_partition(args, torch, ppo, workloads)
+    if args.approx:
+        return bench_approx(args, torch, ppo, workloads)
     if args.valu_probe:
         return bench_valu_probe(args, torch, ppo)
     w = workloads.WORKLOADS[args.workload]()
@@ -260,6 +308,7 @@ def main():
     ops_per_launch = (cand + maxops) * n * kf
     achieved = ops_per_launch / (enum_ms * 1e-3) / 1e12
 
+    prof = profiled(f"enumerate_paired_{args.workload}", ppo.load().ppo_version())
     result = {
         "metric": "node orderings (full DPs) evaluated/sec at k=10,L=100; % of VALU peak",
         "value": value, "unit": "orderings/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -267,11 +316,19 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {n} instances x (L={L}, k={k}), {kf} orderings each, seed={w.seed}",
                    "orderings_per_step": n * kf},
+        "candidates_per_s": value * cand,
         "stage_ms": {"prepare": prep_ms, "enumerate": enum_ms, "finalize": fin_ms},
+        # achieved: the min and max operations the DP recurrence asks for (counted from the inputs, not from the
+        # kernel) per second of the enumeration kernel; peak: 32-bit lane operations of the vector ALUs.  The kernel
+        # works on packed 16-bit halves, whose peak is twice that (frac_packed16); valu_issue is the share of the
+        # vector issue slots the kernel filled according to the hardware counters (from the committed profile of
+        # this library version, else null), as is traffic.
         "roofline": {"bound": "alu", "kernel": "enumerate", "achieved": achieved, "peak": VALU_PEAK_TOPS,
                      "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_TOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, ppo.load().ppo_version())),
-                     "ops_per_ordering": {"min": cand, "max": maxops},
+                     "frac_packed16": achieved / (2.0 * VALU_PEAK_TOPS),
+                     "valu_issue": prof.get("valu_issue"),
+                     "traffic": prof.get("traffic_bytes_per_launch"),
+                     "min_ops_per_ordering": cand, "max_ops_per_ordering": maxops,
                      "kernel_ms": enum_ms},
     }
 
@@ -303,9 +360,17 @@ def main():
         c0 = time.perf_counter()
         ppo_oracle.exhaustive(s.t, s.m, s.M, s.B, n_threads=threads, rank_range=(0, span))
         dt = time.perf_counter() - c0
+        # the same oracle on one thread, on a fixed sample: the first million ranks of the first instance
+        one = w.take(1)
+        span1 = min(kf, 1000000)
+        c1 = time.perf_counter()
+        ppo_oracle.exhaustive(one.t, one.m, one.M, one.B, n_threads=1, rank_range=(0, span1))
+        dt1 = time.perf_counter() - c1
         result["cpu_baseline"] = {"value": n_s * span / dt, "unit": "orderings/s", "cores": threads, "kind": "oracle",
                                   "sample": f"ranks [0,{span}) of the first {n_s} instances of {w.name}, "
-                                            f"{dt:.1f} s on {threads} threads"}
+                                            f"{dt:.1f} s on {threads} threads",
+                                  "one_thread": {"value": span1 / dt1, "unit": "orderings/s",
+                                                 "sample": f"ranks [0,{span1}) of instance 0, {dt1:.1f} s"}}
     print(json.dumps(result), flush=True)
 
 
