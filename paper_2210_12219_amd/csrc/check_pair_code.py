@@ -20,7 +20,7 @@ KERNEL = "enumerate_paired_kernel"
 
 
 def check_reserved_registers(asm_text, lay):
-    lo, hi = lay["rb"] + 1, lay["vtop"]
+    lo, hi = lay["rb"], lay["vtop"]   # entry 0 has a (dummy) register too
     inside_kernel = in_asm = False
     seen_blocks = 0
     for n, line in enumerate(asm_text.splitlines(), 1):

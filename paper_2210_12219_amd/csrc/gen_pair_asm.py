@@ -39,8 +39,12 @@ VA1 = VINF + 1       # slot address + 43 rows, + 86 rows
 VA2 = VA1 + 1
 VB1 = VA2 + 1        # the same for the second slot of LOADX
 VB2 = VB1 + 1
+VS0 = VA1            # the slot the outputs of COMPUTE are stored to, + 21 pairs, + 42 pairs (the address
+VS1 = VA2            # registers of the load and store blocks are free by then)
+VS2 = VB1
 VTOP = VB2           # highest fixed register
-ROW_BYTES = 384 * 4  # distance of two entries of one slot in LDS
+ROW_BYTES = 384 * 8  # a slot keeps entries 2h and 2h+1 side by side (8 bytes); next pair of entries this far on
+HMAX = UMAX // 2     # highest pair index
 ST0 = 36             # s[ST0 .. ST0+47]: the offset table of the row (two offsets per register)
 SPC = 84             # s[84:85] jump target, s[86:87] base
 SBASE = 86
@@ -49,22 +53,26 @@ SMASK = 89
 
 
 def R(u):
-    assert 1 <= u <= UMAX
+    assert 0 <= u <= UMAX
     return f"v{RB + u}"
 
 
-def addr_for(u, a0, a1, a2):
-    """address register and offset of entry u (entries 1..43 from a0, 44..86 from a1, 87..95 from a2)."""
-    i = u - 1
-    if i < 43:
-        return a0, i * ROW_BYTES
-    if i < 86:
-        return a1, (i - 43) * ROW_BYTES
-    return a2, (i - 86) * ROW_BYTES
+def RP(h):
+    """the register pair of entries 2h, 2h+1 (entry 0 does not exist; its register is a dummy)"""
+    return f"v[{RB + 2 * h}:{RB + 2 * h + 1}]"
+
+
+def addr_for(h, a0, a1, a2):
+    """address register and offset of pair h (pairs 0..20 from a0, 21..41 from a1, 42..47 from a2)."""
+    if h < 21:
+        return a0, h * ROW_BYTES
+    if h < 42:
+        return a1, (h - 21) * ROW_BYTES
+    return a2, (h - 42) * ROW_BYTES
 
 
 def entry_jump(stride):
-    """jump to entry `skip` of the table that follows (skip = 95 - highest entry, in %[skip])."""
+    """jump to entry `skip` of the table that follows (%[skip]: entries or pairs of entries to leave out at the top)."""
     return [f"s_mul_i32 s{STMP}, %[skip], {stride}",
             f"s_add_u32 s{STMP}, s{STMP}, 12",
             f"s_getpc_b64 s[{SPC}:{SPC + 1}]",
@@ -76,33 +84,34 @@ def entry_jump(stride):
 def block_load(extra):
     """extra: after the lane's own slot, the upper half of every entry is replaced by the upper half of the same
     entry of a second slot.  (A 16-bit load into a register half is no use here: on this chip it clears the other
-    half.)  The second slot is read whole, 24 entries at a time, and merged under a mask."""
-    lines = [f"v_add_u32_e32 v{VA1}, {43 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {86 * ROW_BYTES}, %[addr]"]
+    half.)  The second slot is read whole, 12 pairs at a time, and merged under a mask."""
+    lines = [f"v_add_u32_e32 v{VA1}, {21 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {42 * ROW_BYTES}, %[addr]"]
     if extra:
-        lines += [f"v_add_u32_e32 v{VB1}, {43 * ROW_BYTES}, %[addr2]", f"v_add_u32_e32 v{VB2}, {86 * ROW_BYTES}, %[addr2]",
+        lines += [f"v_add_u32_e32 v{VB1}, {21 * ROW_BYTES}, %[addr2]", f"v_add_u32_e32 v{VB2}, {42 * ROW_BYTES}, %[addr2]",
                   f"s_mov_b32 s{SMASK}, 0xffff"]
     lines += entry_jump(8)
-    for u in range(UMAX, 0, -1):
-        a, off = addr_for(u, "%[addr]", f"v{VA1}", f"v{VA2}")
-        lines.append(f"ds_read_b32 {R(u)}, {a} offset:{off}")
+    for h in range(HMAX, -1, -1):
+        a, off = addr_for(h, "%[addr]", f"v{VA1}", f"v{VA2}")
+        lines.append(f"ds_read_b64 {RP(h)}, {a} offset:{off}")
     if extra:
-        for first in range(1, UMAX + 1, 24):
-            us = list(range(first, min(first + 24, UMAX + 1)))
-            for n, u in enumerate(us):
-                b, off2 = addr_for(u, "%[addr2]", f"v{VB1}", f"v{VB2}")
-                lines.append(f"ds_read_b32 v{VQ + n}, {b} offset:{off2}")
+        for first in range(0, HMAX + 1, 12):
+            hs = list(range(first, min(first + 12, HMAX + 1)))
+            for n, h in enumerate(hs):
+                b, off2 = addr_for(h, "%[addr2]", f"v{VB1}", f"v{VB2}")
+                lines.append(f"ds_read_b64 v[{VQ + 2 * n}:{VQ + 2 * n + 1}], {b} offset:{off2}")
             lines.append("s_waitcnt lgkmcnt(0)")
-            for n, u in enumerate(us):
-                lines.append(f"v_bfi_b32 {R(u)}, s{SMASK}, {R(u)}, v{VQ + n}")
+            for n, h in enumerate(hs):
+                for d in range(2):
+                    lines.append(f"v_bfi_b32 {R(2 * h + d)}, s{SMASK}, {R(2 * h + d)}, v{VQ + 2 * n + d}")
     return lines
 
 
 def block_store():
-    lines = [f"v_add_u32_e32 v{VA1}, {43 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {86 * ROW_BYTES}, %[addr]"]
+    lines = [f"v_add_u32_e32 v{VA1}, {21 * ROW_BYTES}, %[addr]", f"v_add_u32_e32 v{VA2}, {42 * ROW_BYTES}, %[addr]"]
     lines += entry_jump(8)
-    for u in range(UMAX, 0, -1):
-        a, off = addr_for(u, "%[addr]", f"v{VA1}", f"v{VA2}")
-        lines.append(f"ds_write_b32 {a}, {R(u)} offset:{off}")
+    for h in range(HMAX, -1, -1):
+        a, off = addr_for(h, "%[addr]", f"v{VA1}", f"v{VA2}")
+        lines.append(f"ds_write_b64 {a}, {RP(h)} offset:{off}")
     return lines
 
 
@@ -122,14 +131,19 @@ def block_qmax():
     return lines
 
 
-def header(u):
-    """start of output u: accumulator +inf, jump to the entry the table names (five instructions, 20 bytes)."""
+def header(u, store_pair=None):
+    """start of output u: [the pair of entries completed just before goes to the lane's slot,] accumulator +inf,
+    jump to the entry the table names."""
     x, hi = (u - 1) // 2, (u - 1) & 1
     first = f"s_lshr_b32 s{STMP}, s{ST0 + x}, 16" if hi else f"s_and_b32 s{STMP}, s{ST0 + x}, s{SMASK}"
-    return [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
-            f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
-            f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
-            f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
+    lines = []
+    if store_pair is not None:
+        a, off = addr_for(store_pair, f"v{VS0}", f"v{VS1}", f"v{VS2}")
+        lines.append(f"ds_write_b64 {a}, {RP(store_pair)} offset:{off}")
+    return lines + [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
+                    f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
+                    f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
+                    f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
 
 
 HEADER_BYTES = 20
@@ -145,62 +159,75 @@ def jmax_odd(u):
 
 def block_compute():
     """returns (lines, offsets) with offsets[u] = (even_base, odd_base, zero) and offsets['end'], in bytes from
-    the base (the instruction after s_getpc)."""
+    the base (the instruction after s_getpc).  Outputs are stored as they are completed, a pair of entries at a
+    time, to the slot at %[saddr] (a spare slot when the row is not wanted in LDS)."""
     lines = [f"s_load_dwordx16 s[{ST0}:{ST0 + 15}], %[desc], 0x0",
              f"s_load_dwordx16 s[{ST0 + 16}:{ST0 + 31}], %[desc], 0x40",
              f"s_load_dwordx16 s[{ST0 + 32}:{ST0 + 47}], %[desc], 0x80",
              f"s_mov_b32 s{SMASK}, 0xffff",
              f"v_mov_b32_e32 v{VINF}, 0x7c007c00",
+             f"v_mov_b32_e32 v{VS0}, %[saddr]",
+             f"v_add_u32_e32 v{VS1}, {21 * ROW_BYTES}, %[saddr]",
+             f"v_add_u32_e32 v{VS2}, {42 * ROW_BYTES}, %[saddr]",
              f"s_mul_i32 s{STMP}, %[skip], {HEADER_BYTES}",
              "s_waitcnt lgkmcnt(0)",
              f"s_getpc_b64 s[{SBASE}:{SBASE + 1}]"]
     pos = 0   # bytes from the base
     body = []
 
-    def emit(ls, size):
+    def emit(ls):
         nonlocal pos
-        body.extend(ls)
-        pos += size
+        for ln in ls:
+            body.append(ln)
+            pos += size_of(ln)
 
-    # the first header: jump to the standalone header of the highest entry
+    # the first header: jump to the standalone header of the highest entry (%[skip] = UMAX - highest entry here)
     emit([f"s_add_u32 s{STMP}, s{STMP}, 16",           # distance from the base to the table of standalone headers
           f"s_add_u32 s{SPC}, s{SBASE}, s{STMP}",
           f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
-          f"s_setpc_b64 s[{SPC}:{SPC + 1}]"], 16)
+          f"s_setpc_b64 s[{SPC}:{SPC + 1}]"])
+    assert pos == 16
     for u in range(UMAX, 0, -1):
-        emit(header(u), HEADER_BYTES)
+        emit(header(u))
+    assert pos == 16 + UMAX * HEADER_BYTES
     offsets = {}
     for u in range(UMAX, 0, -1):
-        nxt = header(u - 1) if u > 1 else None
+        # after output u: if u is even, entries u and u+1 are both final and go to LDS
+        nxt = header(u - 1, store_pair=(u // 2 if u % 2 == 0 else None)) if u > 1 else None
         je, jo = jmax_even(u), jmax_odd(u)
         even_base = pos
         if je >= 0:
             for J in range(je, 0, -1):
-                emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"], 8)
-            emit([f"v_pk_minimum3_f16 {R(u)}, v{VACC}, {R(u)}, {R(u - 1)}"], 8)
-            if nxt:
-                emit(nxt, HEADER_BYTES)
-            else:
-                emit(["s_branch ppo_pair_end"], 4)
+                emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"])
+            emit([f"v_pk_minimum3_f16 {R(u)}, v{VACC}, {R(u)}, {R(u - 1)}"])
+            emit(nxt if nxt else ["s_branch ppo_pair_end"])
         odd_base = pos
         for J in range(jo, 0, -1):
-            emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"], 8)
-        emit([f"v_pk_min_u16 {R(u)}, v{VACC}, {R(u)}"], 8)
-        if nxt:
-            emit(nxt, HEADER_BYTES)
-        else:
-            emit(["s_branch ppo_pair_end"], 4)
+            emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"])
+        emit([f"v_pk_min_u16 {R(u)}, v{VACC}, {R(u)}"])
+        emit(nxt if nxt else ["s_branch ppo_pair_end"])
         zero = pos
-        emit([f"v_mov_b32_e32 {R(u)}, v{VINF}"], 4)
+        emit([f"v_mov_b32_e32 {R(u)}, v{VINF}"])
         if nxt:
-            emit(nxt, HEADER_BYTES)
+            emit(nxt)
         offsets[u] = (even_base if je >= 0 else None, odd_base, zero)
     offsets["end"] = pos
     body.append("ppo_pair_end:")
+    a, off = addr_for(0, f"v{VS0}", f"v{VS1}", f"v{VS2}")
+    body.append(f"ds_write_b64 {a}, {RP(0)} offset:{off}")   # entry 1 (with the dummy entry 0)
     return lines + body, offsets
 
 
+def size_of(line):
+    """bytes of one instruction of the COMPUTE block (checked against the assembled code by check_pair_code.py)"""
+    op = line.split()[0]
+    if op.startswith("v_pk_") or op.startswith("ds_"):
+        return 8
+    return 4
+
+
 def block_extract():
+    """%[skip] = UMAX - highest entry"""
     lines = entry_jump(8)
     for u in range(UMAX, 0, -1):
         lines += [f"v_mov_b32_e32 %[res], {R(u)}", "s_branch ppo_pair_out"]
@@ -226,11 +253,12 @@ def c_string(lines):
 def main():
     compute, offsets = block_compute()
     assert offsets["end"] // 4 < 65536
-    clobber_v = ", ".join(f'"v{i}"' for i in range(RB + 1, VTOP + 1))
+    clobber_v = ", ".join(f'"v{i}"' for i in range(RB, VTOP + 1))
     clobber_s = ", ".join(f'"s{i}"' for i in range(ST0, ST0 + 48)) + ", " + ", ".join(f'"s{i}"' for i in range(SPC, SMASK + 1))
     out = ["// Generated by gen_pair_asm.py; do not edit.  Row steps of the paired enumeration kernel (see the generator).",
            "#pragma once", "#include <stdint.h>", "",
            f"#define PPO_PAIR_UMAX {UMAX}",
+           f"#define PPO_PAIR_HMAX {HMAX}",
            f"#define PPO_PAIR_RB {RB}",
            f"#define PPO_PAIR_VTOP {VTOP}",
            f"#define PPO_PAIR_ROW_BYTES {ROW_BYTES}",

@@ -44,7 +44,7 @@ struct PairedShape {
         g.nA = p0 > 1 ? p0 - 1 : 0;
         g.nB = p0 > 0 ? 6 : 0;
         g.nQ = g.nA + g.nB + 15;
-        g.q_off = (uint32_t)(g.NE - 1) * kPairSlots;
+        g.q_off = (uint32_t)((g.NE - 1) / 2 + 1) * 2u * kPairSlots;   // pairs of entries (2h, 2h+1), h = 0 .. (NE-1)/2
         g.q_dwords = (uint32_t)(g.nQ * g.QPITCH);          // one quotient table per team
         g.sync_off = g.q_off + kPairTeams * g.q_dwords;    // then the counters the teams synchronise with
         // 64 dwords behind the tables: the quotient reads of a row always take 48 dwords from their first column
@@ -59,8 +59,12 @@ bool paired_supported(int L, int k) {
     return g.NE - 1 <= PPO_PAIR_UMAX && g.total_bytes <= (uint32_t)kLdsBytesPerCU;
 }
 
-// spare slot that holds the first DP row of node j (both halves the same), and the spare slots of the idle lanes
+// spare slot that holds the first DP row of node j (both halves the same); the spare slots 30, 31, 62, 63 are the
+// idle lanes'; one more takes the stores of rows that are not wanted in LDS
 __host__ __device__ inline uint32_t pair_d0_slot(int j) { return (uint32_t)(2 + j / 2) * 32u + 30u + (uint32_t)(j & 1); }
+constexpr uint32_t kPairDummySlot = 8u * 32u + 30u;
+// dword of entry u of a slot: entries 2h and 2h+1 side by side, the next pair of entries 2 * kPairSlots dwords on
+__host__ __device__ inline uint32_t pair_entry_dword(uint32_t slot, uint32_t u) { return (u >> 1) * (2u * kPairSlots) + slot * 2u + (u & 1u); }
 
 // ---------------------------------------------------------------------------------------------
 // Entry offsets: for node j and DP row s = 1..k-1, where the chain of each output starts.  Row k-1 needs
@@ -120,8 +124,8 @@ __device__ __forceinline__ void pair_store(uint32_t addr, uint32_t skip) {
 __device__ __forceinline__ void pair_qmax(uint32_t qaddr) {
     asm volatile(PPO_PAIR_QMAX_ASM : : [qaddr] "v"(qaddr) : PPO_PAIR_CLOBBERS);
 }
-__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip) {
-    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip, uint32_t saddr) {
+    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip), [saddr] "v"(saddr) : PPO_PAIR_CLOBBERS);
 }
 __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
     uint32_t res;
@@ -161,7 +165,9 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     const int p0 = k - 6;
     const PairedShape ps = PairedShape::make(L, k);
     const int NE = ps.NE, QD = ps.QD, QROW = ps.QROW, QPITCH = ps.QPITCH, nA = ps.nA, nB = ps.nB;
+    // what the blocks leave out at the top of their unrolled ranges: entries (compute, extract), pairs of entries (load, store)
     const uint32_t skip = (uint32_t)__builtin_amdgcn_readfirstlane(PPO_PAIR_UMAX - (NE - 1));
+    const uint32_t skip_pairs = (uint32_t)__builtin_amdgcn_readfirstlane(PPO_PAIR_HMAX - (NE - 1) / 2);
 
     const unsigned char* base = ws + (size_t)inst * y.stride;
     const float* __restrict__ dec = reinterpret_cast<const float*>(base + y.dec_off);
@@ -176,19 +182,20 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                    lc3 = kPairLane[wave][lane][3];
     auto slot_addr = [&](int r) -> uint32_t {
         const uint32_t s = ((r < 3 ? lc0 >> (9 * r) : lc1 >> (9 * (r - 3))) & 511u);
-        return buf_addr + s * 4u;
+        return buf_addr + s * 8u;
     };
+    const uint32_t dummy_addr = buf_addr + kPairDummySlot * 8u;
     // first DP rows of all nodes into their spare slots, and +inf into the spare slots of the idle lanes
     {
         const uint32_t* d0src = reinterpret_cast<const uint32_t*>(base + y.d0_off);
         for (int idx = tid; idx < k * (NE - 1); idx += kPairThreads) {
             const int j = idx / (NE - 1), u = idx - j * (NE - 1) + 1;
             const uint32_t c = (d0src[j * y.wt_cols + (u >> 1)] >> (16 * (u & 1))) & 0xFFFFu;
-            lds[(u - 1) * kPairSlots + pair_d0_slot(j)] = c | (c << 16);
+            lds[pair_entry_dword(pair_d0_slot(j), (uint32_t)u)] = c | (c << 16);
         }
         for (int idx = tid; idx < 4 * (NE - 1); idx += kPairThreads) {
             const int n = idx & 3, u = (idx >> 2) + 1;
-            lds[(u - 1) * kPairSlots + 30 + (n & 1) + 32 * (n >> 1)] = kCodeInf | (kCodeInf << 16);
+            lds[pair_entry_dword(30u + (uint32_t)(n & 1) + 32u * (uint32_t)(n >> 1), (uint32_t)u)] = kCodeInf | (kCodeInf << 16);
         }
         if (tid < (int)(sizeof(PairSync) / 4)) lds[ps.sync_off + tid] = 0u;
     }
@@ -260,17 +267,17 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
         // the wave whatever the lane holds); from the row of position 1 on, a row is loaded from the slots its
         // lanes hold now, and every row but the last is stored for the next one.  One copy of each block: the
         // generated code is large, and its labels are not unique on purpose (a second copy would not assemble).
-        const uint32_t d0_addr = buf_addr + pair_d0_slot(p0 > 0 ? pnode(0) : rnode(wave)) * 4u;
+        const uint32_t d0_addr = buf_addr + pair_d0_slot(p0 > 0 ? pnode(0) : rnode(wave)) * 8u;
 #pragma unroll 1
         for (int s = 0; s < k; ++s) {
             const int r = s - p0;
             if (s == 0 || r >= 1) {
                 const uint32_t a = s == 0 ? d0_addr : slot_addr(r);
                 if (r == 4) {
-                    pair_load_exchange(a, buf_addr + (lc2 & 511u) * 4u, skip);
+                    pair_load_exchange(a, buf_addr + (lc2 & 511u) * 8u, skip_pairs);
                     team_meet();   // every upper half has been fetched before a slot is overwritten
                 } else {
-                    pair_load(a, skip);
+                    pair_load(a, skip_pairs);
                 }
             }
             if (s >= 1) {
@@ -290,14 +297,16 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 pair_qmax(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u);
                 if (s == k - 1) pair_arrive(&sync->done);   // the last row is in registers: the buffer can go on
                 const uint32_t* desc = pt + (uint32_t)__builtin_amdgcn_readfirstlane((node * (k - 1) + (s - 1)) * kPairTableDwords);
-                pair_compute(desc, skip);
+                // the outputs go to LDS as they are completed where the next row has to fetch them from other lanes
+                // (rows of positions 1 .. 4), else to a spare slot
+                pair_compute(desc, skip, (r >= 1 && s < k - 1) ? slot_addr(r) : dummy_addr);
             }
-            if (r >= 0 && s < k - 1) {
-                // the first store of a group waits for the buffer: every wave of the group before it has fetched its last row
-                if (r == 0) pair_spin_until(&sync->done, gi * (uint32_t)kPairWaves);
-                pair_store(slot_addr(r), skip);
-                team_meet();
+            if (r == 0 && s < k - 1) {
+                // the group's first row in LDS waits for the buffer: every wave of the group before it has fetched its last row
+                pair_spin_until(&sync->done, gi * (uint32_t)kPairWaves);
+                pair_store(slot_addr(0), skip_pairs);
             }
+            if (r >= 0 && s < k - 1) team_meet();
         }
         const uint32_t res = pair_extract(skip);   // D[L] of the lane's two orderings
         if (lc3 >> 31) {

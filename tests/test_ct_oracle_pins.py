@@ -87,6 +87,17 @@ def test_a_slow_node_gets_the_light_end(route):
     assert float(b) == 2.0 and list(cuts) == [1] and list(order) == [0, 1]
 
 
+@pytest.mark.parametrize("route", ROUTES)
+def test_compute_stage_is_divided_in_binary64_and_rounded_once(route):
+    """Work 23642438 + 41 on a node of speed 56, one segment: the sum 23642479 is exact in binary64 but not in
+    binary32 (it would round to 23642480); 23642479 / 56 = 422187.125 exactly, so beta = 422187.125, while a
+    binary32 sum or quotient gives 422187.15625 (by hand: 23642480 / 56 = 422187.1428..., nearest float above .125)."""
+    f = ROUTES[route]
+    b, cuts, order = f(np.zeros(2, np.float32), np.ones(2, np.float32), np.array([23642438, 41], np.float32),
+                       np.array([5.0], np.float32), np.array([56.0], np.float32), np.zeros((1, 1), np.float32))
+    assert float(b) == 422187.125
+
+
 def definition(t, m, w, M, v, B):
     """Eq. 1 written out in Python (binary64 sums, one rounding), every (permutation, cut vector) pair."""
     L, k = len(t), len(M)

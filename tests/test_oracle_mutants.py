@@ -14,8 +14,25 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FIXED = ("oracle/ppo_oracle.c", "PPO_ORACLE_SOURCE", ["tests/test_oracle_pins.py"])
 CLUSTER = ("oracle/ppo_cluster_oracle.c", "PPO_CLUSTER_ORACLE_SOURCE", ["tests/test_cluster_oracle_pins.py"])
 
+CT = ("oracle/ppo_ct_oracle.c", "PPO_CT_ORACLE_SOURCE", ["tests/test_ct_oracle_pins.py"])
+
 # (which oracle, text in the source, what replaces it, what the mistake is)
 MUTANTS = [
+    (CT, "volatile double d = (I->Q[e] - I->Q[i]) / (double)I->v[node];", "volatile double d = (I->Q[e] - I->Q[i]) * (double)I->v[node];",
+     "compute stage: work times speed"),
+    (CT, "volatile double d = (I->Q[e] - I->Q[i]) / (double)I->v[node];", "volatile double d = (I->Q[e - 1] - I->Q[i]) / (double)I->v[node];",
+     "compute stage: the last layer of the segment is not counted"),
+    (CT, "volatile double d = (I->Q[e] - I->Q[i]) / (double)I->v[node];",
+     "volatile double d = (double)((float)(I->Q[e] - I->Q[i]) / I->v[node]);", "compute stage: divided in binary32"),
+    (CT, "I->Q[i + 1] = I->Q[i] + (double)w[i];", "I->Q[i + 1] = I->Q[i] + (double)m[i];", "compute stage: weights taken for work"),
+    (CT, "static float fmax2(float a, float b) { return a > b ? a : b; }", "static float fmax2(float a, float b) { return a < b ? a : b; }",
+     "the least stage instead of the largest"),
+    (CT, "if (ct_fits(I, 0, e, perm[0])) rows[e] = ct_comp(I, 0, e, perm[0]);", "if (ct_fits(I, 0, e, perm[0])) rows[e] = 0.0f;",
+     "per-ordering route: the first segment's compute stage is dropped"),
+    (CT, "if (ct_fits(&I, i, L, j)) best = ct_comp(&I, i, L, j);", "if (ct_fits(&I, i, L, j)) best = 0.0f;",
+     "subset route: the last segment's compute stage is dropped"),
+    (CT, "b = fmax2(b, ct_comp(&I, c[s], c[s + 1], perm[s]));", "if (s > 0) b = fmax2(b, ct_comp(&I, c[s], c[s + 1], perm[s]));",
+     "definition route: the first segment's compute stage is dropped"),
     (FIXED, "return (I->P[e] - I->P[i]) <= (double)I->M[node]; }", "return (I->P[e] - I->P[i]) < (double)I->M[node]; }",
      "a segment that fills a node exactly no longer fits"),
     (FIXED, "return (I->P[e] - I->P[i]) <= (double)I->M[node]; }", "return (I->P[e - 1] - I->P[i]) <= (double)I->M[node]; }",
@@ -61,6 +78,28 @@ MUTANTS = [
 # The Python oracles: (file, pin tests, pytest -k expression, [(text, replacement), ...], what the mistake is).
 # The altered file shadows the real one in a copy of the package placed first on the import path.
 PY_MUTANTS = [
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("float(B[a][b]) >= thr", "float(B[a][b]) > thr")], "a link at the threshold is left out (Eq. 8 says at or above)"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("if result is None:\n            low = median + 1\n        else:\n            high = median",
+       "if result is None:\n            high = median\n        else:\n            low = median + 1")],
+     "Alg. 2 bisects the wrong way"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("key=lambda r: (-r[1], r[0])", "key=lambda r: (r[1], r[0])")], "Alg. 3 matches the shortest runs first"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("for X in range(n_classes - 1, -1, -1):", "for X in range(n_classes):")], "Alg. 3 starts with the lowest class"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("g = gamma(t[c - 1], B[nodes[s - 1]][nodes[s]])", "g = gamma(t[c], B[nodes[s - 1]][nodes[s]])")],
+     "tensor of the layer after the cut"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("int(math.floor((float(x) - lo) / (hi - lo) * n_classes))", "int(math.floor((float(x) - lo) / hi * n_classes))")],
+     "class bins not taken over the range of the sizes"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("key=lambda v: (float(B[cur][v]), -v))", "key=lambda v: (-float(B[cur][v]), -v))")],
+     "joint system moves on over the worst link"),
+    ("oracle/ppo_heuristic_oracle.py", "tests/test_heuristic_oracle.py", "",
+     [("        if not at_start and not at_end and not avail[v]:\n            return False\n", "")],
+     "the path search takes nodes that are already used"),
     ("oracle/ppo_partition_oracle.py", "tests/test_partition_oracle.py", "",
      [("P[e] - P[s] <= float(kappa)", "P[e] - P[s] < float(kappa)"), ("P[e] - P[i] <= float(kappa)", "P[e] - P[i] < float(kappa)")],
      "both routes: a segment that fills the node exactly no longer fits"),
@@ -99,6 +138,9 @@ def test_pins_notice_a_planted_mistake_in_a_python_oracle(case, tmp_path):
         assert text.count(old) >= 1, f"the source no longer holds the text this case alters: {old!r}"
         text = text.replace(old, new)
     (shadow / os.path.basename(source)).write_text(text)
+    for other in os.listdir(os.path.join(ROOT, "oracle")):   # what the altered module imports from its own package
+        if other.endswith(".py") and other not in ("__init__.py", os.path.basename(source)):
+            (shadow / other).write_text(open(os.path.join(ROOT, "oracle", other)).read())
     env = dict(os.environ, PYTHONPATH=os.pathsep.join([str(tmp_path), ROOT, os.environ.get("PYTHONPATH", "")]))
     cmd = [sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider", "--rootdir", ROOT,
            os.path.join(ROOT, pin_file)]
