@@ -292,8 +292,8 @@ int ppo_chain_from_dag(int n_vertices, int n_edges, const int32_t *edge_src, con
  * instruction the enumeration is made of (packed 16-bit minimum / maximum), to quote a measured peak beside
  * the nominal one of one wave instruction per 4 clocks per SIMD.  Enqueues one kernel: 256 workgroups (one per
  * compute unit; each asks for more than half a unit's LDS) of 4 * waves_per_simd waves; every wave runs
- * `iters` rounds of 16 such instructions on four independent accumulators, without memory traffic, so a SIMD
- * issues 16 * iters * waves_per_simd of them.  The caller times the stream.
+ * `iters` rounds of 64 such instructions on eight independent accumulators, without memory traffic, so a SIMD
+ * issues 64 * iters * waves_per_simd of them (and 3 scalar instructions of the loop per round).  The caller times the stream.
  *   waves_per_simd  1..4
  *   sink            [256 * 256 * waves_per_simd] device words, written once at the end (so that the work is kept)
  * PPO_EINVAL: waves_per_simd or iters out of range, null sink. */

@@ -31,9 +31,13 @@ def build(verbose: bool = False) -> str:
     cmd = [HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"), "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    check_paired_kernel(verbose)
-    os.replace(tmp, LIB)
+    try:
+        subprocess.check_call(cmd)
+        check_paired_kernel(verbose)
+        os.replace(tmp, LIB)
+    finally:
+        if os.path.exists(tmp):
+            os.remove(tmp)
     return LIB
 
 

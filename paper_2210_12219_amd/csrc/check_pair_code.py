@@ -56,6 +56,8 @@ def check_entry_offsets(disasm_text, lay):
             inside = True
             continue
         if inside and re.match(r"^[0-9a-f]+ <", line):
+            if re.match(r"^[0-9a-f]+ <ppo_pair_\w+>:", line):
+                continue          # the blocks' own labels
             break
         if inside:
             m = re.match(r"^\s*(\S.*?)\s*//\s*([0-9A-Fa-f]+):", line)
@@ -87,6 +89,9 @@ def check_entry_offsets(disasm_text, lay):
             checked += 1
     # the block ends right after the instruction that writes +inf into entry 1
     assert instr.get(base + lay["end"] - 4) == f"v_mov_b32_e32 {R(1)}, v{vinf}", "end of the block is not where the table says"
+    last = instr.get(base + lay["end"], "")
+    assert last.startswith("ds_write_b64") and f"v[{rb}:{rb + 1}]" in last, f"the block does not end with the store of entry 1: `{last}`"
+    assert base + lay["end"] + 8 in instr, "nothing follows the last store at the expected distance"
     return checked
 
 

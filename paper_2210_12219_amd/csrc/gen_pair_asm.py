@@ -286,7 +286,8 @@ def main():
             "    if (w & 1u) return odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
             "    return even_base[u] + 2u * ((u - 2u) / 2u - (w / 2u - 1u));",
             "}",
-            f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block",
+            f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block: entry 1 is stored, then the block is left",
+            f"constexpr uint32_t kPairEndNoStore = {offsets['end'] // 4 + 2};   // past that store (for a caller that has not computed entry 1)",
             "}  // namespace ppo", ""]
     path = os.path.join(HERE, "ppo_pair_asm.h")
     with open(path, "w") as f:

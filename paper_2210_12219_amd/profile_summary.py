@@ -65,8 +65,8 @@ def traffic(fetch_dir, write_dir, kernel):
             if kernel in r["Kernel_Name"]:
                 mine += float(r["Counter_Value"])
                 seen.add(r["Dispatch_Id"])
-            # the probe is torch's elementwise add: the one vectorized_elementwise kernel of the run that is not a fill
-            if "vectorized_elementwise_kernel" in r["Kernel_Name"] and "CUDAFunctor_add" in r["Kernel_Name"]:
+            # the probe is torch's in-place elementwise add: the one vectorized_elementwise kernel that is not a fill
+            if "vectorized_elementwise_kernel" in r["Kernel_Name"] and "_add<" in r["Kernel_Name"]:
                 probe += float(r["Counter_Value"])
         n_mine = max(len(seen), 1)
         factor = PROBE_BYTES / probe if probe else float("nan")   # bytes per count
