@@ -57,6 +57,9 @@ def check_paired_kernel(verbose: bool = False) -> None:
             clang = "/opt/rocm/llvm/bin/clang"
         subprocess.check_call([clang, "-x", "assembler", "-target", "amdgcn-amd-amdhsa", "-mcpu=gfx950", "-c", asm, "-o", obj])
         subprocess.check_call([sys.executable, os.path.join(PKG, "csrc", "check_pair_code.py"), asm, obj])
+    # and the tables that steer the jumps: the kernel's own table builder, compiled for the host, walked through a
+    # model of the generated code (csrc/check_pair_program.py)
+    subprocess.check_call([sys.executable, os.path.join(PKG, "csrc", "check_pair_program.py"), "200"])
 
 
 if __name__ == "__main__":

@@ -6,8 +6,8 @@ at offsets computed from instruction sizes.  Both rest on what the toolchain emi
 code it did emit:
   1. in the compiler's assembly of the kernel, no instruction outside the blocks touches a reserved register;
   2. in the disassembly of the assembled object, the instruction at every entry offset of ppo_pair_layout.json is
-     the chain step the table means (right chain, right depth, right registers), and the block ends where the
-     table says.
+     the chain step or run step the table means (right chain, right depth, right registers), every header
+     reads the table entry of the position below the code it follows, and the block ends where the table says.
 """
 import json
 import os
@@ -87,11 +87,41 @@ def check_entry_offsets(disasm_text, lay):
                         else f"v_pk_minimum3_f16 {R(u)}, v{vacc}, {R(u)}, {R(u - 1)}")
             assert got == want, f"entry u={u} w={w} at +{off}: found `{got}`, expected `{want}`"
             checked += 1
-    # the block ends right after the instruction that writes +inf into entry 1
-    assert instr.get(base + lay["end"] - 4) == f"v_mov_b32_e32 {R(1)}, v{vinf}", "end of the block is not where the table says"
-    last = instr.get(base + lay["end"], "")
-    assert last.startswith("ds_write_b64") and f"v[{rb}:{rb + 1}]" in last, f"the block does not end with the store of entry 1: `{last}`"
-    assert base + lay["end"] + 8 in instr, "nothing follows the last store at the expected distance"
+    # the run code: entered at position a of the piece ending at p, the first instruction folds entry a into the
+    # output below it; the piece's header follows its last instruction
+    for ps, by_a in lay["runs"].items():
+        for as_, off in by_a.items():
+            a = int(as_)
+            got = instr.get(base + off)
+            want = f"v_pk_min_u16 {R(a)}, {R(a - 1)}, {R(a)}"
+            assert got == want, f"run code p={ps} a={a} at +{off}: found `{got}`, expected `{want}`"
+            checked += 1
+        p = int(ps)
+        got = instr.get(base + by_a[ps] + 8)
+        assert got == f"v_mov_b32_e32 v{vacc}, v{vinf}", f"no header after the run code ending at {p}: `{got}`"
+    # every header reads the table entry of the position below the code it follows: the instruction after the
+    # last one of a chain (8 bytes on) starts a header whose second instruction names that entry's register
+    st0, nslot = lay["st0"], lay["nslot"]
+
+    def header_reads(addr, position):
+        slot = (position - 1) % nslot
+        x, hi = slot // 2, slot & 1
+        want = (f"s_lshr_b32 s{lay['stmp']}, s{st0 + x}, 16" if hi
+                else f"s_and_b32 s{lay['stmp']}, s{st0 + x}, s{lay['smask']}")
+        assert instr.get(addr) == f"v_mov_b32_e32 v{vacc}, v{vinf}" and instr.get(addr + 4) == want, \
+            f"header for position {position} at +{addr - base}: `{instr.get(addr)}` / `{instr.get(addr + 4)}`, expected `{want}`"
+
+    for us, by_w in lay["entries"].items():
+        u = int(us)
+        header_reads(base + by_w["1"] + 8, u - 1)    # after the odd chain's last instruction
+        header_reads(base + by_w["0"] + 4, u - 1)    # after the +inf
+        if "2" in by_w:
+            header_reads(base + by_w["2"] + 8, u - 1)
+    for ps, by_a in lay["runs"].items():
+        header_reads(base + by_a[ps] + 8, int(ps) - 1)
+    # the block ends right after the header of the last piece of run code
+    assert instr.get(base + lay["end"] - 4, "").startswith("s_setpc_b64"), "end of the block is not where the table says"
+    assert base + lay["end"] in instr, "no instruction at the end of the block"
     return checked
 
 

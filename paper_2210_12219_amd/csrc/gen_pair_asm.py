@@ -13,14 +13,24 @@ minima (two new entries per instruction), one for even and one for odd w, each e
 writes v[RB + u]; a chain is entered at the step that leaves exactly w entries to fold, by a computed jump
 whose target comes from a table the precompute kernel wrote for this (node, row): 16-bit offsets from the
 block's base in units of four bytes, two per dword, read into scalar registers.  After the last instruction of
-a chain the header of output u-1 follows (a copy of it after each chain), which starts the accumulator at
-+inf and jumps again.  w = 0 (no legal segment start) writes +inf and branches to that header.
+a chain a header follows (a copy of it after each chain), which starts the accumulator at +inf and jumps to
+whatever the table names for the position below.  w = 0 (no legal segment start) writes +inf.
+
+Runs.  Consecutive outputs whose windows start at the same entry (the memory rule lets the window grow with the
+segment end until a heavy layer pushes its start up) are prefix minima of one another: only the lowest output
+of such a run is folded by a chain; each one above it is the minimum of the output below it and its own entry,
+one instruction, `v_pk_min_u16 v[u], v[u-1], v[u]`, in ascending order.  For every end position p there is a
+piece of code with these instructions for the (up to ECAP) positions ending at p, followed by a header; it is
+entered at the run's second output.  Runs are worked from the top of the row down, each run from its lowest
+output up; a lower run reads nothing that a higher one has written.  The table entry a header reads is the
+one of the position below the code it follows; the precompute kernel (ppo_pair_program.h) fills the entries
+so that the jumps walk the runs in this order and leave the block at the end.
 
 Blocks (each one `asm volatile` statement in the kernel; fixed registers, declared clobbered there):
   LOAD     entries NE-1..1 from the lane's slot in LDS (one dword per entry, 1536 bytes apart)
   LOADX    the same, then the upper half of every entry replaced by that of another slot (the pairing changes)
   QMAX     entry u = max(entry u, code of t[u+s-2]/B of the lane's link), both halves the same link
-  COMPUTE  the chains
+  COMPUTE  the chains and the run steps
   STORE    entries NE-1..1 to the lane's slot
   EXTRACT  entry NE-1 to an output register
 Every block that works on a range of entries is entered at entry NE-1 by a computed jump (all entries of one
@@ -39,9 +49,6 @@ VA1 = VINF + 1       # slot address + 43 rows, + 86 rows
 VA2 = VA1 + 1
 VB1 = VA2 + 1        # the same for the second slot of LOADX
 VB2 = VB1 + 1
-VS0 = VA1            # the slot the outputs of COMPUTE are stored to, + 21 pairs, + 42 pairs (the address
-VS1 = VA2            # registers of the load and store blocks are free by then)
-VS2 = VB1
 VTOP = VB2           # highest fixed register
 ROW_BYTES = 384 * 8  # a slot keeps entries 2h and 2h+1 side by side (8 bytes); next pair of entries this far on
 HMAX = UMAX // 2     # highest pair index
@@ -50,6 +57,8 @@ SPC = 84             # s[84:85] jump target, s[86:87] base
 SBASE = 86
 STMP = 88
 SMASK = 89
+ECAP = 16            # outputs of a run that one piece of run code takes (a longer run continues in another piece)
+NSLOT = 96           # 16-bit entries of a row's table: position u reads entry (u - 1) mod 96 (position 0: the last)
 
 
 def R(u):
@@ -131,19 +140,16 @@ def block_qmax():
     return lines
 
 
-def header(u, store_pair=None):
-    """start of output u: [the pair of entries completed just before goes to the lane's slot,] accumulator +inf,
-    jump to the entry the table names."""
-    x, hi = (u - 1) // 2, (u - 1) & 1
+def header(u):
+    """what follows the code of position u + 1 (or starts the row at its highest position u): accumulator +inf,
+    jump to the entry the table names for position u (0 <= u <= UMAX)."""
+    slot = (u - 1) % NSLOT
+    x, hi = slot // 2, slot & 1
     first = f"s_lshr_b32 s{STMP}, s{ST0 + x}, 16" if hi else f"s_and_b32 s{STMP}, s{ST0 + x}, s{SMASK}"
-    lines = []
-    if store_pair is not None:
-        a, off = addr_for(store_pair, f"v{VS0}", f"v{VS1}", f"v{VS2}")
-        lines.append(f"ds_write_b64 {a}, {RP(store_pair)} offset:{off}")
-    return lines + [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
-                    f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
-                    f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
-                    f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
+    return [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
+            f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
+            f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
+            f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
 
 
 HEADER_BYTES = 20
@@ -157,18 +163,19 @@ def jmax_odd(u):
     return (u - 1) // 2
 
 
+def emit_first(p):
+    """the lowest position the run code ending at p holds"""
+    return max(2, p - ECAP + 1)
+
+
 def block_compute():
-    """returns (lines, offsets) with offsets[u] = (even_base, odd_base, zero) and offsets['end'], in bytes from
-    the base (the instruction after s_getpc).  Outputs are stored as they are completed, a pair of entries at a
-    time, to the slot at %[saddr] (a spare slot when the row is not wanted in LDS)."""
+    """returns (lines, offsets) with offsets[u] = (even_base, odd_base, zero), offsets['run'][p] = start of the run
+    code ending at p, and offsets['end'], in bytes from the base (the instruction after s_getpc)."""
     lines = [f"s_load_dwordx16 s[{ST0}:{ST0 + 15}], %[desc], 0x0",
              f"s_load_dwordx16 s[{ST0 + 16}:{ST0 + 31}], %[desc], 0x40",
              f"s_load_dwordx16 s[{ST0 + 32}:{ST0 + 47}], %[desc], 0x80",
              f"s_mov_b32 s{SMASK}, 0xffff",
              f"v_mov_b32_e32 v{VINF}, 0x7c007c00",
-             f"v_mov_b32_e32 v{VS0}, %[saddr]",
-             f"v_add_u32_e32 v{VS1}, {21 * ROW_BYTES}, %[saddr]",
-             f"v_add_u32_e32 v{VS2}, {42 * ROW_BYTES}, %[saddr]",
              f"s_mul_i32 s{STMP}, %[skip], {HEADER_BYTES}",
              "s_waitcnt lgkmcnt(0)",
              f"s_getpc_b64 s[{SBASE}:{SBASE + 1}]"]
@@ -190,31 +197,32 @@ def block_compute():
     for u in range(UMAX, 0, -1):
         emit(header(u))
     assert pos == 16 + UMAX * HEADER_BYTES
-    offsets = {}
+    offsets = {"run": {}}
     for u in range(UMAX, 0, -1):
-        # after output u: if u is even, entries u and u+1 are both final and go to LDS
-        nxt = header(u - 1, store_pair=(u // 2 if u % 2 == 0 else None)) if u > 1 else None
+        nxt = header(u - 1)
         je, jo = jmax_even(u), jmax_odd(u)
         even_base = pos
         if je >= 0:
             for J in range(je, 0, -1):
                 emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"])
             emit([f"v_pk_minimum3_f16 {R(u)}, v{VACC}, {R(u)}, {R(u - 1)}"])
-            emit(nxt if nxt else ["s_branch ppo_pair_end"])
+            emit(nxt)
         odd_base = pos
         for J in range(jo, 0, -1):
             emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"])
         emit([f"v_pk_min_u16 {R(u)}, v{VACC}, {R(u)}"])
-        emit(nxt if nxt else ["s_branch ppo_pair_end"])
+        emit(nxt)
         zero = pos
         emit([f"v_mov_b32_e32 {R(u)}, v{VINF}"])
-        if nxt:
-            emit(nxt)
+        emit(nxt)
         offsets[u] = (even_base if je >= 0 else None, odd_base, zero)
+    for p in range(2, UMAX + 1):
+        offsets["run"][p] = pos
+        for x in range(emit_first(p), p + 1):
+            emit([f"v_pk_min_u16 {R(x)}, {R(x - 1)}, {R(x)}"])
+        emit(header(p - 1))
     offsets["end"] = pos
     body.append("ppo_pair_end:")
-    a, off = addr_for(0, f"v{VS0}", f"v{VS1}", f"v{VS2}")
-    body.append(f"ds_write_b64 {a}, {RP(0)} offset:{off}")   # entry 1 (with the dummy entry 0)
     return lines + body, offsets
 
 
@@ -246,6 +254,12 @@ def entry_offset(offsets, u, w):
     return even_base + 8 * (jmax_even(u) - (w // 2 - 1))
 
 
+def run_offset(offsets, a, p):
+    """byte offset at which the run code ending at p is entered so that positions a .. p are worked."""
+    assert emit_first(p) <= a <= p
+    return offsets["run"][p] + 8 * (a - emit_first(p))
+
+
 def c_string(lines):
     return " \\\n".join('    "' + ln + '\\n"' for ln in lines)
 
@@ -273,12 +287,22 @@ def main():
     ev = [0] + [(offsets[u][0] or 0) // 4 for u in range(1, UMAX + 1)]
     od = [0] + [offsets[u][1] // 4 for u in range(1, UMAX + 1)]
     ze = [0] + [offsets[u][2] // 4 for u in range(1, UMAX + 1)]
-    out += ["namespace ppo {",
+    rn = [0, 0] + [offsets["run"][p] // 4 for p in range(2, UMAX + 1)]
+    out += ["#ifndef PPO_HD",
+            "#ifdef __HIPCC__",
+            "#define PPO_HD __host__ __device__",
+            "#else",
+            "#define PPO_HD",
+            "#endif",
+            "#endif",
+            "namespace ppo {",
+            f"constexpr int kPairRunCap = {ECAP};     // outputs one piece of run code takes",
+            f"constexpr int kPairSlots16 = {NSLOT};   // 16-bit entries of a row's table; position u reads entry (u - 1) mod {NSLOT}",
             "// Where output u of a row with a window of w entries (0 <= w <= u) starts: offset of that instruction from",
             "// the base of the COMPUTE block, in units of four bytes.  Even w: the even chain of u, entered so that",
             "// w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps; w = 0: the",
             "// instruction that writes +inf.",
-            "__host__ __device__ inline uint32_t pair_entry_offset(uint32_t u, uint32_t w) {",
+            "PPO_HD inline uint32_t pair_entry_offset(uint32_t u, uint32_t w) {",
             "    constexpr uint16_t even_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ev)) + "};",
             "    constexpr uint16_t odd_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, od)) + "};",
             "    constexpr uint16_t zero[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ze)) + "};",
@@ -286,8 +310,14 @@ def main():
             "    if (w & 1u) return odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
             "    return even_base[u] + 2u * ((u - 2u) / 2u - (w / 2u - 1u));",
             "}",
-            f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block: entry 1 is stored, then the block is left",
-            f"constexpr uint32_t kPairEndNoStore = {offsets['end'] // 4 + 2};   // past that store (for a caller that has not computed entry 1)",
+            "// Where the run code ending at position p is entered so that the positions a .. p are worked, each the",
+            "// minimum of the output below it and its own entry (2 <= a <= p, p - a < kPairRunCap).",
+            "PPO_HD inline uint32_t pair_run_offset(uint32_t a, uint32_t p) {",
+            "    constexpr uint16_t run_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, rn)) + "};",
+            "    const uint32_t first = p + 1u > (uint32_t)kPairRunCap + 2u ? p + 1u - (uint32_t)kPairRunCap : 2u;",
+            "    return run_base[p] + 2u * (a - first);",
+            "}",
+            f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block",
             "}  // namespace ppo", ""]
     path = os.path.join(HERE, "ppo_pair_asm.h")
     with open(path, "w") as f:
@@ -295,8 +325,11 @@ def main():
     # the same offsets for the build step's check of the compiled code
     import json
     with open(os.path.join(HERE, "ppo_pair_layout.json"), "w") as f:
-        json.dump({"umax": UMAX, "rb": RB, "vtop": VTOP, "vacc": VACC, "vinf": VINF, "sbase": SBASE,
+        json.dump({"umax": UMAX, "rb": RB, "vtop": VTOP, "vacc": VACC, "vinf": VINF, "sbase": SBASE, "ecap": ECAP,
+                   "nslot": NSLOT, "st0": ST0, "stmp": STMP, "smask": SMASK,
                    "entries": {str(u): {str(w): entry_offset(offsets, u, w) for w in range(0, u + 1)} for u in range(1, UMAX + 1)},
+                   "runs": {str(p): {str(a): run_offset(offsets, a, p) for a in range(emit_first(p), p + 1)}
+                            for p in range(2, UMAX + 1)},
                    "end": offsets["end"]}, f)
     print("wrote", path, "compute block", offsets["end"], "bytes")
 

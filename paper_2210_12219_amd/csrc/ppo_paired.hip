@@ -12,8 +12,10 @@
 //     g_s[i] = max(D_{s-1}[i], q_{pi_{s-1},pi_s}[i-1])       at u = i - s + 1
 // and D_s[e] = min over i in [max(lo[pi_s][e], s), e-1] of g_s[i] is the minimum of the w = e - max(lo, s)
 // entries u, u-1, .., u-w+1 with u = e - s; it replaces entry u in place (the outputs are worked from the
-// highest u down).  The chains that do this are generated code entered by computed jumps (ppo_pair_asm.h);
-// the jump targets of a (node, row) come from a table written by pair_tables_kernel below.
+// highest u down).  Outputs whose windows start at the same entry form a run: a chain folds the window of the
+// lowest, and each one above it is the minimum of the output below it and its own entry.  Chains and run steps
+// are generated code entered by computed jumps (ppo_pair_asm.h); the jump targets of a (node, row) come from a
+// table written by pair_tables_kernel below (ppo_pair_program.h).
 //
 // Which orderings a lane holds changes from row to row (the node at the row must be the wave's), so between
 // rows the entries go through LDS: slot = pair, one dword per entry, entry-major, the bank of a slot being its
@@ -22,6 +24,7 @@
 // before the row of position 4 of the six: only upper halves move (see gen_pair_tables.py).
 #include "ppo_common.h"
 #include "ppo_pair_asm.h"
+#include "ppo_pair_program.h"
 #include "ppo_pair_tables.h"
 
 namespace ppo {
@@ -60,48 +63,38 @@ bool paired_supported(int L, int k) {
 }
 
 // spare slot that holds the first DP row of node j (both halves the same); the spare slots 30, 31, 62, 63 are the
-// idle lanes'; one more takes the stores of rows that are not wanted in LDS
+// idle lanes'
 __host__ __device__ inline uint32_t pair_d0_slot(int j) { return (uint32_t)(2 + j / 2) * 32u + 30u + (uint32_t)(j & 1); }
-constexpr uint32_t kPairDummySlot = 8u * 32u + 30u;
 // dword of entry u of a slot: entries 2h and 2h+1 side by side, the next pair of entries 2 * kPairSlots dwords on
 __host__ __device__ inline uint32_t pair_entry_dword(uint32_t slot, uint32_t u) { return (u >> 1) * (2u * kPairSlots) + slot * 2u + (u & 1u); }
 
 // ---------------------------------------------------------------------------------------------
-// Entry offsets: for node j and DP row s = 1..k-1, where the chain of each output starts.  Row k-1 needs
-// D[L] only: its highest output is computed and the one below it is sent to the end of the block.
+// The jump table of every (node, DP row s = 1 .. k-1): one thread each (ppo_pair_program.h).
 // ---------------------------------------------------------------------------------------------
-__host__ __device__ inline uint32_t pair_row_offset(int L, int k, int s, uint32_t u, uint32_t lo_e) {
-    const uint32_t top = (uint32_t)(L - k + 1);   // highest output index, NE - 1
-    if (u > top) return kPairEnd;
-    if (s == k - 1 && u != top) return kPairEnd;
-    const uint32_t e = u + (uint32_t)s;
-    const uint32_t first = lo_e > (uint32_t)s ? lo_e : (uint32_t)s;
-    const uint32_t w = e > first ? e - first : 0u;   // e - s = u bounds it
-    return pair_entry_offset(u, w);
-}
-
-__global__ __launch_bounds__(256) void pair_tables_kernel(Layout y, unsigned char* __restrict__ ws) {
-    const int L = y.L, k = y.k, inst = blockIdx.x;
+static_assert(kPairTableDwords * 2 == kPairSlots16, "two 16-bit entries per dword of the table");
+constexpr int kPairTableThreads = 256;
+__global__ __launch_bounds__(kPairTableThreads) void pair_tables_kernel(Layout y, unsigned char* __restrict__ ws) {
+    // the windows of all nodes, then the tables as they are built, 16 bits an entry
+    __shared__ unsigned char lo_s[PPO_MAX_K * (PPO_MAX_L + 1)];
+    __shared__ __align__(4) uint16_t entry_s[PPO_MAX_K * (PPO_MAX_K - 1) * kPairSlots16];
+    const int L = y.L, k = y.k, inst = blockIdx.x, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
     const unsigned char* lo = base + y.lo_off;
     uint32_t* pt = reinterpret_cast<uint32_t*>(base + y.pt_off);
-    const int total = k * (k - 1) * kPairTableDwords;
-    for (int idx = threadIdx.x; idx < total; idx += 256) {
-        const int x = idx % kPairTableDwords, s = (idx / kPairTableDwords) % (k - 1) + 1, j = idx / (kPairTableDwords * (k - 1));
-        uint32_t v = 0;
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t u = (uint32_t)(2 * x + 1 + h);
-            const uint32_t e = u + (uint32_t)s;
-            const uint32_t lo_e = e <= (uint32_t)L ? lo[j * (L + 1) + e] : 0u;
-            v |= pair_row_offset(L, k, s, u, lo_e) << (16 * h);
-        }
-        pt[idx] = v;
+    for (int i = tid; i < k * (L + 1); i += kPairTableThreads) lo_s[i] = lo[i];
+    __syncthreads();
+    for (int idx = tid; idx < k * (k - 1); idx += kPairTableThreads) {
+        const int j = idx / (k - 1), s = idx - j * (k - 1) + 1;
+        pair_row_program(L, k, s, lo_s + j * (L + 1), entry_s + idx * kPairSlots16);
     }
+    __syncthreads();
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(entry_s);
+    for (int i = tid; i < k * (k - 1) * kPairTableDwords; i += kPairTableThreads) pt[i] = src[i];
 }
 
 hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream) {
     if (y.k < 2) return hipSuccess;
-    hipLaunchKernelGGL(pair_tables_kernel, dim3(n_inst), dim3(256), 0, stream, y, static_cast<unsigned char*>(ws));
+    hipLaunchKernelGGL(pair_tables_kernel, dim3(n_inst), dim3(kPairTableThreads), 0, stream, y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
 
@@ -124,8 +117,8 @@ __device__ __forceinline__ void pair_store(uint32_t addr, uint32_t skip) {
 __device__ __forceinline__ void pair_qmax(uint32_t qaddr) {
     asm volatile(PPO_PAIR_QMAX_ASM : : [qaddr] "v"(qaddr) : PPO_PAIR_CLOBBERS);
 }
-__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip, uint32_t saddr) {
-    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip), [saddr] "v"(saddr) : PPO_PAIR_CLOBBERS);
+__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip) {
+    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
 }
 __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
     uint32_t res;
@@ -184,7 +177,6 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
         const uint32_t s = ((r < 3 ? lc0 >> (9 * r) : lc1 >> (9 * (r - 3))) & 511u);
         return buf_addr + s * 8u;
     };
-    const uint32_t dummy_addr = buf_addr + kPairDummySlot * 8u;
     // first DP rows of all nodes into their spare slots, and +inf into the spare slots of the idle lanes
     {
         const uint32_t* d0src = reinterpret_cast<const uint32_t*>(base + y.d0_off);
@@ -297,10 +289,10 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 pair_qmax(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u);
                 if (s == k - 1) pair_arrive(&sync->done);   // the last row is in registers: the buffer can go on
                 const uint32_t* desc = pt + (uint32_t)__builtin_amdgcn_readfirstlane((node * (k - 1) + (s - 1)) * kPairTableDwords);
-                // the outputs go to LDS as they are completed where the next row has to fetch them from other lanes
-                // (rows of positions 1 .. 4), else to a spare slot
-                pair_compute(desc, skip, (r >= 1 && s < k - 1) ? slot_addr(r) : dummy_addr);
+                pair_compute(desc, skip);
             }
+            // the row goes to LDS where the next row has to fetch it from other lanes (rows of positions 0 .. 4)
+            if (r >= 1 && s < k - 1) pair_store(slot_addr(r), skip_pairs);
             if (r == 0 && s < k - 1) {
                 // the group's first row in LDS waits for the buffer: every wave of the group before it has fetched its last row
                 pair_spin_until(&sync->done, gi * (uint32_t)kPairWaves);

@@ -375,7 +375,7 @@ def test_grouped_kernel_behind_the_switch(ppo):
 
 
 def test_issue_probe_runs(ppo):
-    """The measurement aid launches and keeps its work: every lane writes the sum of its four accumulators."""
+    """The measurement aid launches and keeps its work: every lane writes the sum of its eight accumulators."""
     import torch
     for wps in (1, 4):
         sink = torch.full((256 * 256 * wps,), -1, dtype=torch.int32, device="cuda:0")
@@ -398,7 +398,7 @@ def test_issue_probe_runs(ppo):
             return out
 
         want = np.zeros((256, 256 * wps), np.uint32)
-        for mul in (1, 3, 5, 7):
+        for mul in (1, 3, 5, 7, 11, 13, 17, 19):
             want = (want + clamp((tid * np.uint32(mul)).astype(np.uint32))).astype(np.uint32)
         assert np.array_equal(got, want)
 
