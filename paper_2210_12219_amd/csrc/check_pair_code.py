@@ -6,7 +6,8 @@ at offsets computed from instruction sizes.  Both rest on what the toolchain emi
 code it did emit:
   1. in the compiler's assembly of the kernel, no instruction outside the blocks touches a reserved register;
   2. in the disassembly of the assembled object, the instruction at every entry offset of ppo_pair_layout.json is
-     the chain step or run step the table means (right chain, right depth, right registers), every header
+     the chain or run step the table means and is followed by the steps and the header it should be (right
+     chain, right depth, right registers), every header
      reads the table entry of the position below the code it follows, and the block ends where the table says.
 """
 import json
@@ -67,58 +68,51 @@ def check_entry_offsets(disasm_text, lay):
     bases = [a for a, t in instr.items() if t == f"s_getpc_b64 s[{sb}:{sb + 1}]"]
     assert len(bases) == 1, f"expected one base instruction, found {len(bases)}"
     base = bases[0] + 4
-    rb, vacc, vinf = lay["rb"], lay["vacc"], lay["vinf"]
+    rb, vinf = lay["rb"], lay["vinf"]
+    st0, nslot = lay["st0"], lay["nslot"]
     R = lambda u: f"v{rb + u}"
+
+    def header_text(position):
+        """first instruction of a header that reads the table entry of `position`"""
+        slot = (position - 1) % nslot
+        x, hi = slot // 2, slot & 1
+        return (f"s_lshr_b32 s{lay['stmp']}, s{st0 + x}, 16" if hi
+                else f"s_and_b32 s{lay['stmp']}, s{st0 + x}, s{lay['smask']}")
+
+    def expect(addr, want, what):
+        got = instr.get(addr)
+        assert got == want, f"{what} at +{addr - base}: found `{got}`, expected `{want}`"
+
     checked = 0
     for us, by_w in lay["entries"].items():
         u = int(us)
         for ws, off in by_w.items():
             w = int(ws)
-            got = instr.get(base + off)
+            what = f"entry u={u} w={w}"
             if w == 0:
-                want = f"v_mov_b32_e32 {R(u)}, v{vinf}"
+                expect(base + off, f"v_mov_b32_e32 {R(u)}, v{vinf}", what)
+                expect(base + off + 4, header_text(u - 1), what + " (header)")
             elif w & 1:
-                J = (w - 1) // 2
-                want = (f"v_pk_minimum3_f16 v{vacc}, v{vacc}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}" if J
-                        else f"v_pk_min_u16 {R(u)}, v{vacc}, {R(u)}")
+                J = (w - 1) // 2      # steps to run; then the header of the position below
+                for i in range(J, 0, -1):
+                    expect(base + off + 8 * (J - i), f"v_pk_minimum3_f16 {R(u)}, {R(u)}, {R(u - 2 * i + 1)}, {R(u - 2 * i)}", what)
+                expect(base + off + 8 * J, header_text(u - 1), what + " (header)")
             else:
-                J = w // 2 - 1
-                want = (f"v_pk_minimum3_f16 v{vacc}, v{vacc}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}" if J
-                        else f"v_pk_minimum3_f16 {R(u)}, v{vacc}, {R(u)}, {R(u - 1)}")
-            assert got == want, f"entry u={u} w={w} at +{off}: found `{got}`, expected `{want}`"
+                J = (w - 2) // 2
+                for i in range(J, 0, -1):
+                    expect(base + off + 8 * (J - i), f"v_pk_minimum3_f16 {R(u)}, {R(u)}, {R(u - 2 * i)}, {R(u - 2 * i - 1)}", what)
+                expect(base + off + 8 * J, f"v_pk_min_u16 {R(u)}, {R(u)}, {R(u - 1)}", what)
+                expect(base + off + 8 * J + 8, header_text(u - 1), what + " (header)")
             checked += 1
-    # the run code: entered at position a of the piece ending at p, the first instruction folds entry a into the
-    # output below it; the piece's header follows its last instruction
+    # the run code: entered at position a of the piece ending at p, one instruction per position up to p, each the
+    # minimum of the output below and the position's own entry; then the header of position p - 1
     for ps, by_a in lay["runs"].items():
+        p = int(ps)
         for as_, off in by_a.items():
             a = int(as_)
-            got = instr.get(base + off)
-            want = f"v_pk_min_u16 {R(a)}, {R(a - 1)}, {R(a)}"
-            assert got == want, f"run code p={ps} a={a} at +{off}: found `{got}`, expected `{want}`"
+            expect(base + off, f"v_pk_min_u16 {R(a)}, {R(a - 1)}, {R(a)}", f"run code p={p} a={a}")
             checked += 1
-        p = int(ps)
-        got = instr.get(base + by_a[ps] + 8)
-        assert got == f"v_mov_b32_e32 v{vacc}, v{vinf}", f"no header after the run code ending at {p}: `{got}`"
-    # every header reads the table entry of the position below the code it follows: the instruction after the
-    # last one of a chain (8 bytes on) starts a header whose second instruction names that entry's register
-    st0, nslot = lay["st0"], lay["nslot"]
-
-    def header_reads(addr, position):
-        slot = (position - 1) % nslot
-        x, hi = slot // 2, slot & 1
-        want = (f"s_lshr_b32 s{lay['stmp']}, s{st0 + x}, 16" if hi
-                else f"s_and_b32 s{lay['stmp']}, s{st0 + x}, s{lay['smask']}")
-        assert instr.get(addr) == f"v_mov_b32_e32 v{vacc}, v{vinf}" and instr.get(addr + 4) == want, \
-            f"header for position {position} at +{addr - base}: `{instr.get(addr)}` / `{instr.get(addr + 4)}`, expected `{want}`"
-
-    for us, by_w in lay["entries"].items():
-        u = int(us)
-        header_reads(base + by_w["1"] + 8, u - 1)    # after the odd chain's last instruction
-        header_reads(base + by_w["0"] + 4, u - 1)    # after the +inf
-        if "2" in by_w:
-            header_reads(base + by_w["2"] + 8, u - 1)
-    for ps, by_a in lay["runs"].items():
-        header_reads(base + by_a[ps] + 8, int(ps) - 1)
+        expect(base + by_a[ps] + 8, header_text(p - 1), f"run code p={p} (header)")
     # the block ends right after the header of the last piece of run code
     assert instr.get(base + lay["end"] - 4, "").startswith("s_setpc_b64"), "end of the block is not where the table says"
     assert base + lay["end"] in instr, "no instruction at the end of the block"

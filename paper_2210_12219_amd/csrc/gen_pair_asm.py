@@ -9,12 +9,13 @@ lanes and both halves: every ordering of the wave has the same node at this row)
 place; the outputs are worked from the highest u down, so every input is still there when it is needed.
 
 The code of a row is unrolled over u.  For every u there are two descending chains of packed three-input
-minima (two new entries per instruction), one for even and one for odd w, each ending in the instruction that
-writes v[RB + u]; a chain is entered at the step that leaves exactly w entries to fold, by a computed jump
-whose target comes from a table the precompute kernel wrote for this (node, row): 16-bit offsets from the
-block's base in units of four bytes, two per dword, read into scalar registers.  After the last instruction of
-a chain a header follows (a copy of it after each chain), which starts the accumulator at +inf and jumps to
-whatever the table names for the position below.  w = 0 (no legal segment start) writes +inf.
+minima (two more entries per instruction), one for even and one for odd w, that fold the entries below u into
+v[RB + u] itself (its own entry always belongs to the window); a chain is entered at the step that leaves
+exactly the w - 1 other entries to fold, by a computed jump whose target comes from a table the precompute
+kernel wrote for this (node, row): 16-bit offsets from the block's base in units of four bytes, two per dword,
+read into scalar registers.  After the last instruction of a chain a header follows (a copy of it after each
+chain), which jumps to whatever the table names for the position below; a window of one entry is that header
+itself.  w = 0 (no legal segment start) writes +inf.
 
 Runs.  Consecutive outputs whose windows start at the same entry (the memory rule lets the window grow with the
 segment end until a heavy layer pushes its start up) are prefix minima of one another: only the lowest output
@@ -129,8 +130,8 @@ def block_qmax():
     (lower half) and 2j+2 (upper half).  The loaded entries must have arrived: waits for everything first."""
     lines = []
     for batch in range(2):
-        for j in range(24 * batch, 24 * batch + 24):
-            lines.append(f"ds_read_b32 v{VQ + j % 24}, %[qaddr] offset:{4 * j}")
+        for j in range(24 * batch, 24 * batch + 24, 2):   # two dwords per read (offsets in dwords)
+            lines.append(f"ds_read2_b32 v[{VQ + j % 24}:{VQ + j % 24 + 1}], %[qaddr] offset0:{j} offset1:{j + 1}")
         lines.append("s_waitcnt lgkmcnt(0)")
         for j in range(24 * batch, 24 * batch + 24):
             for h in range(2):
@@ -141,25 +142,27 @@ def block_qmax():
 
 
 def header(u):
-    """what follows the code of position u + 1 (or starts the row at its highest position u): accumulator +inf,
-    jump to the entry the table names for position u (0 <= u <= UMAX)."""
+    """what follows the code of position u + 1 (or starts the row at its highest position u): jump to the entry
+    the table names for position u (0 <= u <= UMAX)."""
     slot = (u - 1) % NSLOT
     x, hi = slot // 2, slot & 1
     first = f"s_lshr_b32 s{STMP}, s{ST0 + x}, 16" if hi else f"s_and_b32 s{STMP}, s{ST0 + x}, s{SMASK}"
-    return [f"v_mov_b32_e32 v{VACC}, v{VINF}", first,
+    return [first,
             f"s_lshl2_add_u32 s{SPC}, s{STMP}, s{SBASE}",
             f"s_addc_u32 s{SPC + 1}, s{SBASE + 1}, 0",
             f"s_setpc_b64 s[{SPC}:{SPC + 1}]"]
 
 
-HEADER_BYTES = 20
+HEADER_BYTES = 16
 
 
 def jmax_even(u):
-    return (u - 2) // 2 if u >= 2 else -1     # steps before the last instruction of the even chain
+    """three-input steps of the even chain (each folds entries u - 2i and u - 2i - 1, i = 1 ..)"""
+    return max((u - 2) // 2, 0)
 
 
 def jmax_odd(u):
+    """three-input steps of the odd chain (each folds entries u - 2i + 1 and u - 2i)"""
     return (u - 1) // 2
 
 
@@ -201,21 +204,21 @@ def block_compute():
     for u in range(UMAX, 0, -1):
         nxt = header(u - 1)
         je, jo = jmax_even(u), jmax_odd(u)
-        even_base = pos
-        if je >= 0:
+        even_base = None
+        if u >= 2:
+            even_base = pos
             for J in range(je, 0, -1):
-                emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"])
-            emit([f"v_pk_minimum3_f16 {R(u)}, v{VACC}, {R(u)}, {R(u - 1)}"])
+                emit([f"v_pk_minimum3_f16 {R(u)}, {R(u)}, {R(u - 2 * J)}, {R(u - 2 * J - 1)}"])
+            emit([f"v_pk_min_u16 {R(u)}, {R(u)}, {R(u - 1)}"])
             emit(nxt)
         odd_base = pos
         for J in range(jo, 0, -1):
-            emit([f"v_pk_minimum3_f16 v{VACC}, v{VACC}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"])
-        emit([f"v_pk_min_u16 {R(u)}, v{VACC}, {R(u)}"])
+            emit([f"v_pk_minimum3_f16 {R(u)}, {R(u)}, {R(u - 2 * J + 1)}, {R(u - 2 * J)}"])
         emit(nxt)
         zero = pos
         emit([f"v_mov_b32_e32 {R(u)}, v{VINF}"])
         emit(nxt)
-        offsets[u] = (even_base if je >= 0 else None, odd_base, zero)
+        offsets[u] = (even_base, odd_base, zero)
     for p in range(2, UMAX + 1):
         offsets["run"][p] = pos
         for x in range(emit_first(p), p + 1):
@@ -250,8 +253,8 @@ def entry_offset(offsets, u, w):
     if w == 0:
         return zero
     if w & 1:
-        return odd_base + 8 * (jmax_odd(u) - (w - 1) // 2)
-    return even_base + 8 * (jmax_even(u) - (w // 2 - 1))
+        return odd_base + 8 * (jmax_odd(u) - (w - 1) // 2)     # (w - 1) / 2 steps, then the header
+    return even_base + 8 * (jmax_even(u) - (w - 2) // 2)       # (w - 2) / 2 steps, then the two-input minimum
 
 
 def run_offset(offsets, a, p):
@@ -300,15 +303,15 @@ def main():
             f"constexpr int kPairSlots16 = {NSLOT};   // 16-bit entries of a row's table; position u reads entry (u - 1) mod {NSLOT}",
             "// Where output u of a row with a window of w entries (0 <= w <= u) starts: offset of that instruction from",
             "// the base of the COMPUTE block, in units of four bytes.  Even w: the even chain of u, entered so that",
-            "// w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps; w = 0: the",
-            "// instruction that writes +inf.",
+            "// w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps (w = 1: the",
+            "// header that follows it); w = 0: the instruction that writes +inf.",
             "PPO_HD inline uint32_t pair_entry_offset(uint32_t u, uint32_t w) {",
             "    constexpr uint16_t even_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ev)) + "};",
             "    constexpr uint16_t odd_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, od)) + "};",
             "    constexpr uint16_t zero[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ze)) + "};",
             "    if (w == 0u) return zero[u];",
             "    if (w & 1u) return odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
-            "    return even_base[u] + 2u * ((u - 2u) / 2u - (w / 2u - 1u));",
+            "    return even_base[u] + 2u * ((u - 2u) / 2u - (w - 2u) / 2u);",
             "}",
             "// Where the run code ending at position p is entered so that the positions a .. p are worked, each the",
             "// minimum of the output below it and its own entry (2 <= a <= p, p - a < kPairRunCap).",
