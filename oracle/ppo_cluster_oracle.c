@@ -26,7 +26,8 @@
  *   ppo_cluster_oracle_bruteforce  every (sequence, cut vector) pair from the definition (tiny inputs);
  *   ppo_cluster_oracle_exhaustive  every sequence in lexicographic order, a plain windowed min-max
  *                                  chain DP for each;
- *   ppo_cluster_oracle_subset_dp   dynamic programme over sets of still-unused nodes.
+ *   ppo_cluster_oracle_subset_dp   dynamic programme over sets of still-unused nodes (n <= 20).
+ * The first two take clusters of up to 64 nodes: with few segments allowed (pmax) the sequences to walk are few.
  * Pins (tests/test_cluster_oracle_pins.py): agreement with the fixed-k oracle's definition route on
  * every node subset of every size (assembled in Python), closed forms (whole model on one node;
  * two nodes), monotonicity in pmax and in the cluster, a useless node changes nothing, relabelling,
@@ -44,7 +45,8 @@
 #define ORC_EDATA (-3)
 #define ORC_ENOMEM (-4)
 
-#define ORC_MAX_N 20
+#define ORC_MAX_N 64        /* routes that walk node sequences */
+#define ORC_MAX_N_SUBSETS 20 /* the route over sets of unused nodes keeps n 2^n rows */
 #define ORC_MAX_L 4096
 
 typedef struct {
@@ -310,6 +312,7 @@ int ppo_cluster_oracle_sequence(const float *t, const float *m, int L, const flo
  * n - |S| + 1 < pmax. */
 int ppo_cluster_oracle_subset_dp(const float *t, const float *m, int L, const float *M, const float *B, int n,
                                  int pmax, float *beta, int32_t *segs, int32_t *cuts, int32_t *order) {
+    if (n > ORC_MAX_N_SUBSETS) return ORC_ETOOBIG;
     cl_t I;
     int rc = cl_open(&I, t, m, L, M, B, n, pmax);
     if (rc) return rc;

@@ -218,3 +218,55 @@ def test_equals_fixed_k_when_every_node_is_needed():
                 assert got[1] == 0
             else:
                 assert as_tuple(got) == (bits(beta[0]), tuple(order[0]), tuple(cuts[0]))
+
+
+def test_large_clusters_with_few_segments():
+    """Clusters beyond the subset route's reach (Sec. IV goes to 50 devices): the two routes that walk node
+    sequences agree there, and the answer is the one of the small cluster that matters — every other node is too
+    small for any layer — carried through a relabelling (exact, ties included: a relabelling that keeps the order
+    of the nodes that matter keeps the lexicographically smallest sequence)."""
+    rng = np.random.default_rng(21)
+    for seed, (L, n0, n, pmax) in enumerate([(8, 5, 24, 2), (9, 6, 33, 3), (7, 4, 50, 3), (10, 5, 64, 2), (12, 6, 40, 4)]):
+        w = W.random_instances(seed=500 + seed, n_inst=3, L=L, k=n0, capacity_factor=2.0, quantised=seed % 2 == 1)
+        for i in range(w.n_inst):
+            t, m, M, B = inst(w, i)
+            m = m + np.float32(0.01)                      # every layer weighs something: a node of capacity 0 holds none
+            small = as_tuple(CO.subset_dp(t, m, M, B, min(pmax, n0)))
+            place = np.sort(rng.permutation(n)[:n0])      # where the nodes that matter sit, in their old order
+            M2 = np.zeros(n, np.float32)
+            M2[place] = M
+            B2 = rng.uniform(1.0, 100.0, size=(n, n)).astype(np.float32)
+            B2 = np.maximum(B2, B2.T)
+            np.fill_diagonal(B2, 0)
+            B2[np.ix_(place, place)] = B
+            big = as_tuple(CO.exhaustive(t, m, M2, B2, pmax))
+            if small is None:
+                assert big is None
+            else:
+                assert big == (small[0], tuple(int(place[j]) for j in small[1]), small[2])
+            if L <= 9 and pmax <= 3 and n <= 33:
+                assert as_tuple(CO.bruteforce(t, m, M2, B2, pmax)) == big
+            # the subset route says so itself when a cluster is beyond it
+            with pytest.raises(CO.OracleError):
+                CO.subset_dp(t, m, M2, B2, pmax)
+
+
+def test_large_cluster_where_every_node_counts():
+    """No decoys: 24 to 30 usable nodes, at most 2 or 3 segments; exhaustive = brute force, and no sampled sequence
+    is better."""
+    rng = np.random.default_rng(22)
+    for seed, (L, n, pmax) in enumerate([(8, 24, 2), (8, 26, 3), (9, 30, 2)]):
+        w = W.random_instances(seed=520 + seed, n_inst=2, L=L, k=n if n <= L else L, capacity_factor=1.0)
+        for i in range(w.n_inst):
+            t, m = w.t[i], w.m[i]
+            M = (rng.uniform(0.6, 0.95, size=n) * m.sum()).astype(np.float32)
+            B = rng.uniform(1.0, 100.0, size=(n, n)).astype(np.float32)
+            B = np.maximum(B, B.T)
+            np.fill_diagonal(B, 0)
+            a = as_tuple(CO.exhaustive(t, m, M, B, pmax))
+            assert a == as_tuple(CO.bruteforce(t, m, M, B, pmax))
+            assert a is not None
+            for _ in range(200):
+                p = int(rng.integers(1, pmax + 1))
+                seq = rng.permutation(n)[:p]
+                assert bits(CO.sequence_beta(t, m, M, B, seq)) >= a[0]
