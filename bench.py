@@ -101,27 +101,35 @@ def bench_approx(args, torch, ppo, workloads):
     optimum of the same instance, on the paper-shaped clusters (Sec. IV)."""
     rows = []
     t_exact = t_heur = 0.0
-    for n in (5, 10, 15, 20):
-        for cap in (32, 16):
+    for n, caps in ((5, (32, 16)), (10, (32, 16)), (15, (32, 16)), (20, (32, 16)), (30, (64, 32)), (50, (64, 32))):
+        for cap in caps:
             n_inst = 32 if n < 20 else 12
             w = workloads.cluster_geometric(n, cap, n_inst=n_inst, seed=500 + n)
             dev = ppo.to_device(w)
             kappa = torch.from_numpy(np.ascontiguousarray(w.M[:, 0])).cuda()
             torch.cuda.synchronize()
             c0 = time.perf_counter()
-            exact = ppo.ppo_solve_cluster(*dev)[0]
-            torch.cuda.synchronize()
-            c1 = time.perf_counter()
-            heur = ppo.ppo_place_kpath(dev[0], dev[1], kappa, dev[3], args.classes)[0]
+            heur, hsegs = ppo.ppo_place_kpath(dev[0], dev[1], kappa, dev[3], args.classes)[:2]
             joint = ppo.ppo_place_baseline(dev[0], dev[1], kappa, dev[3], ppo.PPO_BASELINE_JOINT)[0]
             torch.cuda.synchronize()
+            c1 = time.perf_counter()
+            if n <= ppo.PPO_CLUSTER_MAX_N:
+                limit = None          # any number of segments
+                exact = ppo.ppo_solve_cluster(*dev)[0]
+            else:
+                # beyond 20 nodes: the optimum over at most as many segments as the paper's partitioner made
+                limit = int(hsegs.max().item())
+                if not 1 <= limit <= ppo.PPO_CLUSTER_FEW_MAX_SEGMENTS:
+                    continue
+                exact = ppo.ppo_solve_cluster_few(*dev, max_segments=limit)[0]
+            torch.cuda.synchronize()
             c2 = time.perf_counter()
-            t_exact += c1 - c0
-            t_heur += c2 - c1
+            t_heur += c1 - c0
+            t_exact += c2 - c1
             e, h, j = (x.cpu().numpy().astype(np.float64) for x in (exact, heur, joint))
             ok = np.isfinite(e) & np.isfinite(h) & (e > 0)
             okj = ok & np.isfinite(j)
-            rows.append({"nodes": n, "capacity_mb": cap, "instances": int(ok.sum()),
+            rows.append({"nodes": n, "capacity_mb": cap, "instances": int(ok.sum()), "exact_max_segments": limit,
                          "heuristic_over_exact": float(np.mean(h[ok] / e[ok])) if ok.any() else None,
                          "heuristic_optimal_share": float(np.mean(h[ok] == e[ok])) if ok.any() else None,
                          "joint_over_exact": float(np.mean(j[okj] / e[okj])) if okj.any() else None})
@@ -131,7 +139,7 @@ def bench_approx(args, torch, ppo, workloads):
         "value": float(np.mean(ratios)), "unit": "ratio", "n_gpus": 1, "steps": 1, "warmup": 0,
         "ms_per_step": (t_exact + t_heur) * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "cluster_geometric: 50-layer chain, n = 5..20 devices of 32 and 16 MB, Shannon-rate links",
+        "config": {"workload": "cluster_geometric: 50-layer chain, n = 5..50 devices of 16 to 64 MB, Shannon-rate links",
                    "by_cluster": rows, "seconds_exact": t_exact, "seconds_heuristic_and_joint": t_heur},
         "roofline": None}), flush=True)
 

@@ -216,6 +216,24 @@ int ppo_solve_cluster(const float *t, const float *m, int L, const float *M, con
                       int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out, int32_t *order_out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same problem for LARGE clusters when FEW segments are allowed (the paper's evaluation, Sec. IV, places a
+ * handful of partitions on clusters of 5 to 50 devices): dynamic programming over the sets of nodes still to be
+ * used, of at most max_segments members: the sum over c <= max_segments of C(n, c) c rows per instance (11.6
+ * million at n = 50, max_segments = 5), in binary32.  Same result as ppo_solve_cluster wherever both apply.
+ *   1 <= n <= PPO_CLUSTER_FEW_MAX_N, 1 <= max_segments <= min(n, PPO_CLUSTER_FEW_MAX_SEGMENTS), L <= PPO_MAX_L,
+ *   and fewer than 2^31 rows per instance (else PPO_ETOOBIG; ppo_cluster_few_workspace_bytes returns 0)
+ *   arguments, outputs and uniqueness as for ppo_solve_cluster
+ * workspace: device, 256-byte aligned, at least ppo_cluster_few_workspace_bytes(L, n, max_segments, 1) bytes; it
+ * holds the tables of all instances and the rows of as many instances as fit (they are solved that many at a
+ * time); ppo_cluster_few_workspace_bytes(L, n, max_segments, n_inst) is the size at which all run together,
+ * capped at 16 GiB of rows (but never below one instance's). */
+#define PPO_CLUSTER_FEW_MAX_N 64
+#define PPO_CLUSTER_FEW_MAX_SEGMENTS 8
+size_t ppo_cluster_few_workspace_bytes(int L, int n, int max_segments, int n_inst);
+int ppo_solve_cluster_few(const float *t, const float *m, int L, const float *M, const float *B, int n, int n_inst,
+                          int max_segments, float *beta_out, int32_t *segs_out, int32_t *cuts_out,
+                          int32_t *order_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The paper's own partitioning step (Sec. III-B1, Alg. 1), for comparison with the joint optimum: cut the chain
  * into segments that each fit a node of capacity kappa so that the SUM of the transfer sizes at the cuts,
  * t[c_1 - 1] + ... + t[c_{p-1} - 1], is least (the cheapest root-to-leaf path of the partition graph).

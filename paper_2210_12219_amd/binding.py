@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(PKG, "libppo.so")
 PPO_OK, PPO_EINVAL, PPO_ETOOBIG, PPO_EHIP, PPO_ENOSPC = 0, -1, -2, -3, -4
 PPO_MAX_K, PPO_MAX_L = 12, 128
 PPO_CLUSTER_MAX_N = 20
+PPO_CLUSTER_FEW_MAX_N, PPO_CLUSTER_FEW_MAX_SEGMENTS = 64, 8
 PPO_KEY_NONE = 0xFFFFFFFFFFFFFFFF
 
 
@@ -66,6 +67,9 @@ def load() -> C.CDLL:
         lib.ppo_cluster_workspace_bytes.argtypes = [i, i, i]
         lib.ppo_cluster_workspace_bytes.restype = sz
         lib.ppo_solve_cluster.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
+        lib.ppo_cluster_few_workspace_bytes.argtypes = [i, i, i, i]
+        lib.ppo_cluster_few_workspace_bytes.restype = sz
+        lib.ppo_solve_cluster_few.argtypes = inst + [i, i, vp, vp, vp, vp, vp, sz, vp]
         lib.ppo_probe_valu.argtypes = [i, i, vp, vp]
         _lib = lib
     return _lib
@@ -352,6 +356,31 @@ def ppo_solve_cluster(t, m, M, B, max_segments=None, workspace=None, out=None, s
                                     n if max_segments is None else int(max_segments), _dev(beta, f32),
                                     _dev(segs, i32), C.c_void_p(cuts.data_ptr()), _dev(order, i32),
                                     C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    return beta, segs, cuts, order
+
+
+def ppo_cluster_few_workspace_bytes(L, n, max_segments, n_inst) -> int:
+    return int(load().ppo_cluster_few_workspace_bytes(L, n, max_segments, n_inst))
+
+
+def ppo_solve_cluster_few(t, m, M, B, max_segments, workspace=None, out=None, stream=None):
+    """Cluster form for large clusters and few segments (n <= 64, max_segments <= 8): outputs as ppo_solve_cluster."""
+    torch = _torch()
+    n_inst, L = t.shape
+    n = M.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    if workspace is None:
+        size = ppo_cluster_few_workspace_bytes(L, n, int(max_segments), n_inst)
+        workspace = torch.empty(max(size, 256), dtype=torch.uint8, device=t.device)   # a bad shape is the call's to refuse
+    if out is None:
+        out = (torch.empty(n_inst, dtype=f32, device=t.device), torch.empty(n_inst, dtype=i32, device=t.device),
+               torch.empty((n_inst, max(n - 1, 0)), dtype=i32, device=t.device),
+               torch.empty((n_inst, n), dtype=i32, device=t.device))
+    beta, segs, cuts, order = out
+    _check(load().ppo_solve_cluster_few(_dev(t, f32), _dev(m, f32), L, _dev(M, f32), _dev(B, f32), n, n_inst,
+                                        int(max_segments), _dev(beta, f32), _dev(segs, i32), C.c_void_p(cuts.data_ptr()),
+                                        _dev(order, i32), C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                        _stream(stream)))
     return beta, segs, cuts, order
 
 

@@ -14,6 +14,12 @@ hipError_t launch_traceback(const Layout&, int, const void*, const uint64_t*, fl
                             hipStream_t);
 void set_enumeration_variant(int);
 size_t cluster_tables_bytes(int L, int n);
+bool cluster_few_supported(int L, int n, int pmax);
+size_t cluster_few_tables_bytes(int L, int n, int pmax);
+size_t cluster_few_rows_bytes(int L, int n, int pmax);
+hipError_t launch_cluster_few_tables(const float*, const float*, const float*, const float*, int, int, int, int, void*, void*,
+                                     hipStream_t);
+hipError_t launch_cluster_few_solve(int, int, int, int, void*, void*, float*, int32_t*, int32_t*, int32_t*, hipStream_t);
 size_t cluster_rows_bytes(int L, int n);
 hipError_t launch_cluster_tables(const float*, const float*, const float*, const float*, int, int, int, void*,
                                  hipStream_t);
@@ -253,6 +259,56 @@ int ppo_solve_cluster(const float* t, const float* m, int L, const float* M, con
         PPO_HIP(ppo::launch_cluster_solve(L, n, cnt, pmax, false, ws + tables * first, row_area, nullptr, beta_out + first,
                                           segs_out + first, cuts_out ? cuts_out + first * (size_t)(n - 1) : nullptr,
                                           order_out + first * (size_t)n, s),
+                "cluster DP launch");
+    }
+    return PPO_OK;
+}
+
+static int check_few_shape(int L, int n, int max_segments, int n_inst) {
+    if (L < 1 || n < 1 || n_inst < 0 || max_segments < 1 || max_segments > n) return PPO_EINVAL;
+    if (L > PPO_MAX_L || n > PPO_CLUSTER_FEW_MAX_N) return PPO_ETOOBIG;
+    const int pmax = max_segments < L ? max_segments : L;
+    if (pmax > PPO_CLUSTER_FEW_MAX_SEGMENTS || !ppo::cluster_few_supported(L, n, pmax)) return PPO_ETOOBIG;
+    return PPO_OK;
+}
+
+size_t ppo_cluster_few_workspace_bytes(int L, int n, int max_segments, int n_inst) {
+    if (check_few_shape(L, n, max_segments, n_inst) != PPO_OK) return 0;
+    const int pmax = max_segments < L ? max_segments : L;
+    const size_t rows = ppo::cluster_few_rows_bytes(L, n, pmax);
+    size_t together = ((size_t)16 << 30) / rows;
+    if (together < 1) together = 1;
+    if (together > (size_t)n_inst) together = (size_t)n_inst;
+    if (together < 1) together = 1;
+    return ppo::cluster_few_tables_bytes(L, n, pmax) * (size_t)(n_inst > 0 ? n_inst : 1) + rows * together;
+}
+
+int ppo_solve_cluster_few(const float* t, const float* m, int L, const float* M, const float* B, int n, int n_inst,
+                          int max_segments, float* beta_out, int32_t* segs_out, int32_t* cuts_out, int32_t* order_out,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_few_shape(L, n, max_segments, n_inst);
+    if (rc) return rc;
+    if (n_inst == 0) return PPO_OK;
+    if (!t || !m || !M || !B || !beta_out || !segs_out || !order_out || (n > 1 && !cuts_out) || bad_workspace(workspace))
+        return PPO_EINVAL;
+    const int pmax = max_segments < L ? max_segments : L;
+    const size_t tables = ppo::cluster_few_tables_bytes(L, n, pmax), rows = ppo::cluster_few_rows_bytes(L, n, pmax);
+    if (workspace_bytes < tables * (size_t)n_inst + rows) return PPO_ENOSPC;
+    size_t together = (workspace_bytes - tables * (size_t)n_inst) / rows;
+    if (together > (size_t)kInstPerLaunch) together = (size_t)kInstPerLaunch;
+    if (together > (size_t)n_inst) together = (size_t)n_inst;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    unsigned char* row_area = ws + tables * (size_t)n_inst;   // tables is a multiple of 256
+    for (size_t first = 0; first < (size_t)n_inst; first += together) {
+        const int cnt = (int)(((size_t)n_inst - first < together) ? (size_t)n_inst - first : together);
+        // the tables kernel also writes the rows of the one-node sets, so it runs with the rows it belongs to
+        PPO_HIP(ppo::launch_cluster_few_tables(t + first * L, m + first * L, M + first * n, B + first * n * n, L, n, pmax, cnt,
+                                               ws + tables * first, row_area, s),
+                "cluster tables launch");
+        PPO_HIP(ppo::launch_cluster_few_solve(L, n, pmax, cnt, ws + tables * first, row_area, beta_out + first,
+                                              segs_out + first, cuts_out ? cuts_out + first * (size_t)(n - 1) : nullptr,
+                                              order_out + first * (size_t)n, s),
                 "cluster DP launch");
     }
     return PPO_OK;

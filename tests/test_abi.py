@@ -127,6 +127,32 @@ def test_cluster_entry_point_without_a_gpu(lib):
     assert lib.ppo_solve_cluster(p, p, 10, p, p, 3, 1, 2, null, p, p, p, p, 1 << 30, s) == binding.PPO_EINVAL
 
 
+def test_cluster_few_refuses_bad_arguments(lib):
+    p, null, s = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0)
+
+    def args(L, n, n_inst, pmax, ws=p, size=1 << 40):
+        return (p, p, L, p, p, n, n_inst, pmax, p, p, p, p, ws, size, s)
+
+    f = lib.ppo_solve_cluster_few
+    assert f(*args(0, 3, 1, 2)) == binding.PPO_EINVAL
+    assert f(*args(10, 0, 1, 1)) == binding.PPO_EINVAL
+    assert f(*args(10, 3, 1, 0)) == binding.PPO_EINVAL
+    assert f(*args(10, 3, 1, 4)) == binding.PPO_EINVAL
+    assert f(*args(10, 3, -1, 2)) == binding.PPO_EINVAL
+    assert f(*args(10, 65, 1, 2)) == binding.PPO_ETOOBIG
+    assert f(*args(129, 3, 1, 2)) == binding.PPO_ETOOBIG
+    assert f(*args(100, 30, 1, 9)) == binding.PPO_ETOOBIG
+    assert f(*args(100, 64, 1, 8)) == binding.PPO_ETOOBIG      # more than 2^31 rows
+    assert f(*args(5, 30, 1, 9, p, 64)) == binding.PPO_ENOSPC  # at most L = 5 segments: a legal shape
+    assert f(*args(10, 3, 0, 2, null, 0)) == binding.PPO_OK
+    assert f(*args(10, 3, 1, 2, null)) == binding.PPO_EINVAL
+    assert f(*args(10, 3, 1, 2, C.c_void_p(0x1010))) == binding.PPO_EINVAL
+    assert f(*args(10, 3, 1, 2, p, 64)) == binding.PPO_ENOSPC
+    assert f(p, p, 10, p, p, 3, 1, 2, null, p, p, p, p, 1 << 30, s) == binding.PPO_EINVAL
+    assert lib.ppo_cluster_few_workspace_bytes(100, 50, 5, 1) > 0
+    assert lib.ppo_cluster_few_workspace_bytes(100, 64, 8, 1) == 0
+
+
 def test_partition_and_front_end_refuse_bad_arguments(lib):
     p, null, s = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0)
     assert lib.ppo_min_sum_partition(p, p, 0, p, 1, p, p, p, s) == binding.PPO_EINVAL
