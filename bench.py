@@ -215,6 +215,44 @@ def bench_cluster(args, torch, ppo, workloads):
     print(json.dumps(result), flush=True)
 
 
+def bench_cluster_few(args, torch, ppo, workloads):
+    """Not the headline: whole exact solves per second of the cluster form for large clusters and few segments
+    (ppo_solve_cluster_few), on the paper's largest cluster shape by default (50 devices, 5 segments)."""
+    N = args.cluster
+    pmax = args.max_segments or 5
+    n_inst = args.cluster_instances or 1
+    # every node small enough that the chain needs the segments it is allowed
+    w = workloads.cluster_mixed(N, L=100, n_inst=n_inst, capacity_factor=0.8 / pmax)
+    dev = ppo.to_device(w)
+    ws = torch.empty(ppo.ppo_cluster_few_workspace_bytes(w.L, N, pmax, n_inst), dtype=torch.uint8, device="cuda:0")
+    out = None
+    for _ in range(args.warmup):
+        out = ppo.ppo_solve_cluster_few(*dev, max_segments=pmax, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = ppo.ppo_solve_cluster_few(*dev, max_segments=pmax, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    full = sum(math.comb(N, c) * c for c in range(1, max(pmax, 2)))
+    top = math.comb(N, pmax) * pmax if pmax > 1 else 0
+    # every full row (L binary32 entries, rounded up to even) is written once and read once by the level above,
+    # every entry of the last level is written once; the passes that rebuild the answer read them again
+    row_bytes = 4 * ((w.L + 1) & ~1)
+    alg_bytes = (2 * full * row_bytes + 4 * top) * n_inst
+    achieved = alg_bytes / (wall / args.steps) / 1e9
+    print(json.dumps({
+        "metric": f"clusters solved exactly/sec at n={N},L={w.L}, up to {pmax} segments (dynamic programming over sets of nodes still to be used)",
+        "value": n_inst / (wall / args.steps), "unit": "instances/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {n_inst} instances x (L={w.L}, n={N}), capacities for {pmax} segments, seed={w.seed}",
+                   "dp_rows_per_instance": full + top, "segments_found": [int(x) for x in out[1].cpu().numpy()[:8]]},
+        "roofline": {"bound": "hbm", "kernel": "few_level_kernel (all levels) + tables + answer passes",
+                     "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0, "traffic": None,
+                     "bytes_per_step": alg_bytes}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,9 +268,10 @@ def main():
                          "enumeration: a separate figure in instances per second")
     ap.add_argument("--cluster", type=int, default=0, metavar="N",
                     help="time ppo_solve_cluster on clusters of N nodes (hosting nodes and number of segments "
-                         "free; L=100, mixed capacities): a separate figure in instances per second")
+                         "free; L=100, mixed capacities): a separate figure in instances per second; N > 20: "
+                         "ppo_solve_cluster_few with --max-segments (default 5)")
     ap.add_argument("--cluster-instances", type=int, default=0, help="instances per step with --cluster")
-    ap.add_argument("--max-segments", type=int, default=0, help="with --cluster: most segments allowed (default N)")
+    ap.add_argument("--max-segments", type=int, default=0, help="with --cluster: most segments allowed (default N; 5 beyond 20 nodes)")
     ap.add_argument("--partition", action="store_true",
                     help="time ppo_min_sum_partition (the paper's own partitioning step) on 4096 chains of L=96: "
                          "a separate figure in instances per second")
@@ -258,6 +297,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     ppo.load()
+    if args.cluster > ppo.PPO_CLUSTER_MAX_N:
+        return bench_cluster_few(args, torch, ppo, workloads)
     if args.cluster:
         return bench_cluster(args, torch, ppo, workloads)
     if args.partition:
