@@ -30,8 +30,8 @@ so that the jumps walk the runs in this order and leave the block at the end.
 Blocks (each one `asm volatile` statement in the kernel; fixed registers, declared clobbered there):
   LOAD     entries NE-1..1 from the lane's slot in LDS (one dword per entry, 1536 bytes apart)
   LOADX    the same, then the upper half of every entry replaced by that of another slot (the pairing changes)
-  QMAX     entry u = max(entry u, code of t[u+s-2]/B of the lane's link), both halves the same link
-  COMPUTE  the chains and the run steps
+  ROW      entry u = max(entry u, code of t[u+s-2]/B of the lane's link), both halves the same link; then the
+           chains and the run steps (one block: the row's jump table is requested while the maxima are taken)
   STORE    entries NE-1..1 to the lane's slot
   EXTRACT  entry NE-1 to an output register
 Every block that works on a range of entries is entered at entry NE-1 by a computed jump (all entries of one
@@ -127,17 +127,36 @@ def block_store():
 
 def block_qmax():
     """%[qaddr]: LDS byte address of the lane's quotient dword for entries 1 and 2; dword j covers entries 2j+1
-    (lower half) and 2j+2 (upper half).  The loaded entries must have arrived: waits for everything first."""
-    lines = []
-    for batch in range(2):
-        for j in range(24 * batch, 24 * batch + 24, 2):   # two dwords per read (offsets in dwords)
+    (lower half) and 2j+2 (upper half).  First the row's jump table is requested (scalar loads, used by the
+    chains that follow in the same block), then the quotient dwords, 24 at a time; the second 24 are requested
+    in two halves while the maxima of the first are taken, into the registers those have just freed.  The first
+    wait is for everything (the loaded entries, the table: scalar loads return in any order); after it only LDS
+    reads are in flight, which return in order, so the later waits count them."""
+    lines = [f"s_load_dwordx16 s[{ST0}:{ST0 + 15}], %[desc], 0x0",
+             f"s_load_dwordx16 s[{ST0 + 16}:{ST0 + 31}], %[desc], 0x40",
+             f"s_load_dwordx16 s[{ST0 + 32}:{ST0 + 47}], %[desc], 0x80"]
+
+    def reads(first, count):
+        for j in range(first, first + count, 2):   # two dwords per read (offsets in dwords)
             lines.append(f"ds_read2_b32 v[{VQ + j % 24}:{VQ + j % 24 + 1}], %[qaddr] offset0:{j} offset1:{j + 1}")
-        lines.append("s_waitcnt lgkmcnt(0)")
-        for j in range(24 * batch, 24 * batch + 24):
+
+    def maxima(first, count):
+        for j in range(first, first + count):
             for h in range(2):
                 u = 2 * j + 1 + h
                 if u <= UMAX:
                     lines.append(f"v_pk_max_u16 {R(u)}, {R(u)}, v{VQ + j % 24} op_sel:[0,{h}] op_sel_hi:[1,{h}]")
+
+    reads(0, 24)
+    lines.append("s_waitcnt lgkmcnt(0)")
+    maxima(0, 12)
+    reads(24, 12)
+    maxima(12, 12)
+    reads(36, 12)
+    lines.append("s_waitcnt lgkmcnt(6)")
+    maxima(24, 12)
+    lines.append("s_waitcnt lgkmcnt(0)")
+    maxima(36, 12)
     return lines
 
 
@@ -174,13 +193,9 @@ def emit_first(p):
 def block_compute():
     """returns (lines, offsets) with offsets[u] = (even_base, odd_base, zero), offsets['run'][p] = start of the run
     code ending at p, and offsets['end'], in bytes from the base (the instruction after s_getpc)."""
-    lines = [f"s_load_dwordx16 s[{ST0}:{ST0 + 15}], %[desc], 0x0",
-             f"s_load_dwordx16 s[{ST0 + 16}:{ST0 + 31}], %[desc], 0x40",
-             f"s_load_dwordx16 s[{ST0 + 32}:{ST0 + 47}], %[desc], 0x80",
-             f"s_mov_b32 s{SMASK}, 0xffff",
+    lines = [f"s_mov_b32 s{SMASK}, 0xffff",
              f"v_mov_b32_e32 v{VINF}, 0x7c007c00",
              f"s_mul_i32 s{STMP}, %[skip], {HEADER_BYTES}",
-             "s_waitcnt lgkmcnt(0)",
              f"s_getpc_b64 s[{SBASE}:{SBASE + 1}]"]
     pos = 0   # bytes from the base
     body = []
@@ -282,7 +297,7 @@ def main():
            f"#define PPO_PAIR_CLOBBER_V {clobber_v}",
            f"#define PPO_PAIR_CLOBBER_S {clobber_s}, \"scc\"", ""]
     for name, lines in (("LOAD", block_load(False)), ("LOADX", block_load(True)), ("STORE", block_store()),
-                        ("QMAX", block_qmax()), ("COMPUTE", compute), ("EXTRACT", block_extract())):
+                        ("ROW", block_qmax() + compute), ("EXTRACT", block_extract())):
         out.append(f"#define PPO_PAIR_{name}_ASM \\")
         out.append(c_string(lines))
         out.append("")

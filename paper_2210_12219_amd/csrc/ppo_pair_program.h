@@ -49,6 +49,18 @@ PPO_HD inline void pair_row_program(int L, int k, int s, const unsigned char* lo
                 --u1;
             }
         }
+        // A run of several outputs whose whole window fits one piece of run code is worked as one ascending pass
+        // from the window's second entry: every entry on the way becomes the minimum of the window's entries up
+        // to it.  That changes entries below the run, but only into minima of entries that any lower window
+        // holding them holds as well (windows never start later than those above them), so the outputs below
+        // come out the same; and it takes one jump where the chain and the run code take two.
+        const int first = u2 - w2 + 1;   // lowest entry of the run's windows
+        if (u2 > u1 && u2 - first <= kPairRunCap) {
+            entry[pending] = (uint16_t)pair_run_offset((uint32_t)(first + 1), (uint32_t)u2);
+            pending = pair_slot16(u2 - 1);
+            u2 = u1 - 1;
+            continue;
+        }
         entry[pending] = (uint16_t)pair_entry_offset((uint32_t)u1, (uint32_t)window(u1));
         pending = pair_slot16(u1 - 1);
         for (int a = u1 + 1; a <= u2;) {

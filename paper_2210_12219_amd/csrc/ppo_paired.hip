@@ -114,11 +114,8 @@ __device__ __forceinline__ void pair_load_exchange(uint32_t addr, uint32_t addr2
 __device__ __forceinline__ void pair_store(uint32_t addr, uint32_t skip) {
     asm volatile("s_waitcnt lgkmcnt(0)\n" PPO_PAIR_STORE_ASM : : [addr] "v"(addr), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
 }
-__device__ __forceinline__ void pair_qmax(uint32_t qaddr) {
-    asm volatile(PPO_PAIR_QMAX_ASM : : [qaddr] "v"(qaddr) : PPO_PAIR_CLOBBERS);
-}
-__device__ __forceinline__ void pair_compute(const uint32_t* desc, uint32_t skip) {
-    asm volatile(PPO_PAIR_COMPUTE_ASM : : [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+__device__ __forceinline__ void pair_row(uint32_t qaddr, const uint32_t* desc, uint32_t skip) {
+    asm volatile(PPO_PAIR_ROW_ASM : : [qaddr] "v"(qaddr), [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
 }
 __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
     uint32_t res;
@@ -286,10 +283,9 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                     qrow = (uint32_t)(nA + nB) + ((lc2 >> (9 + 4 * (r - 1))) & 15u);
                     node = rnode(wave);
                 }
-                pair_qmax(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u);
-                if (s == k - 1) pair_arrive(&sync->done);   // the last row is in registers: the buffer can go on
                 const uint32_t* desc = pt + (uint32_t)__builtin_amdgcn_readfirstlane((node * (k - 1) + (s - 1)) * kPairTableDwords);
-                pair_compute(desc, skip);
+                pair_row(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u, desc, skip);
+                if (s == k - 1) pair_arrive(&sync->done);   // the last row has been fetched: the buffer can go on
             }
             // the row goes to LDS where the next row has to fetch it from other lanes (rows of positions 0 .. 4)
             if (r >= 1 && s < k - 1) pair_store(slot_addr(r), skip_pairs);
