@@ -52,3 +52,30 @@ def test_sums_agree_on_real_valued_instances():
             for c in reversed(cb):
                 total = float(t[c - 1]) + total
             assert total == sb and len(cb) == pb - 1
+
+
+def test_order_of_addition_is_immaterial_on_the_tested_inputs():
+    """The definition fixes an order of addition (from the chain's end) only so that the sum is defined when it
+    rounds.  The sizes used in the tests and workloads are binary32 values within a few binary orders of one
+    another: sums of up to 128 of them are exact in binary64, so any order gives the same bits.  Checked here
+    against the correctly rounded sum (math.fsum), for every set of cuts of the brute-force route."""
+    import itertools
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        L = int(rng.integers(2, 11))
+        t = rng.uniform(0.1, 30.0, L).astype(np.float32)
+        for p in range(1, L + 1):
+            for cuts in itertools.combinations(range(1, L), p - 1):
+                ordered = 0.0
+                for c in reversed(cuts):
+                    ordered = float(t[c - 1]) + ordered
+                forward = 0.0
+                for c in cuts:
+                    forward = forward + float(t[c - 1])
+                assert ordered == forward == math.fsum(float(t[c - 1]) for c in cuts)
+    # and at the sizes the GPU tests use: 128 sizes spanning three decimal orders
+    t = np.exp(rng.uniform(np.log(0.05), np.log(60.0), 128)).astype(np.float32)
+    back = 0.0
+    for x in t[::-1]:
+        back = float(x) + back
+    assert back == math.fsum(float(x) for x in t) == float(np.sum(t.astype(np.float64)))
