@@ -133,13 +133,14 @@ int ppo_solve_range(int L, int k, int n_inst, const void *workspace, size_t work
 
 /* Stage 2, the same result with less work (not the unit "full DPs evaluated" that ppo_solve_range stands
  * for).  The orderings are taken in groups that share their first k-6 nodes.  The DP rows of those nodes
- * are the same for the whole group and are computed once; and since no entry of a DP row is below the
- * least entry of the row before it (D_s[e] is a minimum of maxima over entries of D_{s-1}), a group
- * whose last shared row has no entry at or below the best beta already in best_key cannot hold the
- * optimum or a tie with it, and is skipped.  best_key ends up exactly as after ppo_solve_range over the
- * same range.  Shapes the grouped kernel does not take (k < 7, or L-k+2 > 96) are evaluated in full.
- *   skipped_groups  device, [n_inst], may be NULL: incremented by the number of groups (360 orderings
- *                   each) skipped for that instance; the caller zeroes it. */
+ * are the same for the whole group; and since no entry of a DP row is below the least entry of the row
+ * before it (D_s[e] is a minimum of maxima over entries of D_{s-1}), a group whose last shared row has no
+ * entry at or below the best beta already in best_key cannot hold the optimum or a tie with it, and is left
+ * after that row.  What is found is folded into best_key group by group, so that later groups see it.
+ * best_key ends up exactly as after ppo_solve_range over the same range.  Shapes neither the paired nor the
+ * grouped kernel takes (k < 7, or L-k+2 > 96) are evaluated in full.
+ *   skipped_groups  device, [n_inst], may be NULL: incremented by the number of orderings skipped for that
+ *                   instance, in units of 360; the caller zeroes it. */
 int ppo_solve_range_bounded(int L, int k, int n_inst, const void *workspace, size_t workspace_bytes,
                             uint64_t rank_begin, uint64_t rank_end, uint64_t *best_key, uint64_t *skipped_groups,
                             void *stream);

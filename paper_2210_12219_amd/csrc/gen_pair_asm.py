@@ -34,6 +34,7 @@ Blocks (each one `asm volatile` statement in the kernel; fixed registers, declar
            chains and the run steps (one block: the row's jump table is requested while the maxima are taken)
   STORE    entries NE-1..1 to the lane's slot
   EXTRACT  entry NE-1 to an output register
+  ROWMIN   the least entry of the row to an output register
 Every block that works on a range of entries is entered at entry NE-1 by a computed jump (all entries of one
 block have the same size).
 """
@@ -261,6 +262,14 @@ def block_extract():
     return lines
 
 
+def block_rowmin():
+    """%[res] = the least of entries NE-1 .. 1, half by half (%[skip] = UMAX - highest entry); waits for loads first"""
+    lines = ["s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 %[res], 0x7c007c00"] + entry_jump(8)
+    for u in range(UMAX, 0, -1):
+        lines.append(f"v_pk_min_u16 %[res], %[res], {R(u)}")
+    return lines
+
+
 def entry_offset(offsets, u, w):
     """byte offset of the instruction at which output u with a window of w entries starts."""
     assert 0 <= w <= u
@@ -297,7 +306,7 @@ def main():
            f"#define PPO_PAIR_CLOBBER_V {clobber_v}",
            f"#define PPO_PAIR_CLOBBER_S {clobber_s}, \"scc\"", ""]
     for name, lines in (("LOAD", block_load(False)), ("LOADX", block_load(True)), ("STORE", block_store()),
-                        ("ROW", block_qmax() + compute), ("EXTRACT", block_extract())):
+                        ("ROW", block_qmax() + compute), ("EXTRACT", block_extract()), ("ROWMIN", block_rowmin())):
         out.append(f"#define PPO_PAIR_{name}_ASM \\")
         out.append(c_string(lines))
         out.append("")

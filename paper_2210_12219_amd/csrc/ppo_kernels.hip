@@ -371,7 +371,8 @@ __global__ __launch_bounds__(64) void traceback_kernel(Layout y, const unsigned 
 bool paired_supported(int L, int k);
 hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream);
 hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
-                                   uint64_t* best_key, float* beta_export, hipStream_t stream);
+                                   uint64_t* best_key, float* beta_export, bool bounded, uint64_t* skipped_groups,
+                                   hipStream_t stream);
 
 hipError_t launch_precompute(const float* t, const float* m, const float* M, const float* B, const Layout& y,
                              int n_inst, void* ws, hipStream_t stream) {
@@ -404,7 +405,7 @@ void set_enumeration_variant(int v) { g_enumeration_variant.store(v, std::memory
 
 size_t enumerate_lds_bytes(const Layout& y) { return (size_t)y.dec_off + (size_t)(y.L + 1) * kEnumThreads * 2; }
 
-// shared_prefix asks for the grouped kernel's shared-prefix, bounded mode where that kernel applies; elsewhere
+// shared_prefix asks for the bounded mode of the paired or the grouped kernel where one of them applies; elsewhere
 // every ordering is evaluated in full
 hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
                             uint64_t* best_key, float* beta_export, bool shared_prefix, uint64_t* skipped_groups,
@@ -412,8 +413,9 @@ hipError_t launch_enumerate(const Layout& y, int n_inst, const void* ws, uint32_
     const uint32_t span = rank_end - rank_begin;
     if (span == 0 || n_inst == 0) return hipSuccess;
     const int variant = g_enumeration_variant.load(std::memory_order_relaxed);
-    if (variant == PPO_ENUM_AUTO && !shared_prefix && paired_supported(y.L, y.k))
-        return launch_enumerate_paired(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, stream);
+    if (variant == PPO_ENUM_AUTO && paired_supported(y.L, y.k))
+        return launch_enumerate_paired(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, shared_prefix,
+                                       skipped_groups, stream);
     if ((variant == PPO_ENUM_AUTO || variant == PPO_ENUM_GROUPED) && grouped_supported(y.L, y.k))
         return launch_enumerate_grouped(y, n_inst, ws, rank_begin, rank_end, best_key, beta_export, shared_prefix,
                                         skipped_groups, stream);

@@ -117,6 +117,11 @@ __device__ __forceinline__ void pair_store(uint32_t addr, uint32_t skip) {
 __device__ __forceinline__ void pair_row(uint32_t qaddr, const uint32_t* desc, uint32_t skip) {
     asm volatile(PPO_PAIR_ROW_ASM : : [qaddr] "v"(qaddr), [desc] "s"(desc), [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
 }
+__device__ __forceinline__ uint32_t pair_rowmin(uint32_t skip) {
+    uint32_t res;
+    asm volatile(PPO_PAIR_ROWMIN_ASM : [res] "=&v"(res) : [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
+    return res;
+}
 __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
     uint32_t res;
     asm volatile("s_waitcnt lgkmcnt(0)\n" PPO_PAIR_EXTRACT_ASM : [res] "=v"(res) : [skip] "s"(skip) : PPO_PAIR_CLOBBERS);
@@ -132,6 +137,7 @@ __device__ __forceinline__ uint32_t pair_extract(uint32_t skip) {
 struct PairSync {
     uint32_t team[kPairTeams];   // waves of the team that have reached their n-th meeting, summed over n
     uint32_t done;               // waves that are through with the row buffer, summed over the groups in turn
+    uint32_t bound[kPairTeams];  // bounded mode: bits of the best beta known when the team's group started
 };
 __device__ __forceinline__ void pair_spin_until(volatile uint32_t* counter, uint32_t target) {
     while (__hip_atomic_load(const_cast<uint32_t*>(counter), __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
@@ -142,11 +148,15 @@ __device__ __forceinline__ void pair_arrive(uint32_t* counter) {
 }
 
 // beta_export: null for the search; else beta of every ordering of the range is written out as well (one kernel
-// for both: a second instantiation would be a second copy of the generated code)
+// for both: a second instantiation would be a second copy of the generated code).
+// bounded: a group whose last prefix row (the same for all its orderings) has no entry at or below the best beta
+// known when the group starts cannot hold the optimum or a tie with it (no entry of a DP row is below the least
+// entry of the row before it) and is left after that row; every wave of the team takes the same decision from the
+// same row and from one published copy of the best beta.  Waves publish what they find after every group.
 __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     Layout y, const unsigned char* __restrict__ ws, uint32_t rank_begin, uint32_t rank_end, uint32_t prefix_begin,
     uint32_t prefix_end, uint32_t prefixes_per_block, unsigned long long* __restrict__ best_key,
-    float* __restrict__ beta_export) {
+    float* __restrict__ beta_export, int bounded, unsigned long long* __restrict__ skipped_groups) {
     extern __shared__ __align__(16) uint32_t lds[];
     const bool EXPORT = beta_export != nullptr;
     const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
@@ -250,6 +260,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
             const uint32_t* qsrc = qa + pair_index(a, b, k) * y.qa_cols;
             for (int col = lane; col < QROW; col += 64) qtab[row * QPITCH + col] = qsrc[col];
         }
+        if (bounded && wave == 0 && lane == 0)
+            sync->bound[team] = (uint32_t)(__hip_atomic_load(best_key + inst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
         team_meet();
 
         // The k rows in turn.  Rows 0 .. p0 stay in registers (the node of each is the same for all orderings of
@@ -257,6 +269,7 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
         // lanes hold now, and every row but the last is stored for the next one.  One copy of each block: the
         // generated code is large, and its labels are not unique on purpose (a second copy would not assemble).
         const uint32_t d0_addr = buf_addr + pair_d0_slot(p0 > 0 ? pnode(0) : rnode(wave)) * 8u;
+        bool left = false;
 #pragma unroll 1
         for (int s = 0; s < k; ++s) {
             const int r = s - p0;
@@ -287,6 +300,15 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 pair_row(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u, desc, skip);
                 if (s == k - 1) pair_arrive(&sync->done);   // the last row has been fetched: the buffer can go on
             }
+            if (bounded && s == p0 - 1) {
+                // the last row of the prefix: the same in every lane of every wave of the team
+                const uint32_t code = (uint32_t)__builtin_amdgcn_readfirstlane(pair_rowmin(skip)) & 0xFFFFu;
+                const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+                if (bits > (uint32_t)__builtin_amdgcn_readfirstlane((int)sync->bound[team])) {
+                    left = true;
+                    break;
+                }
+            }
             // the row goes to LDS where the next row has to fetch it from other lanes (rows of positions 0 .. 4)
             if (r >= 1 && s < k - 1) pair_store(slot_addr(r), skip_pairs);
             if (r == 0 && s < k - 1) {
@@ -295,6 +317,12 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 pair_store(slot_addr(0), skip_pairs);
             }
             if (r >= 0 && s < k - 1) team_meet();
+        }
+        if (left) {
+            // nothing of this group touches the row buffer: it counts as through with it at once
+            pair_arrive(&sync->done);
+            if (skipped_groups && wave == 0 && lane == 0) atomicAdd(skipped_groups + inst, 2ull);   // in units of 360 orderings
+            continue;
         }
         const uint32_t res = pair_extract(skip);   // D[L] of the lane's two orderings
         if (lc3 >> 31) {
@@ -310,6 +338,20 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                     const unsigned long long key = ((unsigned long long)code << 32) | r;
                     best = key < best ? key : best;
                 }
+            }
+        }
+        if (bounded) {
+            // what this wave has found so far, for the groups that start after this one
+            unsigned long long w = best;
+            for (int off = 32; off >= 1; off >>= 1) {
+                const unsigned long long o = __shfl_xor(w, off, 64);
+                w = o < w ? o : w;
+            }
+            if (lane == 0 && w != PPO_KEY_NONE) {
+                const uint32_t code = (uint32_t)(w >> 32);
+                const uint32_t bits = code >= kCodeInf ? kInfBits : __float_as_uint(dec[code - kCodeZero]);
+                const unsigned long long key = ((unsigned long long)bits << 32) | (w & 0xFFFFFFFFull);
+                if (key < __hip_atomic_load(best_key + inst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(best_key + inst, key);
             }
         }
     }
@@ -329,7 +371,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
 }
 
 hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, uint32_t rank_begin, uint32_t rank_end,
-                                   uint64_t* best_key, float* beta_export, hipStream_t stream) {
+                                   uint64_t* best_key, float* beta_export, bool bounded, uint64_t* skipped_groups,
+                                   hipStream_t stream) {
     if (rank_end <= rank_begin || n_inst == 0) return hipSuccess;
     const PairedShape ps = PairedShape::make(y.L, y.k);
     const uint32_t pbeg = rank_begin / 720u, pend = (rank_end + 719u) / 720u;
@@ -344,7 +387,8 @@ hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, 
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(enumerate_paired_kernel, grid, dim3(kPairThreads), ps.total_bytes, stream, y,
                        static_cast<const unsigned char*>(ws), rank_begin, rank_end, pbeg, pend, ppb,
-                       reinterpret_cast<unsigned long long*>(best_key), beta_export);
+                       reinterpret_cast<unsigned long long*>(best_key), beta_export, bounded && !beta_export ? 1 : 0,
+                       reinterpret_cast<unsigned long long*>(skipped_groups));
     return hipGetLastError();
 }
 

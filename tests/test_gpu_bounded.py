@@ -119,3 +119,19 @@ def test_bounded_row_lengths(ppo):
         got, keys, _ = solve_bounded(ppo, w)
         assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), f"bounded row lengths k={k} L={L}")
         assert np.array_equal(keys, solve_full_keys(ppo, w)), (k, L)
+
+
+def test_bounded_mode_of_the_grouped_kernel_behind_the_switch(ppo):
+    """ppo_solve_range_bounded runs the paired kernel where it applies; the grouped kernel's bounded mode stays
+    reachable through ppo_set_enumeration and must leave the same keys."""
+    w = W.random_instances(950, 16, 40, 8, capacity_factor=1.2, quantised=True)
+    ref_keys = solve_full_keys(ppo, w)
+    try:
+        ppo.ppo_set_enumeration(ppo.PPO_ENUM_GROUPED)
+        got, keys, skipped = solve_bounded(ppo, w)
+    finally:
+        ppo.ppo_set_enumeration(ppo.PPO_ENUM_AUTO)
+    assert np.array_equal(keys, ref_keys)
+    assert_same(got, O.subset_dp(w.t, w.m, w.M, w.B), "grouped kernel, bounded")
+    got2, keys2, skipped2 = solve_bounded(ppo, w)
+    assert np.array_equal(keys2, ref_keys)
