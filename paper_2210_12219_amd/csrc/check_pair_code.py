@@ -21,17 +21,22 @@ KERNEL = "enumerate_paired_kernel"
 
 
 def check_reserved_registers(asm_text, lay):
+    """every instantiation of the kernel; returns how many were found"""
     lo, hi = lay["rb"], lay["vtop"]   # entry 0 has a (dummy) register too
     inside_kernel = in_asm = False
-    seen_blocks = 0
+    kernels = seen_blocks = 0
     for n, line in enumerate(asm_text.splitlines(), 1):
         if re.match(rf"^_ZN3ppo\d+{KERNEL}\w*:", line):
             inside_kernel = True
+            kernels += 1
+            seen_blocks = 0
             continue
         if not inside_kernel:
             continue
         if line.startswith(".Lfunc_end"):
-            break
+            assert seen_blocks >= 5, "the kernel's blocks were not found in the assembly"
+            inside_kernel = False
+            continue
         if ";;#ASMSTART" in line:
             in_asm = True
             seen_blocks += 1
@@ -46,24 +51,29 @@ def check_reserved_registers(asm_text, lay):
             assert not lo <= int(m.group(1)) <= hi, f"line {n}: reserved register outside the blocks: {line.strip()}"
         for m in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
             assert int(m.group(2)) < lo or int(m.group(1)) > hi, f"line {n}: reserved registers outside the blocks: {line.strip()}"
-    assert inside_kernel and seen_blocks >= 5, "kernel or its blocks not found in the assembly"
+    assert kernels >= 1 and not inside_kernel, "kernel not found in the assembly"
+    return kernels
 
 
-def check_entry_offsets(disasm_text, lay):
-    # instructions of the kernel by address
-    instr, inside = {}, False
+def kernel_listings(disasm_text):
+    """instructions by address, one dict per instantiation of the kernel"""
+    out, instr = [], None
     for line in disasm_text.splitlines():
         if re.match(rf"^[0-9a-f]+ <_ZN3ppo\d+{KERNEL}\w*>:", line):
-            inside = True
+            instr = {}
+            out.append(instr)
             continue
-        if inside and re.match(r"^[0-9a-f]+ <", line):
-            if re.match(r"^[0-9a-f]+ <ppo_pair_\w+>:", line):
-                continue          # the blocks' own labels
-            break
-        if inside:
+        if instr is not None and re.match(r"^[0-9a-f]+ <", line):
+            instr = None
+            continue
+        if instr is not None:
             m = re.match(r"^\s*(\S.*?)\s*//\s*([0-9A-Fa-f]+):", line)
             if m:
                 instr[int(m.group(2), 16)] = re.sub(r"\s+", " ", m.group(1).strip())
+    return out
+
+
+def check_entry_offsets(instr, lay):
     sb = lay["sbase"]
     bases = [a for a, t in instr.items() if t == f"s_getpc_b64 s[{sb}:{sb + 1}]"]
     assert len(bases) == 1, f"expected one base instruction, found {len(bases)}"
@@ -121,11 +131,13 @@ def check_entry_offsets(disasm_text, lay):
 
 def main(asm_path, obj_path):
     lay = json.load(open(os.path.join(HERE, "ppo_pair_layout.json")))
-    check_reserved_registers(open(asm_path).read(), lay)
+    kernels = check_reserved_registers(open(asm_path).read(), lay)
     objdump = os.environ.get("LLVM_OBJDUMP", "/opt/rocm/llvm/bin/llvm-objdump")
     dis = subprocess.run([objdump, "-d", obj_path], check=True, capture_output=True, text=True).stdout
-    n = check_entry_offsets(dis, lay)
-    print(f"paired kernel: reserved registers untouched outside the blocks; {n} entry offsets verified")
+    listings = kernel_listings(dis)
+    assert len(listings) == kernels, f"{kernels} kernels in the assembly, {len(listings)} in the object"
+    n = sum(check_entry_offsets(instr, lay) for instr in listings)
+    print(f"paired kernel ({kernels} instantiations): reserved registers untouched outside the blocks; {n} entry offsets verified")
 
 
 if __name__ == "__main__":

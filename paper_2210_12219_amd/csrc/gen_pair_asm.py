@@ -241,7 +241,6 @@ def block_compute():
             emit([f"v_pk_min_u16 {R(x)}, {R(x - 1)}, {R(x)}"])
         emit(header(p - 1))
     offsets["end"] = pos
-    body.append("ppo_pair_end:")
     return lines + body, offsets
 
 
@@ -257,8 +256,8 @@ def block_extract():
     """%[skip] = UMAX - highest entry"""
     lines = entry_jump(8)
     for u in range(UMAX, 0, -1):
-        lines += [f"v_mov_b32_e32 %[res], {R(u)}", "s_branch ppo_pair_out"]
-    lines.append("ppo_pair_out:")
+        lines += [f"v_mov_b32_e32 %[res], {R(u)}", "s_branch 1f"]
+    lines.append("1:")
     return lines
 
 

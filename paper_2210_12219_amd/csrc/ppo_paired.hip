@@ -63,8 +63,10 @@ bool paired_supported(int L, int k) {
 }
 
 // spare slot that holds the first DP row of node j (both halves the same); the spare slots 30, 31, 62, 63 are the
-// idle lanes'
+// idle lanes'; eight more keep prefix rows in the bounded mode (team t, row 1 .. 4)
 __host__ __device__ inline uint32_t pair_d0_slot(int j) { return (uint32_t)(2 + j / 2) * 32u + 30u + (uint32_t)(j & 1); }
+__host__ __device__ inline uint32_t pair_kept_slot(int team, int row) { return (uint32_t)(7 + row) * 32u + 30u + (uint32_t)team; }
+static_assert(PPO_MAX_K - 6 - 2 <= 4, "one spare slot per team for each of the prefix rows 1 .. p0-2");
 // dword of entry u of a slot: entries 2h and 2h+1 side by side, the next pair of entries 2 * kPairSlots dwords on
 __host__ __device__ inline uint32_t pair_entry_dword(uint32_t slot, uint32_t u) { return (u >> 1) * (2u * kPairSlots) + slot * 2u + (u & 1u); }
 
@@ -153,10 +155,12 @@ __device__ __forceinline__ void pair_arrive(uint32_t* counter) {
 // known when the group starts cannot hold the optimum or a tie with it (no entry of a DP row is below the least
 // entry of the row before it) and is left after that row; every wave of the team takes the same decision from the
 // same row and from one published copy of the best beta.  Waves publish what they find after every group.
+// (A template parameter rather than an argument: the plain search must not carry the other mode's code in its loop.)
+template <bool bounded>
 __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     Layout y, const unsigned char* __restrict__ ws, uint32_t rank_begin, uint32_t rank_end, uint32_t prefix_begin,
     uint32_t prefix_end, uint32_t prefixes_per_block, unsigned long long* __restrict__ best_key,
-    float* __restrict__ beta_export, int bounded, unsigned long long* __restrict__ skipped_groups) {
+    float* __restrict__ beta_export, unsigned long long* __restrict__ skipped_groups) {
     extern __shared__ __align__(16) uint32_t lds[];
     const bool EXPORT = beta_export != nullptr;
     const int L = y.L, k = y.k, inst = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
@@ -200,6 +204,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
     }
     __syncthreads();   // the only hardware barrier: from here on the teams run on their own
     unsigned long long best = PPO_KEY_NONE;
+    uint64_t prev_prefix = 0;   // bounded mode: the prefix of the team's previous group
+    bool prev_valid = false;
     uint32_t meetings = 0;   // meetings of this wave's team so far
     auto team_meet = [&]() {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -266,15 +272,27 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
 
         // The k rows in turn.  Rows 0 .. p0 stay in registers (the node of each is the same for all orderings of
         // the wave whatever the lane holds); from the row of position 1 on, a row is loaded from the slots its
-        // lanes hold now, and every row but the last is stored for the next one.  One copy of each block: the
-        // generated code is large, and its labels are not unique on purpose (a second copy would not assemble).
+        // lanes hold now, and every row but the last is stored for the next one.  One copy of each block per
+        // kernel: the generated code is large.
         const uint32_t d0_addr = buf_addr + pair_d0_slot(p0 > 0 ? pnode(0) : rnode(wave)) * 8u;
+        // Bounded mode: the rows 1 .. p0-2 of the prefix (the same in every lane) are kept in spare slots of the
+        // row buffer, one per team and row, and the group starts from the deepest of them that its prefix shares
+        // with the team's previous group.
+        int s_first = 0;
+        if (bounded) {
+            const uint64_t diff = prefix ^ prev_prefix;
+            const int shared = !prev_valid ? 0 : diff ? (__ffsll((long long)diff) - 1) / 4 : p0;   // leading nodes in common
+            if (shared >= 2 && p0 >= 3) s_first = shared - 1 < p0 - 2 ? shared - 1 : p0 - 2;
+            prev_prefix = prefix;
+            prev_valid = true;
+        }
+        auto kept_addr = [&](int row) -> uint32_t { return buf_addr + pair_kept_slot(team, row) * 8u; };
         bool left = false;
 #pragma unroll 1
-        for (int s = 0; s < k; ++s) {
+        for (int s = s_first; s < k; ++s) {
             const int r = s - p0;
-            if (s == 0 || r >= 1) {
-                const uint32_t a = s == 0 ? d0_addr : slot_addr(r);
+            if (s == s_first || r >= 1) {
+                const uint32_t a = s == s_first ? (s == 0 ? d0_addr : kept_addr(s)) : slot_addr(r);
                 if (r == 4) {
                     pair_load_exchange(a, buf_addr + (lc2 & 511u) * 8u, skip_pairs);
                     team_meet();   // every upper half has been fetched before a slot is overwritten
@@ -282,7 +300,7 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                     pair_load(a, skip_pairs);
                 }
             }
-            if (s >= 1) {
+            if (s >= 1 && s != s_first) {
                 // the link between the nodes of rows s-1 and s, and the node of row s
                 uint32_t qrow;
                 int node;
@@ -300,6 +318,8 @@ __global__ __launch_bounds__(kPairThreads) void enumerate_paired_kernel(
                 pair_row(qtab_addr + qrow * (uint32_t)(QPITCH * 4) + (uint32_t)link_col(s) * 4u, desc, skip);
                 if (s == k - 1) pair_arrive(&sync->done);   // the last row has been fetched: the buffer can go on
             }
+            if (bounded && s >= 1 && s <= p0 - 2 && s != s_first && wave == 0 && lane == 0)
+                pair_store(kept_addr(s), skip_pairs);   // for the team's next groups (they meet before they read it)
             if (bounded && s == p0 - 1) {
                 // the last row of the prefix: the same in every lane of every wave of the team
                 const uint32_t code = (uint32_t)__builtin_amdgcn_readfirstlane(pair_rowmin(skip)) & 0xFFFFu;
@@ -382,13 +402,23 @@ hipError_t launch_enumerate_paired(const Layout& y, int n_inst, const void* ws, 
     uint32_t ppb = 16;
     while (ppb > 2 && (uint64_t)(count / ppb) * (uint64_t)n_inst < 4096u) ppb >>= 1;
     const dim3 grid((count + ppb - 1) / ppb, n_inst);
-    static std::atomic<uint64_t> lds_allowed{0};
-    const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_paired_kernel), lds_allowed);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(enumerate_paired_kernel, grid, dim3(kPairThreads), ps.total_bytes, stream, y,
-                       static_cast<const unsigned char*>(ws), rank_begin, rank_end, pbeg, pend, ppb,
-                       reinterpret_cast<unsigned long long*>(best_key), beta_export, bounded && !beta_export ? 1 : 0,
-                       reinterpret_cast<unsigned long long*>(skipped_groups));
+    if (bounded && !beta_export) {
+        static std::atomic<uint64_t> lds_allowed{0};
+        const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_paired_kernel<true>), lds_allowed);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(enumerate_paired_kernel<true>, grid, dim3(kPairThreads), ps.total_bytes, stream, y,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, pbeg, pend, ppb,
+                           reinterpret_cast<unsigned long long*>(best_key), beta_export,
+                           reinterpret_cast<unsigned long long*>(skipped_groups));
+    } else {
+        static std::atomic<uint64_t> lds_allowed{0};
+        const hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&enumerate_paired_kernel<false>), lds_allowed);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(enumerate_paired_kernel<false>, grid, dim3(kPairThreads), ps.total_bytes, stream, y,
+                           static_cast<const unsigned char*>(ws), rank_begin, rank_end, pbeg, pend, ppb,
+                           reinterpret_cast<unsigned long long*>(best_key), beta_export,
+                           reinterpret_cast<unsigned long long*>(skipped_groups));
+    }
     return hipGetLastError();
 }
 
