@@ -22,56 +22,76 @@ namespace ppo {
 
 PPO_HD inline int pair_slot16(int x) { return (x + kPairSlots16 - 1) % kPairSlots16; }
 
-// lo_row: lo[j][0 .. L] of the row's node (first legal segment start per segment end); entry: kPairSlots16 offsets
-PPO_HD inline void pair_row_program(int L, int k, int s, const unsigned char* lo_row, uint16_t* entry) {
+// window length of output u of row s; lo_row: lo[j][0 .. L] of the row's node (first legal segment start per end)
+PPO_HD inline int pair_window(int s, const unsigned char* lo_row, int u) {
+    const int e = u + s;
+    const int first = (int)lo_row[e] > s ? (int)lo_row[e] : s;
+    return e > first ? e - first : 0;
+}
+// the highest output of the run whose lowest output is u1 (window w1): outputs above it whose windows start where
+// its window starts
+PPO_HD inline int pair_run_top(int s, const unsigned char* lo_row, int top, int u1, int w1) {
+    int u2 = u1;
+    if (w1 > 0)
+        while (u2 < top) {
+            const int wn = pair_window(s, lo_row, u2 + 1);
+            if (wn == 0 || (u2 + 1) - wn != u1 - w1) break;
+            ++u2;
+        }
+    return u2;
+}
+
+// The entries that position u of row s is responsible for: none unless u is the lowest output of a run; else the
+// entry that leads to the run (the row's first jump for the top run, otherwise the one the run above leaves to
+// be read) and the entries read within the run.  Every entry has one writer, so the positions can be worked in
+// any order or side by side, on entries preset to the offset of the block's end.
+PPO_HD inline void pair_row_program_at(int L, int k, int s, const unsigned char* lo_row, int u, uint16_t* entry) {
     const int top = L - k + 1;   // highest output of a row
-    for (int i = 0; i < kPairSlots16; ++i) entry[i] = (uint16_t)kPairEnd;
-    auto window = [&](int u) -> int {
-        const int e = u + s;
-        const int first = (int)lo_row[e] > s ? (int)lo_row[e] : s;
-        return e > first ? e - first : 0;
-    };
-    if (top < 1) return;
+    if (u < 1 || u > top) return;
+    const int w = pair_window(s, lo_row, u);
     if (s == k - 1) {   // the last row: D[L] only
-        entry[pair_slot16(top)] = (uint16_t)pair_entry_offset((uint32_t)top, (uint32_t)window(top));
+        if (u == top) entry[pair_slot16(top)] = (uint16_t)pair_entry_offset((uint32_t)top, (uint32_t)w);
         return;
     }
-    int pending = pair_slot16(top);   // the entry that the code worked last will read
-    int u2 = top;
-    while (u2 >= 1) {
-        int u1 = u2;
-        const int w2 = window(u2);
-        if (w2 > 0) {
-            const int start = u2 - w2;   // one below the lowest entry of the window: the same for the whole run
-            while (u1 > 1) {
-                const int wb = window(u1 - 1);
-                if (wb == 0 || (u1 - 1) - wb != start) break;
-                --u1;
-            }
-        }
-        // A run of several outputs whose whole window fits one piece of run code is worked as one ascending pass
-        // from the window's second entry: every entry on the way becomes the minimum of the window's entries up
-        // to it.  That changes entries below the run, but only into minima of entries that any lower window
-        // holding them holds as well (windows never start later than those above them), so the outputs below
-        // come out the same; and it takes one jump where the chain and the run code take two.
-        const int first = u2 - w2 + 1;   // lowest entry of the run's windows
-        if (u2 > u1 && u2 - first <= kPairRunCap) {
-            entry[pending] = (uint16_t)pair_run_offset((uint32_t)(first + 1), (uint32_t)u2);
-            pending = pair_slot16(u2 - 1);
-            u2 = u1 - 1;
-            continue;
-        }
-        entry[pending] = (uint16_t)pair_entry_offset((uint32_t)u1, (uint32_t)window(u1));
-        pending = pair_slot16(u1 - 1);
-        for (int a = u1 + 1; a <= u2;) {
+    if (u > 1 && w > 0) {
+        const int wb = pair_window(s, lo_row, u - 1);
+        if (wb > 0 && (u - 1) - wb == u - w) return;   // the output below belongs to the same run
+    }
+    const int u2 = pair_run_top(s, lo_row, top, u, w);
+    int pending;   // the entry that the code worked before this run reads
+    if (u2 == top) {
+        pending = pair_slot16(top);
+    } else {
+        const int a1 = u2 + 1;
+        const int a2 = pair_run_top(s, lo_row, top, a1, pair_window(s, lo_row, a1));
+        pending = a2 > a1 ? pair_slot16(a2 - 1) : pair_slot16(a1 - 1);
+    }
+    // A run of several outputs whose whole window fits one piece of run code is worked as one ascending pass
+    // from the window's second entry: every entry on the way becomes the minimum of the window's entries up
+    // to it.  That changes entries below the run, but only into minima of entries that any lower window
+    // holding them holds as well (windows never start later than those above them), so the outputs below
+    // come out the same; and it takes one jump where the chain and the run code take two.
+    const int first = u - w + 1;   // lowest entry of the run's windows
+    if (u2 > u && u2 - first <= kPairRunCap) {
+        entry[pending] = (uint16_t)pair_run_offset((uint32_t)(first + 1), (uint32_t)u2);
+        pending = pair_slot16(u2 - 1);
+    } else {
+        entry[pending] = (uint16_t)pair_entry_offset((uint32_t)u, (uint32_t)w);
+        pending = pair_slot16(u - 1);
+        for (int a = u + 1; a <= u2;) {
             const int p = a + kPairRunCap - 1 < u2 ? a + kPairRunCap - 1 : u2;
             entry[pending] = (uint16_t)pair_run_offset((uint32_t)a, (uint32_t)p);
             pending = pair_slot16(p - 1);
             a = p + 1;
         }
-        u2 = u1 - 1;
     }
-    entry[pending] = (uint16_t)kPairEnd;
+    if (u == 1) entry[pending] = (uint16_t)kPairEnd;   // after the lowest run the block is left
+}
+
+// entry: kPairSlots16 offsets
+PPO_HD inline void pair_row_program(int L, int k, int s, const unsigned char* lo_row, uint16_t* entry) {
+    for (int i = 0; i < kPairSlots16; ++i) entry[i] = (uint16_t)kPairEnd;
+    for (int u = 1; u <= L - k + 1; ++u) pair_row_program_at(L, k, s, lo_row, u, entry);
 }
 
 }  // namespace ppo

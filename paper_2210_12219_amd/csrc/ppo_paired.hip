@@ -71,10 +71,10 @@ static_assert(PPO_MAX_K - 6 - 2 <= 4, "one spare slot per team for each of the p
 __host__ __device__ inline uint32_t pair_entry_dword(uint32_t slot, uint32_t u) { return (u >> 1) * (2u * kPairSlots) + slot * 2u + (u & 1u); }
 
 // ---------------------------------------------------------------------------------------------
-// The jump table of every (node, DP row s = 1 .. k-1): one thread each (ppo_pair_program.h).
+// The jump table of every (node, DP row s = 1 .. k-1), one thread per output position (ppo_pair_program.h).
 // ---------------------------------------------------------------------------------------------
 static_assert(kPairTableDwords * 2 == kPairSlots16, "two 16-bit entries per dword of the table");
-constexpr int kPairTableThreads = 256;
+constexpr int kPairTableThreads = 512;
 __global__ __launch_bounds__(kPairTableThreads) void pair_tables_kernel(Layout y, unsigned char* __restrict__ ws) {
     // the windows of all nodes, then the tables as they are built, 16 bits an entry
     __shared__ unsigned char lo_s[PPO_MAX_K * (PPO_MAX_L + 1)];
@@ -84,10 +84,15 @@ __global__ __launch_bounds__(kPairTableThreads) void pair_tables_kernel(Layout y
     const unsigned char* lo = base + y.lo_off;
     uint32_t* pt = reinterpret_cast<uint32_t*>(base + y.pt_off);
     for (int i = tid; i < k * (L + 1); i += kPairTableThreads) lo_s[i] = lo[i];
+    uint32_t* fill = reinterpret_cast<uint32_t*>(entry_s);
+    for (int i = tid; i < k * (k - 1) * kPairTableDwords; i += kPairTableThreads) fill[i] = kPairEnd | (kPairEnd << 16);
     __syncthreads();
-    for (int idx = tid; idx < k * (k - 1); idx += kPairTableThreads) {
-        const int j = idx / (k - 1), s = idx - j * (k - 1) + 1;
-        pair_row_program(L, k, s, lo_s + j * (L + 1), entry_s + idx * kPairSlots16);
+    // every output position of every (node, row) writes the entries it is responsible for: one writer per entry
+    const int top = L - k + 1;
+    for (int idx = tid; idx < k * (k - 1) * top; idx += kPairTableThreads) {
+        const int row = idx / top, u = idx - row * top + 1;
+        const int j = row / (k - 1), s = row - j * (k - 1) + 1;
+        pair_row_program_at(L, k, s, lo_s + j * (L + 1), u, entry_s + row * kPairSlots16);
     }
     __syncthreads();
     const uint32_t* src = reinterpret_cast<const uint32_t*>(entry_s);
