@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kPairTableThreads) void pair_tables_kernel(Layout y
 }
 
 hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream) {
-    if (y.k < 2) return hipSuccess;
+    if (!paired_supported(y.L, y.k)) return hipSuccess;   // nothing reads the tables then
     hipLaunchKernelGGL(pair_tables_kernel, dim3(n_inst), dim3(kPairTableThreads), 0, stream, y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }

@@ -154,10 +154,10 @@ def test_headline_in_both_launch_shapes(ppo):
     assert np.array_equal(k16 & np.uint64(0xFFFFFFFF), want_rank)
 
 
-def test_grouped_kernel_at_twelve_nodes(ppo):
-    """k = 12 with rows short enough for the grouped kernel (L - k + 2 <= 96): six prefix digits, five links
-    inside the prefix, three passes over the quotient rows.  Ragged rank ranges at both ends of [0, 12!)
-    through every route that takes a range, against the oracle on the same ranges."""
+def test_paired_and_grouped_kernels_at_twelve_nodes(ppo):
+    """k = 12 with rows short enough for the paired and the grouped kernel (L - k + 2 <= 96): six prefix digits,
+    five links inside the prefix, four kept prefix rows in the bounded mode.  Ragged rank ranges at both ends of
+    [0, 12!) through every route that takes a range, against the oracle on the same ranges, with each kernel."""
     import torch
     kf = math.factorial(12)
     for seed, L in ((1, 30), (2, 47), (3, 60)):
@@ -166,24 +166,29 @@ def test_grouped_kernel_at_twelve_nodes(ppo):
         ws = ppo.alloc_workspace(L, 12, 2)
         ppo.ppo_prepare(*dev, ws)
         for r0, r1 in ((0, 30011), (kf - 25013, kf), (kf // 2 - 977, kf // 2 + 20000)):
-            print(f"k=12 L={L} ranks [{r0}, {r1})", flush=True)
             ref = O.exhaustive(w.t, w.m, w.M, w.B, rank_range=(r0, r1))[:3]
-            for bounded in (False, True):
-                keys = torch.empty(2, dtype=torch.int64, device="cuda:0")
-                ppo.ppo_init_keys(keys)
-                if bounded:
-                    ppo.ppo_solve_range_bounded(L, 12, 2, ws, r0, r1, keys, None)
-                else:
-                    ppo.ppo_solve_range(L, 12, 2, ws, r0, r1, keys)
-                out = tuple(x.cpu().numpy() for x in ppo.ppo_finalize(L, 12, 2, ws, keys))
-                torch.cuda.synchronize()
-                assert_same(out, ref, f"k=12 L={L} [{r0},{r1}) bounded={bounded}")
-            for j in range(2):
-                a, b = r0, min(r1, r0 + 6000)
-                got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], a, b)
-                torch.cuda.synchronize()
-                per, _ = O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], a, b)
-                assert np.array_equal(bits(got.cpu().numpy()), bits(per)), (L, j, a)
+            per = [O.eval_orderings(w.t[j], w.m[j], w.M[j], w.B[j], r0, min(r1, r0 + 6000))[0] for j in range(2)]
+            for variant in (ppo.PPO_ENUM_AUTO, ppo.PPO_ENUM_GROUPED):
+                print(f"k=12 L={L} ranks [{r0}, {r1}) kernel {variant}", flush=True)
+                try:
+                    ppo.ppo_set_enumeration(variant)
+                    for bounded in (False, True):
+                        keys = torch.empty(2, dtype=torch.int64, device="cuda:0")
+                        ppo.ppo_init_keys(keys)
+                        if bounded:
+                            ppo.ppo_solve_range_bounded(L, 12, 2, ws, r0, r1, keys, None)
+                        else:
+                            ppo.ppo_solve_range(L, 12, 2, ws, r0, r1, keys)
+                        out = tuple(x.cpu().numpy() for x in ppo.ppo_finalize(L, 12, 2, ws, keys))
+                        torch.cuda.synchronize()
+                        assert_same(out, ref, f"k=12 L={L} [{r0},{r1}) bounded={bounded} kernel {variant}")
+                    for j in range(2):
+                        a, b = r0, min(r1, r0 + 6000)
+                        got = ppo.ppo_eval_orderings(dev[0][j], dev[1][j], dev[2][j], dev[3][j], a, b)
+                        torch.cuda.synchronize()
+                        assert np.array_equal(bits(got.cpu().numpy()), bits(per[j])), (L, j, a, variant)
+                finally:
+                    ppo.ppo_set_enumeration(ppo.PPO_ENUM_AUTO)
 
 
 def test_large_workload_full(ppo):
