@@ -324,24 +324,33 @@ def main():
             "namespace ppo {",
             f"constexpr int kPairRunCap = {ECAP};     // outputs one piece of run code takes",
             f"constexpr int kPairSlots16 = {NSLOT};   // 16-bit entries of a row's table; position u reads entry (u - 1) mod {NSLOT}",
-            "// Where output u of a row with a window of w entries (0 <= w <= u) starts: offset of that instruction from",
-            "// the base of the COMPUTE block, in units of four bytes.  Even w: the even chain of u, entered so that",
-            "// w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps (w = 1: the",
-            "// header that follows it); w = 0: the instruction that writes +inf.",
-            "PPO_HD inline uint32_t pair_entry_offset(uint32_t u, uint32_t w) {",
-            "    constexpr uint16_t even_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ev)) + "};",
-            "    constexpr uint16_t odd_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, od)) + "};",
-            "    constexpr uint16_t zero[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, ze)) + "};",
-            "    if (w == 0u) return zero[u];",
-            "    if (w & 1u) return odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
-            "    return even_base[u] + 2u * ((u - 2u) / 2u - (w - 2u) / 2u);",
+            "// Where the pieces of the COMPUTE block start, in units of four bytes from its base: per position u the",
+            "// chain for even windows, the chain for odd windows and the instruction that writes +inf; per end",
+            "// position p the run code.  One constant copy; a kernel that looks offsets up many times copies it to LDS.",
+            "struct PairOffsets {",
+            "    uint16_t even_base[PPO_PAIR_UMAX + 1], odd_base[PPO_PAIR_UMAX + 1], zero[PPO_PAIR_UMAX + 1], run_base[PPO_PAIR_UMAX + 1];",
+            "};",
+            "PPO_HD inline const PairOffsets& pair_offsets() {",
+            "    static constexpr PairOffsets t = {",
+            "        {" + ",".join(map(str, ev)) + "},",
+            "        {" + ",".join(map(str, od)) + "},",
+            "        {" + ",".join(map(str, ze)) + "},",
+            "        {" + ",".join(map(str, rn)) + "}};",
+            "    return t;",
+            "}",
+            "// Where output u of a row with a window of w entries (0 <= w <= u) starts.  Even w: the even chain of u,",
+            "// entered so that w / 2 - 1 steps precede its last instruction; odd w: the odd chain, (w - 1) / 2 steps",
+            "// (w = 1: the header that follows it); w = 0: the instruction that writes +inf.",
+            "PPO_HD inline uint32_t pair_entry_offset(const PairOffsets& t, uint32_t u, uint32_t w) {",
+            "    if (w == 0u) return t.zero[u];",
+            "    if (w & 1u) return t.odd_base[u] + 2u * ((u - 1u) / 2u - (w - 1u) / 2u);",
+            "    return t.even_base[u] + 2u * ((u - 2u) / 2u - (w - 2u) / 2u);",
             "}",
             "// Where the run code ending at position p is entered so that the positions a .. p are worked, each the",
             "// minimum of the output below it and its own entry (2 <= a <= p, p - a < kPairRunCap).",
-            "PPO_HD inline uint32_t pair_run_offset(uint32_t a, uint32_t p) {",
-            "    constexpr uint16_t run_base[PPO_PAIR_UMAX + 1] = {" + ",".join(map(str, rn)) + "};",
+            "PPO_HD inline uint32_t pair_run_offset(const PairOffsets& t, uint32_t a, uint32_t p) {",
             "    const uint32_t first = p + 1u > (uint32_t)kPairRunCap + 2u ? p + 1u - (uint32_t)kPairRunCap : 2u;",
-            "    return run_base[p] + 2u * (a - first);",
+            "    return t.run_base[p] + 2u * (a - first);",
             "}",
             f"constexpr uint32_t kPairEnd = {offsets['end'] // 4};   // the end of the block",
             "}  // namespace ppo", ""]

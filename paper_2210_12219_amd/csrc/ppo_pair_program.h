@@ -28,42 +28,43 @@ PPO_HD inline int pair_window(int s, const unsigned char* lo_row, int u) {
     const int first = (int)lo_row[e] > s ? (int)lo_row[e] : s;
     return e > first ? e - first : 0;
 }
-// the highest output of the run whose lowest output is u1 (window w1): outputs above it whose windows start where
-// its window starts
-PPO_HD inline int pair_run_top(int s, const unsigned char* lo_row, int top, int u1, int w1) {
+// What the program of a row is made from: below[u] = u - w(u), the position just below output u's window
+// (kPairNoWindow if the window is empty), for u = 1 .. top.  Outputs with equal `below` next to each other form a run.
+constexpr unsigned char kPairNoWindow = 0xFF;
+PPO_HD inline unsigned char pair_below(int s, const unsigned char* lo_row, int u) {
+    const int w = pair_window(s, lo_row, u);
+    return w > 0 ? (unsigned char)(u - w) : kPairNoWindow;
+}
+// the highest output of the run whose lowest output is u1
+PPO_HD inline int pair_run_top(const unsigned char* below, int top, int u1) {
     int u2 = u1;
-    if (w1 > 0)
-        while (u2 < top) {
-            const int wn = pair_window(s, lo_row, u2 + 1);
-            if (wn == 0 || (u2 + 1) - wn != u1 - w1) break;
-            ++u2;
-        }
+    const unsigned char b = below[u1];
+    if (b != kPairNoWindow)
+        while (u2 < top && below[u2 + 1] == b) ++u2;
     return u2;
 }
 
-// The entries that position u of row s is responsible for: none unless u is the lowest output of a run; else the
+// The entries that position u of a row is responsible for: none unless u is the lowest output of a run; else the
 // entry that leads to the run (the row's first jump for the top run, otherwise the one the run above leaves to
 // be read) and the entries read within the run.  Every entry has one writer, so the positions can be worked in
-// any order or side by side, on entries preset to the offset of the block's end.
-PPO_HD inline void pair_row_program_at(int L, int k, int s, const unsigned char* lo_row, int u, uint16_t* entry) {
-    const int top = L - k + 1;   // highest output of a row
+// any order or side by side, on entries preset to the offset of the block's end.  below: see pair_below,
+// indexed by position (index 0 unused); last_row: only the highest output is wanted (D[L]).
+PPO_HD inline void pair_row_program_at(const PairOffsets& t, int top, bool last_row, const unsigned char* below, int u,
+                                       uint16_t* entry) {
     if (u < 1 || u > top) return;
-    const int w = pair_window(s, lo_row, u);
-    if (s == k - 1) {   // the last row: D[L] only
-        if (u == top) entry[pair_slot16(top)] = (uint16_t)pair_entry_offset((uint32_t)top, (uint32_t)w);
+    const int w = below[u] == kPairNoWindow ? 0 : u - (int)below[u];
+    if (last_row) {
+        if (u == top) entry[pair_slot16(top)] = (uint16_t)pair_entry_offset(t, (uint32_t)top, (uint32_t)w);
         return;
     }
-    if (u > 1 && w > 0) {
-        const int wb = pair_window(s, lo_row, u - 1);
-        if (wb > 0 && (u - 1) - wb == u - w) return;   // the output below belongs to the same run
-    }
-    const int u2 = pair_run_top(s, lo_row, top, u, w);
+    if (u > 1 && w > 0 && below[u - 1] == below[u]) return;   // the output below belongs to the same run
+    const int u2 = pair_run_top(below, top, u);
     int pending;   // the entry that the code worked before this run reads
     if (u2 == top) {
         pending = pair_slot16(top);
     } else {
         const int a1 = u2 + 1;
-        const int a2 = pair_run_top(s, lo_row, top, a1, pair_window(s, lo_row, a1));
+        const int a2 = pair_run_top(below, top, a1);
         pending = a2 > a1 ? pair_slot16(a2 - 1) : pair_slot16(a1 - 1);
     }
     // A run of several outputs whose whole window fits one piece of run code is worked as one ascending pass
@@ -73,14 +74,14 @@ PPO_HD inline void pair_row_program_at(int L, int k, int s, const unsigned char*
     // come out the same; and it takes one jump where the chain and the run code take two.
     const int first = u - w + 1;   // lowest entry of the run's windows
     if (u2 > u && u2 - first <= kPairRunCap) {
-        entry[pending] = (uint16_t)pair_run_offset((uint32_t)(first + 1), (uint32_t)u2);
+        entry[pending] = (uint16_t)pair_run_offset(t, (uint32_t)(first + 1), (uint32_t)u2);
         pending = pair_slot16(u2 - 1);
     } else {
-        entry[pending] = (uint16_t)pair_entry_offset((uint32_t)u, (uint32_t)w);
+        entry[pending] = (uint16_t)pair_entry_offset(t, (uint32_t)u, (uint32_t)w);
         pending = pair_slot16(u - 1);
         for (int a = u + 1; a <= u2;) {
             const int p = a + kPairRunCap - 1 < u2 ? a + kPairRunCap - 1 : u2;
-            entry[pending] = (uint16_t)pair_run_offset((uint32_t)a, (uint32_t)p);
+            entry[pending] = (uint16_t)pair_run_offset(t, (uint32_t)a, (uint32_t)p);
             pending = pair_slot16(p - 1);
             a = p + 1;
         }
@@ -90,8 +91,11 @@ PPO_HD inline void pair_row_program_at(int L, int k, int s, const unsigned char*
 
 // entry: kPairSlots16 offsets
 PPO_HD inline void pair_row_program(int L, int k, int s, const unsigned char* lo_row, uint16_t* entry) {
+    const int top = L - k + 1;   // highest output of a row
+    unsigned char below[PPO_PAIR_UMAX + 2];
+    for (int u = 1; u <= top && u <= PPO_PAIR_UMAX; ++u) below[u] = pair_below(s, lo_row, u);
     for (int i = 0; i < kPairSlots16; ++i) entry[i] = (uint16_t)kPairEnd;
-    for (int u = 1; u <= L - k + 1; ++u) pair_row_program_at(L, k, s, lo_row, u, entry);
+    for (int u = 1; u <= top; ++u) pair_row_program_at(pair_offsets(), top, s == k - 1, below, u, entry);
 }
 
 }  // namespace ppo

@@ -71,37 +71,48 @@ static_assert(PPO_MAX_K - 6 - 2 <= 4, "one spare slot per team for each of the p
 __host__ __device__ inline uint32_t pair_entry_dword(uint32_t slot, uint32_t u) { return (u >> 1) * (2u * kPairSlots) + slot * 2u + (u & 1u); }
 
 // ---------------------------------------------------------------------------------------------
-// The jump table of every (node, DP row s = 1 .. k-1), one thread per output position (ppo_pair_program.h).
+// The jump tables of one node's DP rows s = 1 .. k-1, one thread per output position (ppo_pair_program.h).
 // ---------------------------------------------------------------------------------------------
 static_assert(kPairTableDwords * 2 == kPairSlots16, "two 16-bit entries per dword of the table");
-constexpr int kPairTableThreads = 512;
+constexpr int kPairTableThreads = 256;
+// one workgroup per (node, instance): the rows s = 1 .. k-1 of that node
 __global__ __launch_bounds__(kPairTableThreads) void pair_tables_kernel(Layout y, unsigned char* __restrict__ ws) {
-    // the windows of all nodes, then the tables as they are built, 16 bits an entry
-    __shared__ unsigned char lo_s[PPO_MAX_K * (PPO_MAX_L + 1)];
-    __shared__ __align__(4) uint16_t entry_s[PPO_MAX_K * (PPO_MAX_K - 1) * kPairSlots16];
-    const int L = y.L, k = y.k, inst = blockIdx.x, tid = threadIdx.x;
+    __shared__ unsigned char lo_s[PPO_MAX_L + 1];
+    __shared__ __align__(4) uint16_t entry_s[(PPO_MAX_K - 1) * kPairSlots16];
+    __shared__ __align__(4) PairOffsets off_s;   // a copy close by: every position looks a few offsets up
+    __shared__ unsigned char below_s[(PPO_MAX_K - 1) * kPairSlots16];   // see pair_below
+    const int L = y.L, k = y.k, j = blockIdx.x, inst = blockIdx.y, tid = threadIdx.x;
     unsigned char* base = ws + (size_t)inst * y.stride;
-    const unsigned char* lo = base + y.lo_off;
-    uint32_t* pt = reinterpret_cast<uint32_t*>(base + y.pt_off);
-    for (int i = tid; i < k * (L + 1); i += kPairTableThreads) lo_s[i] = lo[i];
+    const unsigned char* lo = base + y.lo_off + (size_t)j * (L + 1);
+    uint32_t* pt = reinterpret_cast<uint32_t*>(base + y.pt_off) + (size_t)j * (k - 1) * kPairTableDwords;
+    for (int i = tid; i <= L; i += kPairTableThreads) lo_s[i] = lo[i];
+    {
+        const uint16_t* src = reinterpret_cast<const uint16_t*>(&pair_offsets());
+        uint16_t* dst = reinterpret_cast<uint16_t*>(&off_s);
+        for (int i = tid; i < (int)(sizeof(PairOffsets) / 2); i += kPairTableThreads) dst[i] = src[i];
+    }
     uint32_t* fill = reinterpret_cast<uint32_t*>(entry_s);
-    for (int i = tid; i < k * (k - 1) * kPairTableDwords; i += kPairTableThreads) fill[i] = kPairEnd | (kPairEnd << 16);
+    for (int i = tid; i < (k - 1) * kPairTableDwords; i += kPairTableThreads) fill[i] = kPairEnd | (kPairEnd << 16);
     __syncthreads();
-    // every output position of every (node, row) writes the entries it is responsible for: one writer per entry
     const int top = L - k + 1;
-    for (int idx = tid; idx < k * (k - 1) * top; idx += kPairTableThreads) {
+    for (int idx = tid; idx < (k - 1) * top; idx += kPairTableThreads) {
         const int row = idx / top, u = idx - row * top + 1;
-        const int j = row / (k - 1), s = row - j * (k - 1) + 1;
-        pair_row_program_at(L, k, s, lo_s + j * (L + 1), u, entry_s + row * kPairSlots16);
+        below_s[row * kPairSlots16 + u] = pair_below(row + 1, lo_s, u);
+    }
+    __syncthreads();
+    // every output position of every row writes the entries it is responsible for: one writer per entry
+    for (int idx = tid; idx < (k - 1) * top; idx += kPairTableThreads) {
+        const int row = idx / top, u = idx - row * top + 1;
+        pair_row_program_at(off_s, top, row + 1 == k - 1, below_s + row * kPairSlots16, u, entry_s + row * kPairSlots16);
     }
     __syncthreads();
     const uint32_t* src = reinterpret_cast<const uint32_t*>(entry_s);
-    for (int i = tid; i < k * (k - 1) * kPairTableDwords; i += kPairTableThreads) pt[i] = src[i];
+    for (int i = tid; i < (k - 1) * kPairTableDwords; i += kPairTableThreads) pt[i] = src[i];
 }
 
 hipError_t launch_pair_tables(const Layout& y, int n_inst, void* ws, hipStream_t stream) {
     if (!paired_supported(y.L, y.k)) return hipSuccess;   // nothing reads the tables then
-    hipLaunchKernelGGL(pair_tables_kernel, dim3(n_inst), dim3(kPairTableThreads), 0, stream, y, static_cast<unsigned char*>(ws));
+    hipLaunchKernelGGL(pair_tables_kernel, dim3(y.k, n_inst), dim3(kPairTableThreads), 0, stream, y, static_cast<unsigned char*>(ws));
     return hipGetLastError();
 }
 
