@@ -113,7 +113,7 @@ static bool bad_keys(const void* keys) { return !keys || misaligned(keys, 8); }
 
 extern "C" {
 
-int ppo_version(void) { return 203; }
+int ppo_version(void) { return 204; }
 
 int ppo_set_enumeration(int variant) {
     if (variant != PPO_ENUM_AUTO && variant != PPO_ENUM_GENERIC && variant != PPO_ENUM_GROUPED) return PPO_EINVAL;
