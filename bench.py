@@ -52,6 +52,34 @@ def algorithmic_ops_per_ordering(w):
     return cand, maxops
 
 
+def run_sharing(w):
+    """How much of that work the paired kernel's run sharing leaves: outputs of a DP row whose windows start at the
+    same entry are prefix minima of one another, so a run of r outputs whose lowest window has w entries costs
+    ceil((w - 1) / 2) three-input minima and r - 1 two-input ones instead of one chain per output.  Returns (outputs
+    per run, vector instructions per output with one chain per output, with run sharing), means over rows 1..k-2,
+    all nodes and up to 16 instances."""
+    L, k = w.L, w.k
+    outputs = runs = per_output = shared = 0
+    for n in range(min(w.n_inst, 16)):
+        P = np.concatenate([[0.0], np.cumsum(w.m[n].astype(np.float64))])
+        for j in range(k):
+            cap = float(w.M[n, j])
+            lo = np.array([int(np.argmax(P[e] - P[: e + 1] <= cap)) for e in range(L + 1)])
+            for s in range(1, k - 1):
+                e = np.arange(s + 1, L - (k - 1 - s) + 1)
+                start = np.maximum(lo[e], s)
+                width = np.maximum(e - start, 0)
+                base = np.ones(len(e), dtype=bool)          # lowest output of its run
+                base[1:] = (start[1:] != start[:-1]) | (width[1:] == 0) | (width[:-1] == 0)
+                outputs += len(e)
+                runs += int(base.sum())
+                per_output += int((width // 2).sum())       # ceil((w - 1) / 2) per output
+                shared += int((width[base] // 2).sum()) + int((~base).sum())
+    if outputs == 0:
+        return None
+    return outputs / runs, per_output / outputs, shared / outputs
+
+
 def profiled(name, version):
     """Figures that only a profiler run can give (HBM traffic, share of the vector issue slots), read from the
     summary under profiles/ that `python -m paper_2210_12219_amd.profile_summary` wrote from rocprofv3 output, and
@@ -378,6 +406,8 @@ def main():
                      "valu_issue": prof.get("valu_issue"),
                      "traffic": prof.get("traffic_bytes_per_launch"),
                      "min_ops_per_ordering": cand, "max_ops_per_ordering": maxops,
+                     "run_sharing": dict(zip(("outputs_per_run", "vector_instructions_per_output_unshared",
+                                              "vector_instructions_per_output"), run_sharing(w) or (None,) * 3)),
                      "kernel_ms": enum_ms},
     }
 
