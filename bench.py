@@ -123,6 +123,33 @@ def bench_partition(args, torch, ppo, workloads):
         "roofline": None}), flush=True)
 
 
+def bench_ct(args, torch, ppo, workloads):
+    """Not the headline: the search with the compute-time term of the paper's Eq. 1 (ppo_solve_ct), whole solves."""
+    w = getattr(workloads, args.workload)() if args.workload != "headline" else workloads.resnet50_shaped()
+    work, speed = workloads.compute_terms(w, seconds=10.0)
+    t, m, M, B = ppo.to_device(w)
+    wd, vd = torch.from_numpy(work).cuda(), torch.from_numpy(speed).cuda()
+    out = None
+    for _ in range(args.warmup):
+        out = ppo.ppo_solve_ct(t, m, wd, M, vd, B, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = ppo.ppo_solve_ct(t, m, wd, M, vd, B, out=out)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kf = math.factorial(w.k)
+    print(json.dumps({
+        "metric": f"node orderings evaluated/sec with the compute-time term at k={w.k},L={w.L}",
+        "value": w.n_inst * kf / (wall / args.steps), "unit": "orderings/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_inst} instances x (L={w.L}, k={w.k}), {kf} orderings each, "
+                               "work per layer log-uniform over a factor of 30, node speeds 1x/2x/4x, 10 s for the model",
+                   "orderings_per_step": w.n_inst * kf},
+        "roofline": None}), flush=True)
+
+
 def bench_approx(args, torch, ppo, workloads):
     """Not the headline: the experiment of the paper's Sec. V with the true optimum in place of Theorem 1's bound:
     bottleneck latency of the paper's placement algorithm (and of its greedy comparison system) over the exact
@@ -303,6 +330,9 @@ def main():
     ap.add_argument("--partition", action="store_true",
                     help="time ppo_min_sum_partition (the paper's own partitioning step) on 4096 chains of L=96: "
                          "a separate figure in instances per second")
+    ap.add_argument("--ct", action="store_true",
+                    help="time ppo_solve_ct (the search with the compute-time term of Eq. 1) on --workload "
+                         "(default resnet50_shaped): a separate figure")
     ap.add_argument("--approx", action="store_true",
                     help="the paper's placement algorithm against the exact optimum on paper-shaped clusters "
                          "(ppo_place_kpath / ppo_place_baseline / ppo_solve_cluster): mean ratio of bottleneck latencies")
@@ -331,6 +361,8 @@ def main():
         return bench_cluster(args, torch, ppo, workloads)
     if args.partition:
         return bench_partition(args, torch, ppo, workloads)
+    if args.ct:
+        return bench_ct(args, torch, ppo, workloads)
     if args.approx:
         return bench_approx(args, torch, ppo, workloads)
     if args.valu_probe:
