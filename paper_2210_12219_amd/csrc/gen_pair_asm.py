@@ -28,7 +28,7 @@ one of the position below the code it follows; the precompute kernel (ppo_pair_p
 so that the jumps walk the runs in this order and leave the block at the end.
 
 Blocks (each one `asm volatile` statement in the kernel; fixed registers, declared clobbered there):
-  LOAD     entries NE-1..1 from the lane's slot in LDS (one dword per entry, 1536 bytes apart)
+  LOAD     entries NE-1..1 from the lane's slot in LDS (two entries per 64-bit read, the next two ROW_BYTES on)
   LOADX    the same, then the upper half of every entry replaced by that of another slot (the pairing changes)
   ROW      entry u = max(entry u, code of t[u+s-2]/B of the lane's link), both halves the same link; then the
            chains and the run steps (one block: the row's jump table is requested while the maxima are taken)
@@ -44,10 +44,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 UMAX = 95            # highest entry index a row can have (L - k + 2 <= 96)
 RB = 40              # entry u lives in v[RB + u]
-VQ = RB + UMAX + 1   # 24 registers for the quotient dwords of QMAX
-VACC = VQ + 24
+VQ = RB + UMAX + 1   # 24 registers for the quotient dwords of the link maxima
+VACC = VQ + 24       # (free)
 VINF = VACC + 1
-VA1 = VINF + 1       # slot address + 43 rows, + 86 rows
+VA1 = VINF + 1       # slot address + 21 pairs of entries, + 42 pairs
 VA2 = VA1 + 1
 VB1 = VA2 + 1        # the same for the second slot of LOADX
 VB2 = VB1 + 1

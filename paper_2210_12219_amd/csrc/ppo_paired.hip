@@ -1,7 +1,7 @@
 // Paired enumeration kernel for k >= 6: two orderings per lane, the DP row in registers.
 //
-// One workgroup of six waves evaluates the 720 orderings that share a prefix of k-6 nodes.  Every ordering runs
-// all of its k DP rows (the unit the headline figure counts).  Wave c holds, at every row, the orderings that
+// A team of six waves evaluates the 720 orderings that share a prefix of k-6 nodes (a workgroup is two teams, each
+// on a group of its own).  Every ordering runs all of its k DP rows (the unit the headline figure counts).  Wave c holds, at every row, the orderings that
 // put the c-th of the six remaining nodes at that row: the memory window [lo[node][e], e-1] is then the same for
 // the whole wave, and since a lane's two orderings (one per 16-bit half of its registers) are chosen to share
 // that node as well, every instruction works on both halves alike: one packed three-input minimum folds two
@@ -18,8 +18,8 @@
 // table written by pair_tables_kernel below (ppo_pair_program.h).
 //
 // Which orderings a lane holds changes from row to row (the node at the row must be the wave's), so between
-// rows the entries go through LDS: slot = pair, one dword per entry, entry-major, the bank of a slot being its
-// coset class (ppo_pair_tables.h), conflict free by construction.  The rows of the shared prefix and the first
+// rows the entries go through LDS: slot = pair, entries 2h and 2h+1 side by side (64 bits), the next two a fixed
+// distance on, the bank of a slot being its coset class (ppo_pair_tables.h), conflict free by construction.  The rows of the shared prefix and the first
 // row after it need no exchange: all orderings of a lane set keep their node there.  The pairing changes once,
 // before the row of position 4 of the six: only upper halves move (see gen_pair_tables.py).
 #include "ppo_common.h"
